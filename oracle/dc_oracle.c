@@ -1,0 +1,497 @@
+/*
+ * CPU oracle for the chunked Huffman codec of INT8 LLM weights.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP library is checked against.  It shares no code, header, table or helper
+ * with the library, and only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may build or call it.
+ *
+ * What the paper fixes (Section 3.1, Section 3.3 "Speed Adaptive Partial
+ * Compression"): quantised INT8 weights are compressed losslessly, in
+ * independently coded data chunks, and only some chunks of every data block are
+ * compressed while the others stay raw.  The paper picks an entropy coder
+ * (Section 4.2) but describes no bitstream.  The bitstream here is this
+ * project's own: a per-chunk canonical Huffman code over the 256 byte values,
+ * code length at most 11, each chunk split into S symbol-interleaved
+ * sub-bitstreams.  The format, restated:
+ *
+ *   chunk table entry (16 bytes, little endian)
+ *     u64 off          payload offset in the blob, multiple of 16
+ *     u32 comp_bytes   payload size including padding, multiple of 16
+ *     u32 raw_bytes | RAW<<31
+ *   raw payload       raw_bytes bytes, zero padded to 16
+ *   Huffman payload
+ *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
+ *                      (0 = value absent, else 1..11)
+ *     [128,128+4S)     u32 off[j]: start of sub-stream j from payload start,
+ *                      multiple of 4
+ *     sub-streams      stream j = codes of the bytes of the 16-byte groups
+ *                      g = j, j+S, j+2S, ... of the chunk, in increasing
+ *                      position; a stream is padded with zero bits to a whole
+ *                      number of 32-bit words; payload zero padded to 16
+ *   bit order          stream bit i is bit (i mod 8) of stream byte i/8; a code
+ *                      is written most significant code bit first
+ *   codes              canonical: lengths by package-merge (below), codes
+ *                      numbered in order of (length, byte value)
+ *
+ * Every function is written for a reader to check by eye, not for speed:
+ * one bit at a time, explicit item lists, no tables.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_E_ARG (-1)
+#define ORC_E_CAP (-2)
+#define ORC_E_FORMAT (-3)
+
+#define ORC_RAW_FLAG 0x80000000u
+
+enum { ORC_ALL_HUFF = 0, ORC_AUTO = 1, ORC_RAW_FRACTION = 2, ORC_RAW_MASK = 3, ORC_BLOCK_LAST = 4 };
+
+typedef struct {
+    uint64_t off;
+    uint32_t comp_bytes;
+    uint32_t raw_bytes_flags;
+} orc_chunk;
+
+/* ---------------------------------------------------------------- histogram */
+
+/* Counts of each byte value (the int8 weight seen as its two's-complement byte). */
+void orc_histogram(const uint8_t *src, uint64_t n, uint64_t *cnt)
+{
+    memset(cnt, 0, 256 * sizeof(uint64_t));
+    for (uint64_t i = 0; i < n; i++)
+        cnt[src[i]]++;
+}
+
+/* ------------------------------------------------- length-limited code lengths */
+
+/*
+ * Package-merge (Larmore & Hirschberg's coin-collector view), written with
+ * explicit items.  An item is a weight plus, for every leaf, how many times the
+ * leaf is inside it.  Level 1 is the sorted leaves.  Level j is the sorted
+ * leaves merged with the packages made of consecutive pairs of level j-1.  The
+ * first 2n-2 items of level max_len are bought; a leaf's code length is the
+ * number of bought items that contain it, counted with multiplicity.
+ *
+ * Determinism: leaves are ordered by (count ascending, byte value ascending);
+ * when a leaf and a package weigh the same the leaf goes first; packages keep
+ * the order they were made in.
+ *
+ * Values with count 0 get length 0.  A single distinct value gets length 1.
+ */
+typedef struct {
+    uint64_t w;
+    uint16_t mult[256]; /* indexed by leaf rank */
+} pm_item;
+
+int orc_code_lengths(const uint64_t *cnt, int max_len, uint8_t *len)
+{
+    int leaf_sym[256];
+    int n = 0;
+    memset(len, 0, 256);
+    if (max_len < 1 || max_len > 15)
+        return ORC_E_ARG;
+    for (int v = 0; v < 256; v++)
+        if (cnt[v] > 0)
+            leaf_sym[n++] = v;
+    if (n == 0)
+        return ORC_E_ARG;
+    if (n == 1) {
+        len[leaf_sym[0]] = 1;
+        return ORC_OK;
+    }
+    if ((n - 1) >> max_len)
+        return ORC_E_ARG; /* more than 2^max_len values cannot be coded */
+
+    /* insertion sort of the leaves by (count, byte value) */
+    for (int i = 1; i < n; i++) {
+        int s = leaf_sym[i], j = i;
+        while (j > 0 && (cnt[leaf_sym[j - 1]] > cnt[s])) {
+            leaf_sym[j] = leaf_sym[j - 1];
+            j--;
+        }
+        leaf_sym[j] = s;
+    }
+
+    pm_item *prev = calloc(2 * (size_t)n, sizeof(pm_item));
+    pm_item *cur = calloc(2 * (size_t)n, sizeof(pm_item));
+    pm_item *pk = calloc((size_t)n, sizeof(pm_item));
+    if (!prev || !cur || !pk) {
+        free(prev); free(cur); free(pk);
+        return ORC_E_CAP;
+    }
+    int n_prev = n;
+    for (int i = 0; i < n; i++) {
+        prev[i].w = cnt[leaf_sym[i]];
+        prev[i].mult[i] = 1;
+    }
+    for (int level = 2; level <= max_len; level++) {
+        int n_pk = n_prev / 2;
+        for (int i = 0; i < n_pk; i++) {
+            pk[i].w = prev[2 * i].w + prev[2 * i + 1].w;
+            for (int r = 0; r < n; r++)
+                pk[i].mult[r] = (uint16_t)(prev[2 * i].mult[r] + prev[2 * i + 1].mult[r]);
+        }
+        int a = 0, b = 0, m = 0;
+        while (a < n || b < n_pk) {
+            int take_leaf;
+            if (a >= n) take_leaf = 0;
+            else if (b >= n_pk) take_leaf = 1;
+            else take_leaf = (cnt[leaf_sym[a]] <= pk[b].w);
+            if (take_leaf) {
+                memset(&cur[m], 0, sizeof(pm_item));
+                cur[m].w = cnt[leaf_sym[a]];
+                cur[m].mult[a] = 1;
+                a++;
+            } else {
+                cur[m] = pk[b];
+                b++;
+            }
+            m++;
+        }
+        pm_item *t = prev; prev = cur; cur = t;
+        n_prev = m;
+    }
+    int buy = 2 * n - 2;
+    int rc = ORC_OK;
+    if (n_prev < buy) {
+        rc = ORC_E_ARG;
+    } else {
+        for (int r = 0; r < n; r++) {
+            unsigned l = 0;
+            for (int i = 0; i < buy; i++)
+                l += prev[i].mult[r];
+            len[leaf_sym[r]] = (uint8_t)l;
+        }
+    }
+    free(prev); free(cur); free(pk);
+    return rc;
+}
+
+/* --------------------------------------------------------------- canonical codes */
+
+/*
+ * Codes are numbered in order of (length, byte value): the first code of the
+ * shortest length is 0, and going to the next code adds one and, when the
+ * length grows by d, appends d zero bits.
+ */
+void orc_canonical_codes(const uint8_t *len, uint16_t *code)
+{
+    unsigned next = 0;
+    int prev_len = 0;
+    memset(code, 0, 256 * sizeof(uint16_t));
+    for (int l = 1; l <= 15; l++) {
+        for (int v = 0; v < 256; v++) {
+            if (len[v] != l)
+                continue;
+            if (prev_len != 0)
+                next = (next + 1) << (l - prev_len);
+            code[v] = (uint16_t)next;
+            prev_len = l;
+        }
+    }
+}
+
+/* ------------------------------------------------------------ sub-stream geometry */
+
+/* Number of symbols of sub-stream j of a chunk of raw_bytes bytes split S ways. */
+uint32_t orc_stream_symbols(uint32_t raw_bytes, uint32_t S, uint32_t j)
+{
+    uint32_t n = 0;
+    uint32_t groups = (raw_bytes + 15) / 16;
+    for (uint32_t g = j; g < groups; g += S) {
+        uint32_t lo = 16 * g;
+        uint32_t hi = lo + 16 < raw_bytes ? lo + 16 : raw_bytes;
+        n += hi - lo;
+    }
+    return n;
+}
+
+static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+/* Upper bound of a Huffman payload: header + 11 bits a symbol + stream padding + tail. */
+uint64_t orc_huff_bound(uint32_t raw_bytes, uint32_t S)
+{
+    return round_up(128 + 4 * (uint64_t)S + ((uint64_t)raw_bytes * 11 + 7) / 8 + 4 * (uint64_t)S, 16);
+}
+
+/* ------------------------------------------------------------------ chunk encode */
+
+/*
+ * Encode one chunk as a Huffman payload.  Returns the payload size (multiple of
+ * 16) or 0 on error (capacity too small, bad arguments).  out may be NULL to
+ * only measure.  max_len is 11 in the format; tests may pass less.
+ */
+uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, int max_len,
+                          uint8_t *out, uint64_t cap)
+{
+    uint64_t cnt[256];
+    uint8_t len[256];
+    uint16_t code[256];
+    if (raw_bytes == 0 || S == 0 || max_len > 11)
+        return 0;
+    orc_histogram(src, raw_bytes, cnt);
+    if (orc_code_lengths(cnt, max_len, len) != ORC_OK)
+        return 0;
+    orc_canonical_codes(len, code);
+
+    /* size: header, then each stream rounded up to whole 32-bit words */
+    uint64_t pos = 128 + 4 * (uint64_t)S;
+    uint32_t groups = (raw_bytes + 15) / 16;
+    for (uint32_t j = 0; j < S; j++) {
+        uint64_t bits = 0;
+        for (uint32_t g = j; g < groups; g += S)
+            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
+                bits += len[src[p]];
+        pos += (bits + 31) / 32 * 4;
+    }
+    uint64_t total = round_up(pos, 16);
+    if (!out)
+        return total;
+    if (cap < total)
+        return 0;
+    memset(out, 0, total);
+
+    for (int v = 0; v < 256; v++)
+        out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
+
+    pos = 128 + 4 * (uint64_t)S;
+    for (uint32_t j = 0; j < S; j++) {
+        uint32_t off32 = (uint32_t)pos;
+        memcpy(out + 128 + 4 * (uint64_t)j, &off32, 4); /* little-endian host */
+        uint64_t bit = 0;
+        uint8_t *st = out + pos;
+        for (uint32_t g = j; g < groups; g += S) {
+            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
+                int l = len[src[p]];
+                unsigned c = code[src[p]];
+                for (int k = l - 1; k >= 0; k--) { /* most significant code bit first */
+                    if ((c >> k) & 1)
+                        st[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+                    bit++;
+                }
+            }
+        }
+        pos += (bit + 31) / 32 * 4;
+    }
+    return total;
+}
+
+/* ------------------------------------------------------------------ chunk decode */
+
+/*
+ * Decode one Huffman payload bit by bit: grow the code one bit at a time and
+ * stop when it falls inside the range of codes of its length.  Symbol counts
+ * come from raw_bytes, never from the stream.
+ */
+int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_bytes, uint32_t S,
+                     uint8_t *dst)
+{
+    uint8_t len[256];
+    unsigned count[16] = {0}, first[16] = {0}, base[16] = {0};
+    uint8_t sorted[256];
+    if (S == 0 || comp_bytes < 128 + 4 * (uint64_t)S)
+        return ORC_E_FORMAT;
+    for (int v = 0; v < 256; v++) {
+        len[v] = (payload[v >> 1] >> (4 * (v & 1))) & 15;
+        if (len[v] > 11)
+            return ORC_E_FORMAT;
+        count[len[v]]++;
+    }
+    count[0] = 0;
+    {
+        /* symbols in order of (length, byte value); first code and first rank of each length */
+        int k = 0;
+        unsigned code = 0;
+        for (int l = 1; l <= 11; l++) {
+            code <<= 1;
+            first[l] = code;
+            base[l] = (unsigned)k;
+            for (int v = 0; v < 256; v++)
+                if (len[v] == l)
+                    sorted[k++] = (uint8_t)v;
+            code += count[l];
+        }
+        if (k == 0)
+            return ORC_E_FORMAT;
+    }
+    uint32_t groups = (raw_bytes + 15) / 16;
+    for (uint32_t j = 0; j < S; j++) {
+        uint32_t off32;
+        memcpy(&off32, payload + 128 + 4 * (uint64_t)j, 4);
+        const uint8_t *st = payload + off32;
+        uint64_t avail_bits = off32 <= comp_bytes ? (comp_bytes - off32) * 8 : 0;
+        uint64_t bit = 0;
+        for (uint32_t g = j; g < groups; g += S) {
+            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
+                unsigned code = 0;
+                int l = 0, found = 0;
+                while (l < 11) {
+                    if (bit >= avail_bits)
+                        return ORC_E_FORMAT;
+                    code = (code << 1) | ((st[bit >> 3] >> (bit & 7)) & 1u);
+                    bit++;
+                    l++;
+                    if (code >= first[l] && code - first[l] < count[l]) {
+                        dst[p] = sorted[base[l] + (code - first[l])];
+                        found = 1;
+                        break;
+                    }
+                }
+                if (!found)
+                    return ORC_E_FORMAT;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------- whole-buffer operations */
+
+static uint32_t chunk_raw_bytes(uint64_t n, uint32_t C, uint64_t k)
+{
+    uint64_t lo = k * C;
+    uint64_t hi = lo + C < n ? lo + C : n;
+    return (uint32_t)(hi - lo);
+}
+
+uint64_t orc_num_chunks(uint64_t n, uint32_t C) { return (n + C - 1) / C; }
+
+/* Huffman payload size of chunks k0 <= k < k1 (no output written). */
+int orc_chunk_sizes(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, uint64_t k0, uint64_t k1,
+                    uint32_t *huff_bytes)
+{
+    for (uint64_t k = k0; k < k1; k++) {
+        uint64_t sz = orc_encode_chunk(src + k * C, chunk_raw_bytes(n, C, k), S, 11, NULL, 0);
+        if (sz == 0)
+            return ORC_E_ARG;
+        huff_bytes[k] = (uint32_t)sz;
+    }
+    return ORC_OK;
+}
+
+/*
+ * Which chunks stay raw.
+ *   ALL_HUFF      none (even when coding enlarges the chunk)
+ *   AUTO          those whose gain = raw_bytes - huffman_payload_bytes is <= 0
+ *   RAW_FRACTION  the floor(f * n_chunks + 1/2) chunks of lowest gain, lower
+ *                 index first among equal gains
+ *   RAW_MASK      those with mask[k] != 0
+ *   BLOCK_LAST    the paper's rule (Section 3.3, "Speed Adaptive Partial
+ *                 Compression"): chunks are grouped in blocks of `block`
+ *                 consecutive chunks and only the last chunk of each block is
+ *                 compressed; a trailing partial block has no compressed chunk
+ */
+int orc_select_raw(const uint32_t *huff_bytes, uint64_t n, uint32_t C, uint64_t n_chunks, int policy,
+                   double raw_fraction, uint32_t block, const uint8_t *mask, uint8_t *is_raw)
+{
+    memset(is_raw, 0, n_chunks);
+    if (policy == ORC_ALL_HUFF)
+        return ORC_OK;
+    if (policy == ORC_AUTO) {
+        for (uint64_t k = 0; k < n_chunks; k++)
+            is_raw[k] = (int64_t)chunk_raw_bytes(n, C, k) - (int64_t)huff_bytes[k] <= 0;
+        return ORC_OK;
+    }
+    if (policy == ORC_RAW_MASK) {
+        if (!mask) return ORC_E_ARG;
+        for (uint64_t k = 0; k < n_chunks; k++)
+            is_raw[k] = mask[k] != 0;
+        return ORC_OK;
+    }
+    if (policy == ORC_BLOCK_LAST) {
+        if (block == 0) return ORC_E_ARG;
+        for (uint64_t k = 0; k < n_chunks; k++)
+            is_raw[k] = (k % block) != (uint64_t)(block - 1);
+        return ORC_OK;
+    }
+    if (policy == ORC_RAW_FRACTION) {
+        if (!(raw_fraction >= 0.0 && raw_fraction <= 1.0)) return ORC_E_ARG;
+        uint64_t n_raw = (uint64_t)(raw_fraction * (double)n_chunks + 0.5);
+        if (n_raw > n_chunks) n_raw = n_chunks;
+        /* selection by repeated minimum: slow and plain */
+        for (uint64_t r = 0; r < n_raw; r++) {
+            int64_t best_gain = 0;
+            uint64_t best = n_chunks;
+            for (uint64_t k = 0; k < n_chunks; k++) {
+                if (is_raw[k]) continue;
+                int64_t gain = (int64_t)chunk_raw_bytes(n, C, k) - (int64_t)huff_bytes[k];
+                if (best == n_chunks || gain < best_gain) {
+                    best = k;
+                    best_gain = gain;
+                }
+            }
+            is_raw[best] = 1;
+        }
+        return ORC_OK;
+    }
+    return ORC_E_ARG;
+}
+
+/* Offsets and sizes of every payload, laid out back to back.  Returns the blob size. */
+uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t n, uint32_t C,
+                    uint64_t n_chunks, orc_chunk *table)
+{
+    uint64_t off = 0;
+    for (uint64_t k = 0; k < n_chunks; k++) {
+        uint32_t raw = chunk_raw_bytes(n, C, k);
+        table[k].off = off;
+        if (is_raw[k]) {
+            table[k].comp_bytes = (uint32_t)round_up(raw, 16);
+            table[k].raw_bytes_flags = raw | ORC_RAW_FLAG;
+        } else {
+            table[k].comp_bytes = huff_bytes[k];
+            table[k].raw_bytes_flags = raw;
+        }
+        off += table[k].comp_bytes;
+    }
+    return off;
+}
+
+/* Write the payloads of chunks k0 <= k < k1 at the offsets the table gives. */
+int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_chunk *table,
+             uint64_t k0, uint64_t k1, uint8_t *blob)
+{
+    for (uint64_t k = k0; k < k1; k++) {
+        uint32_t raw = table[k].raw_bytes_flags & ~ORC_RAW_FLAG;
+        uint8_t *out = blob + table[k].off;
+        if (raw != chunk_raw_bytes(n, C, k))
+            return ORC_E_ARG;
+        if (table[k].raw_bytes_flags & ORC_RAW_FLAG) {
+            memset(out, 0, table[k].comp_bytes);
+            memcpy(out, src + k * C, raw);
+        } else {
+            uint64_t sz = orc_encode_chunk(src + k * C, raw, S, 11, out, table[k].comp_bytes);
+            if (sz != table[k].comp_bytes)
+                return ORC_E_ARG;
+        }
+    }
+    return ORC_OK;
+}
+
+/* Decode chunks k0 <= k < k1: chunk k lands at dst + k*C. */
+int orc_decompress(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *table, uint64_t k0,
+                   uint64_t k1, uint32_t C, uint32_t S, uint8_t *dst)
+{
+    for (uint64_t k = k0; k < k1; k++) {
+        uint32_t raw = table[k].raw_bytes_flags & ~ORC_RAW_FLAG;
+        if (raw == 0 || raw > C)
+            return ORC_E_FORMAT;
+        if (table[k].off + table[k].comp_bytes > blob_bytes)
+            return ORC_E_FORMAT;
+        const uint8_t *in = blob + table[k].off;
+        if (table[k].raw_bytes_flags & ORC_RAW_FLAG) {
+            if (table[k].comp_bytes < raw)
+                return ORC_E_FORMAT;
+            memcpy(dst + k * C, in, raw);
+        } else {
+            int rc = orc_decode_chunk(in, table[k].comp_bytes, raw, S, dst + k * C);
+            if (rc != ORC_OK)
+                return rc;
+        }
+    }
+    return ORC_OK;
+}

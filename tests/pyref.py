@@ -1,0 +1,130 @@
+"""Independent pure-Python references used to pin the C oracle.
+
+Nothing here calls the oracle or the library: a textbook Huffman (heap), an
+exhaustive / dynamic-programming optimum for length-limited codes, and a
+bit-walking decoder written straight from the format description.
+"""
+from __future__ import annotations
+
+import heapq
+import itertools
+import math
+from typing import Dict, List, Sequence
+
+
+def entropy_bits(cnt: Sequence[int]) -> float:
+    n = float(sum(cnt))
+    return -sum(c / n * math.log2(c / n) for c in cnt if c > 0)
+
+
+def huffman_lengths(cnt: Sequence[int]) -> List[int]:
+    """Unrestricted Huffman code lengths (textbook heap construction)."""
+    syms = [i for i, c in enumerate(cnt) if c > 0]
+    out = [0] * len(cnt)
+    if len(syms) == 1:
+        out[syms[0]] = 1
+        return out
+    heap = [(cnt[i], i, (i,)) for i in syms]
+    heapq.heapify(heap)
+    tick = len(cnt)
+    while len(heap) > 1:
+        a = heapq.heappop(heap)
+        b = heapq.heappop(heap)
+        for s in a[2] + b[2]:
+            out[s] += 1
+        heapq.heappush(heap, (a[0] + b[0], tick, a[2] + b[2]))
+        tick += 1
+    return out
+
+
+def cost(cnt: Sequence[int], lens: Sequence[int]) -> int:
+    return sum(int(c) * int(l) for c, l in zip(cnt, lens))
+
+
+def brute_force_limited_cost(cnt: Sequence[int], max_len: int) -> int:
+    """Minimum of sum cnt*len over ALL length vectors in 1..max_len with Kraft sum <= 1."""
+    syms = [c for c in cnt if c > 0]
+    if len(syms) == 1:
+        return syms[0]
+    best = None
+    for lens in itertools.product(range(1, max_len + 1), repeat=len(syms)):
+        if sum(1 << (max_len - l) for l in lens) <= (1 << max_len):
+            c = sum(a * b for a, b in zip(syms, lens))
+            if best is None or c < best:
+                best = c
+    return best
+
+
+def dp_limited_cost(cnt: Sequence[int], max_len: int) -> int:
+    """Optimal length-limited cost by dynamic programming over levels.
+
+    In some optimal code lengths do not decrease as counts decrease, so sort counts descending and
+    hand out lengths level by level: f[i][k] = least cost of giving the i most frequent symbols
+    lengths <= l using k units of 2^-max_len of the Kraft budget.
+    """
+    c = sorted((int(x) for x in cnt if x > 0), reverse=True)
+    n = len(c)
+    if n == 1:
+        return c[0]
+    pre = [0]
+    for x in c:
+        pre.append(pre[-1] + x)
+    full = 1 << max_len
+    INF = float("inf")
+    f = [[INF] * (full + 1) for _ in range(n + 1)]
+    f[0][0] = 0
+    for l in range(1, max_len + 1):
+        unit = 1 << (max_len - l)
+        g = [row[:] for row in f]  # zero symbols at this level
+        for i in range(n):
+            fi = f[i]
+            for k in range(0, full + 1):
+                base = fi[k]
+                if base == INF:
+                    continue
+                m = 1
+                while i + m <= n and k + m * unit <= full:
+                    v = base + l * (pre[i + m] - pre[i])
+                    if v < g[i + m][k + m * unit]:
+                        g[i + m][k + m * unit] = v
+                    m += 1
+        f = g
+    return int(min(f[n]))
+
+
+def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
+    """Decode one Huffman payload by walking bits, from the written format alone.
+
+    header: 128 bytes of 4-bit code lengths (value v in nibble v&1 of byte v>>1), then S little-endian
+    u32 stream offsets; stream bit i = bit (i%8) of byte i/8; codes canonical by (length, value),
+    written most significant bit first; bytes of 16-byte group g go to stream g % S.
+    """
+    lens = [(payload[v >> 1] >> (4 * (v & 1))) & 15 for v in range(256)]
+    book: Dict[tuple, int] = {}
+    code = 0
+    prev = 0
+    for l in range(1, 16):
+        for v in range(256):
+            if lens[v] == l:
+                if prev:
+                    code = (code + 1) << (l - prev)
+                book[(l, code)] = v
+                prev = l
+    offs = [int.from_bytes(payload[128 + 4 * j:132 + 4 * j], "little") for j in range(S)]
+    out = bytearray(raw_bytes)
+    groups = (raw_bytes + 15) // 16
+    for j in range(S):
+        bit = offs[j] * 8
+        for g in range(j, groups, S):
+            for p in range(16 * g, min(16 * g + 16, raw_bytes)):
+                l = 0
+                c = 0
+                while True:
+                    c = (c << 1) | ((payload[bit >> 3] >> (bit & 7)) & 1)
+                    bit += 1
+                    l += 1
+                    if (l, c) in book:
+                        out[p] = book[(l, c)]
+                        break
+                    assert l < 15, "no code matched"
+    return bytes(out)
