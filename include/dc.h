@@ -1,0 +1,200 @@
+/*
+ * dc.h - C ABI of the MI355X double-compression decode library (libdc_mi355x.so).
+ *
+ * The library implements the runtime half of the paper's double-compression
+ * method (Section 3.1 overview, Section 3.3 "Inference with DC-Compressed
+ * LLMs"): INT8-quantised, pruned LLM weights are stored as independently coded
+ * chunks in GPU memory and are decompressed by the GPU, for the layer that is
+ * about to be used, into a caller-owned decompression buffer; a speed-adaptive
+ * share of the chunks is stored raw.  The lossless coder is a per-chunk
+ * canonical Huffman code over the 256 byte values (code length <= 11) with S
+ * symbol-interleaved sub-bitstreams per chunk; its layout is given below.
+ *
+ * Conventions for every entry point
+ *   - extern "C", plain pointers and sizes.  "_host" pointers are ordinary
+ *     host memory, "_dev" pointers are device memory of the current HIP device.
+ *   - The caller owns every buffer.  The library allocates no memory the caller
+ *     can see and keeps no state between calls (except dc_set_num_threads).
+ *   - Return value: DC_OK (0) or a negative DC_E_* code; dc_strerror() names it.
+ *   - Device entry points only enqueue work on `hip_stream` (a hipStream_t, NULL
+ *     = the default stream) and never synchronise.  Arguments are checked on the
+ *     host before anything is enqueued; device memory contents (table, blob) are
+ *     not read by the host.  The kernels never read outside
+ *     [blob_dev, blob_dev + blob_bytes) nor write outside the destination's
+ *     stated capacity whatever the table or the payloads contain; a corrupt
+ *     chunk yields unspecified bytes for that chunk only.  dc_validate() is the
+ *     host-side checker that reports corruption.
+ *
+ * Stored format
+ *   chunk table entry (dc_chunk, 16 bytes, little endian)
+ *       off              payload offset inside the blob, multiple of 16
+ *       comp_bytes       payload size including padding, multiple of 16
+ *       raw_bytes_flags  bits 0..30 decoded size of the chunk (1..chunk_bytes),
+ *                        bit 31 set = payload is the raw bytes (DC_CHUNK_RAW)
+ *     chunk k decodes to bytes [k*chunk_bytes, k*chunk_bytes + raw_bytes) of the
+ *     destination; only the last chunk may be shorter than chunk_bytes.
+ *   raw payload          the bytes, zero padded to a multiple of 16
+ *   Huffman payload
+ *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
+ *                        byte v >> 1; 0 = value absent, otherwise 1..11
+ *       [128,128+4S)     u32 off[j], j < S: first byte of sub-stream j counted
+ *                        from the payload start, multiple of 4, non-decreasing
+ *       sub-streams      the chunk is cut in 16-byte groups; group g belongs to
+ *                        sub-stream g mod S; a sub-stream is the concatenated
+ *                        codes of its bytes in increasing position, zero padded
+ *                        to a whole number of 32-bit words.  No end marker:
+ *                        symbol counts follow from raw_bytes.
+ *       bit order        stream bit i is bit (i mod 32) of little-endian u32
+ *                        word i / 32; a code is written most significant code
+ *                        bit first.
+ *       codes            canonical: lengths from package-merge with limit 11
+ *                        (leaves ordered by count then byte value, a leaf before
+ *                        a package of equal weight); codes numbered in order of
+ *                        (length, byte value), first code 0.
+ */
+#ifndef DC_MI355X_H
+#define DC_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DC_OK 0
+#define DC_E_ARG (-1)    /* bad argument: null pointer, misalignment, unsupported parameter */
+#define DC_E_CAP (-2)    /* an output buffer is too small; required sizes are written back where stated */
+#define DC_E_FORMAT (-3) /* dc_validate: table or payload violates the stored format */
+#define DC_E_HIP (-4)    /* a HIP runtime call failed (launch error, no device) */
+
+#define DC_CHUNK_RAW 0x80000000u
+#define DC_MAX_CODE_LEN 11
+#define DC_MAX_CHUNK_BYTES (1u << 20)
+
+/* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
+#define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */
+#define DC_POLICY_AUTO 1         /* raw where gain = raw_bytes - huffman payload bytes <= 0 */
+#define DC_POLICY_RAW_FRACTION 2 /* the floor(raw_fraction*n_chunks + 1/2) chunks of lowest gain stay raw
+                                    (equal gains: lower chunk index first) */
+#define DC_POLICY_RAW_MASK 3     /* chunk k raw iff raw_mask[k] != 0 */
+#define DC_POLICY_BLOCK_LAST 4   /* the paper's rule: blocks of block_chunks consecutive chunks, only the
+                                    last chunk of each block is compressed */
+
+typedef struct {
+    uint64_t off;
+    uint32_t comp_bytes;
+    uint32_t raw_bytes_flags;
+} dc_chunk;
+
+typedef struct {
+    uint32_t chunk_bytes;   /* decoded bytes per chunk: multiple of 16, 16..DC_MAX_CHUNK_BYTES */
+    uint32_t n_streams;     /* S: sub-streams per chunk, one of 32, 64, 128 */
+    uint32_t policy;        /* DC_POLICY_*; only the compressor reads it */
+    float raw_fraction;     /* DC_POLICY_RAW_FRACTION: share of chunks kept raw, 0..1 */
+    uint32_t block_chunks;  /* DC_POLICY_BLOCK_LAST: chunks per block, >= 1 */
+    uint32_t reserved;      /* 0 */
+    const uint8_t *raw_mask; /* DC_POLICY_RAW_MASK: host array of n_chunks bytes, else NULL */
+} dc_params;
+
+/* Library identification string (static storage). */
+const char *dc_version(void);
+/* Name of a DC_E_* code (static storage). */
+const char *dc_strerror(int code);
+/* Host worker threads used by dc_quantize_rows / dc_compress_chunks / dc_validate; 0 = all cores.
+ * Returns the previous setting. */
+int dc_set_num_threads(int n);
+
+/*
+ * Compression-aware quantisation (Section 3.2; Eqs. 1, 2, 4 and the pruning step around Eq. 5).
+ *   w_host            fp32 W[rows][cols], row-major, cols = input channels
+ *   act_absmax_host   fp32 max|X_j| per input channel (cols values), or NULL for no rescale
+ *   alpha             exponent of Eq. 2: s_j = act_absmax_j ^ alpha (evaluated in fp64, rounded to fp32)
+ *   prune_abs         quantised weights with |q| <= prune_abs become 0 (0 = no pruning)
+ *   q_host            out: int8 q[rows][cols]
+ *   row_scale_host    out: fp32 scale per row; dequantised weight = q * row_scale
+ *   col_scale_host    out, may be NULL: the s_j that were applied (activations must be divided by them)
+ * Per row i: W' = W * s (fp32), m = max_j |W'_ij|, scale_i = m / 127 (fp32 division; 1 if m == 0),
+ * q_ij = clamp(round-half-even(W'_ij / scale_i), -127, 127).
+ * Errors: DC_E_ARG for null pointers or zero sizes.
+ */
+int dc_quantize_rows(const float *w_host, uint32_t rows, uint32_t cols, const float *act_absmax_host,
+                     double alpha, uint32_t prune_abs, int8_t *q_host, float *row_scale_host,
+                     float *col_scale_host);
+
+/*
+ * Worst-case blob size and number of chunks for raw_bytes input bytes (Section 3.3: the weight
+ * data is divided into data chunks).  Either output pointer may be NULL.
+ */
+int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, uint64_t *max_blob_bytes,
+                      uint64_t *n_chunks);
+
+/*
+ * Lossless compression of the quantised, pruned weights into a binary blob (last step of the
+ * compression stage, Section 3.1; chunk selection per Section 3.3).  Host to host.
+ *   src_host    raw_bytes int8 values (a row-major matrix or any byte string)
+ *   blob_host   out: payloads back to back in chunk order, blob_cap bytes available
+ *   blob_bytes  out: bytes used (on DC_E_CAP: bytes required)
+ *   table_host  out: one dc_chunk per chunk, table_cap entries available
+ *   n_chunks    out: entries used (on DC_E_CAP: entries required)
+ * The result is a function of the input and params alone (not of the thread count).
+ */
+int dc_compress_chunks(const int8_t *src_host, uint64_t raw_bytes, const dc_params *params,
+                       uint8_t *blob_host, uint64_t blob_cap, uint64_t *blob_bytes, dc_chunk *table_host,
+                       uint64_t table_cap, uint64_t *n_chunks);
+
+/*
+ * Host-side check of a table and blob against the stored format: offsets, sizes, alignment, code
+ * lengths forming a complete code, sub-stream extents, and that every sub-stream holds its symbols.
+ * Returns DC_OK or DC_E_FORMAT (first offending chunk index in *bad_chunk when not NULL).
+ */
+int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *table_host,
+                uint64_t n_chunks, const dc_params *params, uint64_t *bad_chunk);
+
+/*
+ * GPU decompression into the decompression buffer (Section 3.3, "Inference Process" and
+ * "Throughput Analysis": compressed chunks resident in GPU memory are decompressed by the GPU into
+ * a buffer in GPU memory from which inference reads the weights).  One kernel launch.
+ *   blob_dev, blob_bytes   the blob, 16-byte aligned
+ *   table_dev, n_chunks    chunk table in device memory
+ *   dst_dev, dst_cap       destination, 16-byte aligned; needs (n_chunks-1)*chunk_bytes + last chunk's
+ *                          raw_bytes bytes; the host checks dst_cap >= (n_chunks-1)*chunk_bytes + 1 and
+ *                          the kernel skips any chunk that would end beyond dst_cap
+ */
+int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                         uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
+                         void *hip_stream);
+
+/*
+ * Decompression fused with dequantisation to bf16 (replaces the separate conversion of the
+ * decompressed memory into tensors that Section 4.6 counts as overhead; dequantisation inverts Eq. 4):
+ *   dst[i*cols + j] = bf16_round_nearest_even( float(q_ij) * row_scale[i] ).
+ * The decoded bytes are the row-major int8 matrix q[rows][cols]; rows*cols must equal the decoded
+ * size, cols must be a multiple of 16.  dst_cap_elems counts bf16 elements.
+ */
+int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                               uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
+                               uint32_t rows, uint32_t cols, uint16_t *dst_bf16_dev,
+                               uint64_t dst_cap_elems, void *hip_stream);
+
+/*
+ * Decompression fused with the batch-1 product of Eq. 1, Y = X' W'^T for one activation row:
+ *   y_i = row_scale[i] * sum_j q_ij * x_j,   x given as bf16, accumulated in fp32.
+ * Nothing decoded is written to memory.  y_accum_dev (rows fp32 values) is zeroed by the call on the
+ * stream and receives the result; y_bf16_dev (rows bf16 values, may be NULL) receives it rounded to
+ * bf16.  cols must be a multiple of 16 and at most 16384.
+ */
+int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                       uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
+                       uint32_t rows, uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev,
+                       uint16_t *y_bf16_dev, void *hip_stream);
+
+/*
+ * Plain device copy kernel (reads n bytes, writes n bytes, 16-byte aligned): the denominator for
+ * "share of achievable bandwidth" next to the decode kernels (cf. B_gpu in Eq. 11).
+ */
+int dc_device_copy(const void *src_dev, void *dst_dev, uint64_t bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DC_MI355X_H */

@@ -1,0 +1,29 @@
+"""MI355X-native decode path of the double-compression method (arXiv 2502.15443).
+
+Thin Python binding over the C-ABI library libdc_mi355x.so (see include/dc.h).  Every step of the
+path runs inside the library (host C++ for quantise/compress/validate, HIP kernels for the decode
+calls); this package only marshals arguments.  There is no CPU fallback: if the library is missing
+the import of the binding fails.
+"""
+from .binding import (  # noqa: F401
+    DCError,
+    Params,
+    CHUNK_DTYPE,
+    POLICY_ALL_HUFF,
+    POLICY_AUTO,
+    POLICY_RAW_FRACTION,
+    POLICY_RAW_MASK,
+    POLICY_BLOCK_LAST,
+    CHUNK_RAW,
+    lib_path,
+    version,
+    set_num_threads,
+    quantize_rows,
+    compress_bound,
+    compress_chunks,
+    validate,
+    decompress_chunks,
+    decompress_dequant_bf16,
+    decompress_gemv,
+    device_copy,
+)

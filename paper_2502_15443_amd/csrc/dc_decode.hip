@@ -1,0 +1,543 @@
+// Device side of libdc_mi355x: chunk decode kernels for gfx950 (CDNA4, wave64).
+//
+// Paper: Section 3.3 ("Inference Process", "Throughput Analysis"): compressed chunks resident in GPU
+// memory are decompressed by the GPU into a decompression buffer; "Speed Adaptive Partial
+// Compression": some chunks are raw and only need a copy.  The stored format is in include/dc.h.
+//
+// Work decomposition: one wavefront owns 64 sub-streams.  With S = 32 sub-streams per chunk a wave
+// owns two chunks (lanes 0-31 / 32-63), with S = 64 one chunk, with S = 128 one chunk and every lane
+// owns two sub-streams.  The decode table of a chunk (2048 x u16: symbol << 8 | length, indexed by
+// the next 11 stream bits) lives in LDS.  A lane packs 16 decoded bytes and writes them with one
+// 128-bit store; the lanes of a chunk write S*16 contiguous bytes per round.
+#include <hip/hip_runtime.h>
+
+#include "dc.h"
+
+namespace {
+
+constexpr int kPeekBits = DC_MAX_CODE_LEN;
+constexpr int kTableEntries = 1 << kPeekBits;
+
+enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 128-bit streaming accesses: data that is touched once should not displace the bitstream lines
+// that the lanes keep re-reading from L2.
+__device__ __forceinline__ void store16_stream(void *p, uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    u32x4 v = {a, b, c, d};
+    __builtin_nontemporal_store(v, static_cast<u32x4 *>(p));
+}
+__device__ __forceinline__ u32x4 load16_stream(const void *p)
+{
+    return __builtin_nontemporal_load(static_cast<const u32x4 *>(p));
+}
+
+template <int S> struct Geometry {
+    static constexpr int kLanesPerChunk = S >= 64 ? 64 : S;
+    static constexpr int kChunksPerWave = 64 / kLanesPerChunk;
+    static constexpr int kStreamsPerLane = S / kLanesPerChunk;
+    static constexpr int kSymbolsPerLane = 256 / kLanesPerChunk; // header values handled by a lane
+};
+
+struct DecodeArgs {
+    const uint8_t *blob;
+    uint64_t blob_bytes;
+    const dc_chunk *table;
+    uint64_t n_chunks;
+    uint32_t chunk_bytes;
+    // kModeI8: dst = int8 bytes, dst_cap in bytes.  kModeBf16: dst = bf16, dst_cap in elements.
+    void *dst;
+    uint64_t dst_cap;
+    const float *row_scale; // kModeBf16
+    uint32_t rows, cols;    // kModeBf16 / kModeGemv
+    const uint16_t *x_bf16; // kModeGemv
+    float *y_accum;         // kModeGemv
+};
+
+// One sub-stream as a lane sees it: a 64-bit LSB-first bit buffer, one prefetched word, and the
+// index of the next word to fetch (relative to the chunk payload, clamped to the blob).
+struct BitReader {
+    uint64_t buf;
+    uint32_t avail; // valid bits in buf; only the low 8 bits are meaningful between refills
+    uint32_t next;
+    uint32_t word;
+
+    __device__ __forceinline__ uint32_t fetch(const uint32_t *__restrict__ payload, uint32_t max_word)
+    {
+        const uint32_t w = word < max_word ? word : max_word;
+        word++;
+        return payload[w];
+    }
+    __device__ __forceinline__ void init(const uint32_t *__restrict__ payload, uint32_t first, uint32_t max_word)
+    {
+        word = first;
+        const uint32_t lo = fetch(payload, max_word);
+        const uint32_t hi = fetch(payload, max_word);
+        buf = (uint64_t)lo | ((uint64_t)hi << 32);
+        next = fetch(payload, max_word);
+        avail = 64;
+    }
+    // After this at least 33 bits are valid: enough for three codes of 11 bits.
+    __device__ __forceinline__ void refill(const uint32_t *__restrict__ payload, uint32_t max_word)
+    {
+        uint32_t a = avail & 0xFFu;
+        if (a <= 32) {
+            buf |= (uint64_t)next << a;
+            a += 32;
+            next = fetch(payload, max_word);
+        }
+        avail = a;
+    }
+    // Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount
+    // and `avail` is only read through its low 8 bits, so the entry is used unmasked for both.
+    __device__ __forceinline__ uint32_t symbol(const uint16_t *__restrict__ tbl)
+    {
+        const uint32_t e = tbl[(uint32_t)buf & (kTableEntries - 1)];
+        buf >>= (e & 63u);
+        avail -= e;
+        return e;
+    }
+};
+
+// bytes 1 of four entries -> one little-endian word of four symbols
+__device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(e1, e0, 0x0c0c0501u);
+    const uint32_t hi = __builtin_amdgcn_perm(e3, e2, 0x0c0c0501u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+__device__ __forceinline__ void decode16(BitReader &br, const uint16_t *__restrict__ tbl,
+                                         const uint32_t *__restrict__ payload, uint32_t max_word, uint32_t out[4])
+{
+    uint32_t e[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        if (i % 3 == 0) br.refill(payload, max_word);
+        e[i] = br.symbol(tbl);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) out[i] = pack4(e[4 * i], e[4 * i + 1], e[4 * i + 2], e[4 * i + 3]);
+}
+
+__device__ __forceinline__ uint32_t bf16x2(float a, float b)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Four int8 values in a word -> fp32.  q = (byte ^ 0x80) - 128, so q*s = fma(float(byte^0x80), s, -128 s)
+// with a single rounding.
+__device__ __forceinline__ void word_to_scaled_f32(uint32_t w, float s, float bias, float f[4])
+{
+    const uint32_t u = w ^ 0x80808080u;
+    f[0] = __builtin_fmaf((float)(u & 0xFFu), s, bias);
+    f[1] = __builtin_fmaf((float)((u >> 8) & 0xFFu), s, bias);
+    f[2] = __builtin_fmaf((float)((u >> 16) & 0xFFu), s, bias);
+    f[3] = __builtin_fmaf((float)(u >> 24), s, bias);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+template <int S, int MODE>
+__global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
+{
+    using G = Geometry<S>;
+    constexpr int LPC = G::kLanesPerChunk;
+    constexpr int CPW = G::kChunksPerWave;
+    constexpr int NS = G::kStreamsPerLane;
+    constexpr int SPL = G::kSymbolsPerLane;
+    constexpr uint32_t kHeader = 128 + 4 * S;
+
+    __shared__ uint16_t lds_table[CPW][kTableEntries];
+    __shared__ uint32_t lds_first[CPW][16]; // left-aligned first code of each length
+
+    const uint32_t lane = threadIdx.x;
+    const uint32_t sub = lane / LPC;
+    const uint32_t cl = lane % LPC;
+    const uint64_t k = (uint64_t)blockIdx.x * CPW + sub;
+
+    // ---- chunk table entry, checked so that nothing below can leave the blob or the destination
+    bool active = k < a.n_chunks;
+    dc_chunk ent = {0, 0, 0};
+    if (active) ent = a.table[k];
+    const uint32_t raw = ent.raw_bytes_flags & ~DC_CHUNK_RAW;
+    const bool is_raw = (ent.raw_bytes_flags & DC_CHUNK_RAW) != 0;
+    const uint64_t dst_pos = k * (uint64_t)a.chunk_bytes; // first decoded byte of the chunk
+    active = active && raw >= 1 && raw <= a.chunk_bytes && (ent.off & 15) == 0 && ent.off <= a.blob_bytes &&
+             ent.comp_bytes <= a.blob_bytes - ent.off && ent.comp_bytes >= 16 && dst_pos + raw <= a.dst_cap &&
+             (is_raw ? ent.comp_bytes >= ((raw + 15u) & ~15u) : ent.comp_bytes >= kHeader);
+    const uint8_t *payload8 = a.blob + (active ? ent.off : 0);
+    const uint32_t *payload = reinterpret_cast<const uint32_t *>(payload8);
+    const bool huff = active && !is_raw;
+
+    uint16_t *tbl = lds_table[sub];
+
+    // ---- decode table (all lanes walk through this block; inactive chunks contribute nothing)
+    {
+        uint4 *z = reinterpret_cast<uint4 *>(tbl);
+        for (uint32_t i = cl; i < kTableEntries * 2 / 16; i += LPC) z[i] = make_uint4(0, 0, 0, 0);
+
+        // this lane's SPL code lengths, values v = cl*SPL + s
+        uint32_t nib = 0;
+        if (huff) {
+            if (SPL == 8) nib = payload[cl];
+            else nib = reinterpret_cast<const uint16_t *>(payload8)[cl];
+        }
+        // counts per length, packed three 10-bit fields a register: length l in reg (l-1)/3
+        uint32_t mine[4] = {0, 0, 0, 0};
+        uint32_t len_of[SPL];
+#pragma unroll
+        for (int s = 0; s < SPL; s++) {
+            uint32_t l = (nib >> (4 * s)) & 15u;
+            if (l > DC_MAX_CODE_LEN) l = 0;
+            len_of[s] = l;
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                if (l != 0 && (l - 1) / 3 == (uint32_t)r) mine[r] += 1u << (10 * ((l - 1) % 3));
+        }
+        uint32_t incl[4], total[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            uint32_t v = mine[r];
+#pragma unroll
+            for (int d = 1; d < LPC; d <<= 1) {
+                const uint32_t t = __shfl_up(v, d, LPC);
+                if (cl >= (uint32_t)d) v += t;
+            }
+            incl[r] = v;
+            total[r] = __shfl(v, LPC - 1, LPC);
+        }
+        // left-aligned (11-bit) first code of every length
+        if (cl == 0) {
+            uint32_t first = 0;
+#pragma unroll
+            for (int l = 1; l <= DC_MAX_CODE_LEN; l++) {
+                lds_first[sub][l] = first;
+                const uint32_t c = (total[(l - 1) / 3] >> (10 * ((l - 1) % 3))) & 1023u;
+                first += c << (kPeekBits - l);
+            }
+        }
+        __syncthreads();
+        uint32_t before[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) before[r] = incl[r] - mine[r];
+#pragma unroll
+        for (int s = 0; s < SPL; s++) {
+            const uint32_t l = len_of[s];
+            if (l != 0) {
+                const uint32_t r = (l - 1) / 3, sh = 10 * ((l - 1) % 3);
+                const uint32_t packed = r == 0 ? before[0] : r == 1 ? before[1] : r == 2 ? before[2] : before[3];
+                const uint32_t rank = (packed >> sh) & 1023u;
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    if (r == (uint32_t)q) before[q] += 1u << sh;
+                const uint32_t start = lds_first[sub][l] + (rank << (kPeekBits - l)); // MSB-first slot
+                if (start < (uint32_t)kTableEntries) {
+                    const uint32_t rev = __brev(start) >> (32 - kPeekBits); // code bits in stream order
+                    const uint16_t entry = (uint16_t)(l | ((cl * SPL + s) << 8));
+                    for (uint32_t i = rev; i < (uint32_t)kTableEntries; i += 1u << l) tbl[i] = entry;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- raw chunks: the lanes of the chunk copy it 16 bytes at a time
+    if (active && is_raw) {
+        if (MODE == kModeI8) {
+            uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
+            const uint32_t n16 = raw / 16;
+            for (uint32_t i = cl; i < n16; i += LPC) {
+                const u32x4 v = load16_stream(payload8 + 16 * (size_t)i);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d8 + 16 * (size_t)i));
+            }
+            for (uint32_t i = n16 * 16 + cl; i < raw; i += LPC) d8[i] = payload8[i];
+        }
+    }
+
+    if (MODE != kModeI8 && !(active)) return;
+    if (MODE == kModeI8 && !huff) return;
+
+    // ---- sub-stream set-up
+    const uint64_t last_word = (a.blob_bytes - ent.off) / 4 - 1; // last whole word of the blob, from this payload
+    const uint32_t max_word = last_word > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)last_word;
+    BitReader br[NS];
+    uint32_t stream_id[NS];
+#pragma unroll
+    for (int t = 0; t < NS; t++) {
+        stream_id[t] = cl + t * LPC;
+        uint32_t off = kHeader;
+        if (huff) off = payload[32 + stream_id[t]];
+        if ((off & 3u) || off > ent.comp_bytes) off = kHeader;
+        if (huff) br[t].init(payload, off / 4, max_word);
+    }
+
+    const uint32_t round_bytes = 16 * S;
+    const uint32_t full_rounds = raw / round_bytes;
+    const uint32_t rem = raw - full_rounds * round_bytes;
+
+    if (MODE == kModeI8) {
+        uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
+        for (uint32_t r = 0; r < full_rounds; r++) {
+#pragma unroll
+            for (int t = 0; t < NS; t++) {
+                uint32_t w[4];
+                decode16(br[t], tbl, payload, max_word, w);
+                store16_stream(d8 + (size_t)r * round_bytes + stream_id[t] * 16, w[0], w[1], w[2], w[3]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NS; t++) {
+            const uint32_t start = stream_id[t] * 16;
+            const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
+            uint8_t *d = d8 + (size_t)full_rounds * round_bytes + start;
+            for (uint32_t i = 0; i < n; i++) {
+                br[t].refill(payload, max_word);
+                d[i] = (uint8_t)(br[t].symbol(tbl) >> 8);
+            }
+        }
+        return;
+    }
+
+    // ---- fused consumers walk the matrix: group position -> (row, column)
+    const uint32_t cols = a.cols;
+    if (MODE == kModeBf16) {
+        uint16_t *out = static_cast<uint16_t *>(a.dst);
+        const uint32_t rounds = full_rounds + (rem ? 1 : 0);
+#pragma unroll
+        for (int t = 0; t < NS; t++) {
+            uint64_t pos = dst_pos + stream_id[t] * 16;
+            uint32_t row = (uint32_t)(pos / cols);
+            uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
+            for (uint32_t r = 0; r < rounds; r++) {
+                const uint32_t start = r * round_bytes + stream_id[t] * 16;
+                // the matrix size is a multiple of 16, so a group is whole or absent
+                const bool whole = raw >= start + 16;
+                uint32_t w[4] = {0, 0, 0, 0};
+                if (whole) {
+                    if (is_raw) {
+                        const u32x4 v = load16_stream(payload8 + start);
+                        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+                    } else {
+                        decode16(br[t], tbl, payload, max_word, w);
+                    }
+                    const float s = a.row_scale[row];
+                    const float bias = -128.0f * s;
+                    uint32_t o[8];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        float f[4];
+                        word_to_scaled_f32(w[i], s, bias, f);
+                        o[2 * i] = bf16x2(f[0], f[1]);
+                        o[2 * i + 1] = bf16x2(f[2], f[3]);
+                    }
+                    uint16_t *d = out + (pos + (uint64_t)r * round_bytes);
+                    store16_stream(d, o[0], o[1], o[2], o[3]);
+                    store16_stream(d + 8, o[4], o[5], o[6], o[7]);
+                }
+                col += round_bytes;
+                while (col >= cols) { col -= cols; row++; }
+            }
+        }
+        return;
+    }
+
+    if (MODE == kModeGemv) {
+        // Partial dot products of byte^0x80 (1..255) with x; the -128*sum(x) term and the row scale
+        // are applied once per row by dc_gemv_finish_kernel.
+        const uint32_t rounds = full_rounds + (rem ? 1 : 0);
+#pragma unroll
+        for (int t = 0; t < NS; t++) {
+            uint64_t pos = dst_pos + stream_id[t] * 16;
+            uint32_t row = (uint32_t)(pos / cols);
+            uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
+            uint32_t cur_row = row;
+            float acc = 0.0f;
+            for (uint32_t r = 0; r < rounds; r++) {
+                const uint32_t start = r * round_bytes + stream_id[t] * 16;
+                const bool whole = raw >= start + 16;
+                if (whole) {
+                    uint32_t w[4];
+                    if (is_raw) {
+                        const u32x4 v = load16_stream(payload8 + start);
+                        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+                    } else {
+                        decode16(br[t], tbl, payload, max_word, w);
+                    }
+                    if (row != cur_row) {
+                        atomicAdd(a.y_accum + cur_row, acc);
+                        acc = 0.0f;
+                        cur_row = row;
+                    }
+                    const uint4 *xp = reinterpret_cast<const uint4 *>(a.x_bf16 + col);
+                    const uint4 xa = xp[0], xb = xp[1];
+                    const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const uint32_t u = w[i] ^ 0x80808080u;
+                        acc = __builtin_fmaf((float)(u & 0xFFu), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
+                        acc = __builtin_fmaf((float)((u >> 8) & 0xFFu), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
+                        acc = __builtin_fmaf((float)((u >> 16) & 0xFFu), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
+                        acc = __builtin_fmaf((float)(u >> 24), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
+                    }
+                }
+                col += round_bytes;
+                while (col >= cols) { col -= cols; row++; }
+            }
+            atomicAdd(a.y_accum + cur_row, acc);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void dc_fill_f32_kernel(float *p, uint32_t n, float v)
+{
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// y_i = scale_i * (acc_i - 128 * sum_j x_j); every block re-reduces x (at most 32 KiB, cache resident).
+__global__ __launch_bounds__(256) void dc_gemv_finish_kernel(float *y_accum, uint16_t *y_bf16, const float *row_scale,
+                                                             const uint16_t *x_bf16, uint32_t rows, uint32_t cols)
+{
+    __shared__ float part[256];
+    float s = 0.0f;
+    for (uint32_t j = threadIdx.x; j < cols; j += 256) s += bf16_bits_to_f32(x_bf16[j]);
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int d = 128; d > 0; d >>= 1) {
+        if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
+        __syncthreads();
+    }
+    const float xsum = part[0];
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i < rows) {
+        const float y = row_scale[i] * (y_accum[i] - 128.0f * xsum);
+        y_accum[i] = y;
+        if (y_bf16) y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
+    }
+}
+
+__global__ __launch_bounds__(256) void dc_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, uint64_t n16)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+bool decode_params_ok(const dc_params *p)
+{
+    if (!p) return false;
+    if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
+    return p->n_streams == 32 || p->n_streams == 64 || p->n_streams == 128;
+}
+
+template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream_t stream)
+{
+    if (a.n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
+    if (S == 32) {
+        const uint32_t grid = (uint32_t)((a.n_chunks + 1) / 2);
+        hipLaunchKernelGGL((dc_decode_kernel<32, MODE>), dim3(grid), dim3(64), 0, stream, a);
+    } else if (S == 64) {
+        hipLaunchKernelGGL((dc_decode_kernel<64, MODE>), dim3((uint32_t)a.n_chunks), dim3(64), 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((dc_decode_kernel<128, MODE>), dim3((uint32_t)a.n_chunks), dim3(64), 0, stream, a);
+    }
+    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+} // namespace
+
+extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                    uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
+                                    void *hip_stream)
+{
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_dev || n_chunks == 0 || blob_bytes < 16)
+        return DC_E_ARG;
+    if (!aligned16(blob_dev) || !aligned16(dst_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
+    if (dst_cap < (n_chunks - 1) * (uint64_t)params->chunk_bytes + 1) return DC_E_CAP;
+    DecodeArgs a = {};
+    a.blob = blob_dev;
+    a.blob_bytes = blob_bytes;
+    a.table = table_dev;
+    a.n_chunks = n_chunks;
+    a.chunk_bytes = params->chunk_bytes;
+    a.dst = dst_dev;
+    a.dst_cap = dst_cap;
+    return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                          uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
+                                          uint32_t rows, uint32_t cols, uint16_t *dst_bf16_dev, uint64_t dst_cap_elems,
+                                          void *hip_stream)
+{
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_bf16_dev || !row_scale_dev || n_chunks == 0 ||
+        blob_bytes < 16 || rows == 0 || cols == 0 || cols % 16)
+        return DC_E_ARG;
+    if (!aligned16(blob_dev) || !aligned16(dst_bf16_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
+    const uint64_t total = (uint64_t)rows * cols;
+    if ((total + params->chunk_bytes - 1) / params->chunk_bytes != n_chunks) return DC_E_ARG;
+    if (dst_cap_elems < total) return DC_E_CAP;
+    DecodeArgs a = {};
+    a.blob = blob_dev;
+    a.blob_bytes = blob_bytes;
+    a.table = table_dev;
+    a.n_chunks = n_chunks;
+    a.chunk_bytes = params->chunk_bytes;
+    a.dst = dst_bf16_dev;
+    a.dst_cap = total; // chunks may not decode past the matrix
+    a.row_scale = row_scale_dev;
+    a.rows = rows;
+    a.cols = cols;
+    return launch_decode<kModeBf16>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                  uint64_t n_chunks, const dc_params *params, const float *row_scale_dev, uint32_t rows,
+                                  uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev, uint16_t *y_bf16_dev,
+                                  void *hip_stream)
+{
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !row_scale_dev || !x_bf16_dev || !y_accum_dev ||
+        n_chunks == 0 || blob_bytes < 16 || rows == 0 || cols == 0 || cols % 16 || cols > 16384)
+        return DC_E_ARG;
+    if (!aligned16(blob_dev) || !aligned16(x_bf16_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
+    const uint64_t total = (uint64_t)rows * cols;
+    if ((total + params->chunk_bytes - 1) / params->chunk_bytes != n_chunks) return DC_E_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(dc_fill_f32_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, y_accum_dev, rows, 0.0f);
+    DecodeArgs a = {};
+    a.blob = blob_dev;
+    a.blob_bytes = blob_bytes;
+    a.table = table_dev;
+    a.n_chunks = n_chunks;
+    a.chunk_bytes = params->chunk_bytes;
+    a.dst_cap = total;
+    a.rows = rows;
+    a.cols = cols;
+    a.x_bf16 = x_bf16_dev;
+    a.y_accum = y_accum_dev;
+    const int rc = launch_decode<kModeGemv>(a, params->n_streams, stream);
+    if (rc != DC_OK) return rc;
+    hipLaunchKernelGGL(dc_gemv_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, y_accum_dev, y_bf16_dev,
+                       row_scale_dev, x_bf16_dev, rows, cols);
+    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+}
+
+extern "C" int dc_device_copy(const void *src_dev, void *dst_dev, uint64_t bytes, void *hip_stream)
+{
+    if (!src_dev || !dst_dev || bytes == 0 || bytes % 16 || !aligned16(src_dev) || !aligned16(dst_dev)) return DC_E_ARG;
+    const uint64_t n16 = bytes / 16;
+    uint64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256ull * 32) blocks = 256ull * 32;
+    hipLaunchKernelGGL(dc_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const u32x4 *>(src_dev), static_cast<u32x4 *>(dst_dev), n16);
+    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+}

@@ -1,0 +1,490 @@
+// Host side of libdc_mi355x: quantisation front end, chunk compressor, format checker.
+//
+// Paper: Section 3.2 (per-channel scaling Eqs. 1-2, INT8 quantisation Eq. 4, pruning around Eq. 5),
+// Section 3.1 / 3.3 (lossless compression in chunks, speed-adaptive choice of raw chunks).
+// The stored format is described in include/dc.h.
+#include "dc.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+std::atomic<int> g_threads{0};
+
+int worker_count(uint64_t items)
+{
+    int n = g_threads.load();
+    if (n <= 0) {
+        n = (int)std::thread::hardware_concurrency();
+        if (n <= 0) n = 1;
+    }
+    if ((uint64_t)n > items) n = (int)std::max<uint64_t>(items, 1);
+    return n;
+}
+
+// Static partition of [0, items) over the worker threads.
+template <class F> void parallel_ranges(uint64_t items, F &&fn)
+{
+    const int n = worker_count(items);
+    if (n <= 1) {
+        fn(0, items);
+        return;
+    }
+    std::vector<std::thread> pool;
+    pool.reserve(n);
+    for (int t = 0; t < n; t++) {
+        const uint64_t a = items * (uint64_t)t / n, b = items * (uint64_t)(t + 1) / n;
+        if (b > a) pool.emplace_back([&fn, a, b] { fn(a, b); });
+    }
+    for (auto &th : pool) th.join();
+}
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+bool params_ok(const dc_params *p)
+{
+    if (!p) return false;
+    if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
+    if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128) return false;
+    return true;
+}
+
+inline uint32_t chunk_len(uint64_t total, uint32_t C, uint64_t k)
+{
+    const uint64_t lo = k * C;
+    return (uint32_t)std::min<uint64_t>(C, total - lo);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Code construction
+// ---------------------------------------------------------------------------------------------
+
+struct CodeBook {
+    uint8_t len[256];
+    uint16_t rev[256]; // code with its bits reversed: ready to be OR-ed into an LSB-first accumulator
+};
+
+// Length-limited optimal code lengths by package-merge, in the "how many leaves are bought at each
+// level" form: every level list is the sorted leaves merged with the pairs of the level below
+// (a leaf before a package of equal weight); buying the first m items of a level buys a prefix of
+// the leaves, plus packages that each stand for two items of the level below.
+void limited_lengths(const uint32_t cnt[256], uint8_t len[256])
+{
+    constexpr int L = DC_MAX_CODE_LEN;
+    int order[256];
+    int n = 0;
+    for (int v = 0; v < 256; v++)
+        if (cnt[v]) order[n++] = v;
+    std::memset(len, 0, 256);
+    if (n == 0) return;
+    if (n == 1) {
+        len[order[0]] = 1;
+        return;
+    }
+    std::stable_sort(order, order + n, [&](int a, int b) { return cnt[a] < cnt[b]; });
+    uint64_t leafw[256];
+    for (int i = 0; i < n; i++) leafw[i] = cnt[order[i]];
+
+    // weight[j][i] and leaves_before[j][i] = number of leaves among the first i items of level j
+    static thread_local uint64_t weight[L][512];
+    static thread_local uint16_t leaves_before[L][513];
+    int size[L];
+    for (int i = 0; i < n; i++) {
+        weight[0][i] = leafw[i];
+        leaves_before[0][i] = (uint16_t)i;
+    }
+    leaves_before[0][n] = (uint16_t)n;
+    size[0] = n;
+    for (int j = 1; j < L; j++) {
+        const int npk = size[j - 1] / 2;
+        int a = 0, b = 0, m = 0;
+        while (a < n || b < npk) {
+            const uint64_t pw = b < npk ? weight[j - 1][2 * b] + weight[j - 1][2 * b + 1] : 0;
+            const bool leaf = b >= npk || (a < n && leafw[a] <= pw);
+            leaves_before[j][m] = (uint16_t)a;
+            if (leaf) weight[j][m] = leafw[a++];
+            else { weight[j][m] = pw; b++; }
+            m++;
+        }
+        leaves_before[j][m] = (uint16_t)a;
+        size[j] = m;
+    }
+    int bought = 2 * n - 2;
+    int depth[256] = {0};
+    for (int j = L - 1; j >= 0 && bought > 0; j--) {
+        const int nl = leaves_before[j][bought];
+        for (int i = 0; i < nl; i++) depth[i]++;
+        bought = 2 * (bought - nl);
+    }
+    for (int i = 0; i < n; i++) len[order[i]] = (uint8_t)depth[i];
+}
+
+inline uint32_t bit_reverse(uint32_t x, int bits)
+{
+    uint32_t r = 0;
+    for (int i = 0; i < bits; i++) r |= ((x >> i) & 1u) << (bits - 1 - i);
+    return r;
+}
+
+void make_codebook(const uint32_t cnt[256], CodeBook &cb)
+{
+    limited_lengths(cnt, cb.len);
+    uint32_t per_len[DC_MAX_CODE_LEN + 2] = {0};
+    for (int v = 0; v < 256; v++) per_len[cb.len[v]]++;
+    per_len[0] = 0;
+    uint32_t next[DC_MAX_CODE_LEN + 2];
+    uint32_t code = 0;
+    for (int l = 1; l <= DC_MAX_CODE_LEN; l++) {
+        code = (code + per_len[l - 1]) << 1;
+        next[l] = code;
+    }
+    for (int v = 0; v < 256; v++) {
+        const int l = cb.len[v];
+        cb.rev[v] = l ? (uint16_t)bit_reverse(next[l]++, l) : 0;
+    }
+}
+
+void histogram256(const uint8_t *p, uint32_t n, uint32_t out[256])
+{
+    uint32_t h[4][256];
+    std::memset(h, 0, sizeof(h));
+    uint32_t i = 0;
+    for (; i + 4 <= n; i += 4) {
+        h[0][p[i]]++;
+        h[1][p[i + 1]]++;
+        h[2][p[i + 2]]++;
+        h[3][p[i + 3]]++;
+    }
+    for (; i < n; i++) h[0][p[i]]++;
+    for (int v = 0; v < 256; v++) out[v] = h[0][v] + h[1][v] + h[2][v] + h[3][v];
+}
+
+// Bits of every sub-stream of a chunk under a codebook.
+void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb, uint64_t *bits)
+{
+    std::fill(bits, bits + S, 0);
+    const uint32_t groups = (raw + 15) / 16;
+    uint32_t j = 0;
+    for (uint32_t g = 0; g < groups; g++) {
+        const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16);
+        uint32_t b = 0;
+        for (uint32_t p = lo; p < hi; p++) b += cb.len[src[p]];
+        bits[j] += b;
+        if (++j == S) j = 0;
+    }
+}
+
+uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
+{
+    uint64_t pos = 128 + 4ull * S;
+    for (uint32_t j = 0; j < S; j++) pos += (bits[j] + 31) / 32 * 4;
+    return (uint32_t)align_up(pos, 16);
+}
+
+// Writes one Huffman payload (header, offsets, sub-streams); `out` has comp_bytes bytes.
+void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb,
+                        const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
+{
+    std::memset(out, 0, comp_bytes);
+    for (int v = 0; v < 256; v++) out[v >> 1] |= (uint8_t)(cb.len[v] << (4 * (v & 1)));
+    uint32_t pos = 128 + 4 * S;
+    const uint32_t groups = (raw + 15) / 16;
+    for (uint32_t j = 0; j < S; j++) {
+        std::memcpy(out + 128 + 4 * j, &pos, 4);
+        uint32_t *w = reinterpret_cast<uint32_t *>(out + pos);
+        uint64_t acc = 0;
+        int fill = 0;
+        for (uint32_t g = j; g < groups; g += S) {
+            const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16);
+            for (uint32_t p = lo; p < hi; p++) {
+                const uint8_t v = src[p];
+                acc |= (uint64_t)cb.rev[v] << fill;
+                fill += cb.len[v];
+                if (fill >= 32) {
+                    *w++ = (uint32_t)acc;
+                    acc >>= 32;
+                    fill -= 32;
+                }
+            }
+        }
+        if (fill > 0) *w++ = (uint32_t)acc;
+        pos += (uint32_t)((bits[j] + 31) / 32 * 4);
+    }
+}
+
+} // namespace
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.1 (gfx950; canonical Huffman L11, LSB-first sub-streams)"; }
+
+extern "C" const char *dc_strerror(int code)
+{
+    switch (code) {
+    case DC_OK: return "DC_OK";
+    case DC_E_ARG: return "DC_E_ARG: bad argument";
+    case DC_E_CAP: return "DC_E_CAP: output buffer too small";
+    case DC_E_FORMAT: return "DC_E_FORMAT: table or payload violates the stored format";
+    case DC_E_HIP: return "DC_E_HIP: HIP runtime call failed";
+    default: return "unknown dc error code";
+    }
+}
+
+extern "C" int dc_set_num_threads(int n)
+{
+    return g_threads.exchange(n < 0 ? 0 : n);
+}
+
+extern "C" int dc_quantize_rows(const float *w, uint32_t rows, uint32_t cols, const float *act_absmax,
+                                double alpha, uint32_t prune_abs, int8_t *q, float *row_scale,
+                                float *col_scale_out)
+{
+    if (!w || !q || !row_scale || rows == 0 || cols == 0) return DC_E_ARG;
+    std::vector<float> s;
+    if (act_absmax) {
+        s.resize(cols);
+        for (uint32_t j = 0; j < cols; j++) s[j] = (float)std::pow((double)act_absmax[j], alpha);
+    }
+    if (col_scale_out) {
+        for (uint32_t j = 0; j < cols; j++) col_scale_out[j] = act_absmax ? s[j] : 1.0f;
+    }
+    const float *sp = act_absmax ? s.data() : nullptr;
+    const int thr = (int)std::min<uint32_t>(prune_abs, 127);
+    parallel_ranges(rows, [&](uint64_t r0, uint64_t r1) {
+        std::vector<float> tmp(cols);
+        for (uint64_t i = r0; i < r1; i++) {
+            const float *wr = w + i * cols;
+            float m = 0.0f;
+            if (sp) {
+                for (uint32_t j = 0; j < cols; j++) {
+                    const float v = wr[j] * sp[j];
+                    tmp[j] = v;
+                    m = std::max(m, std::fabs(v));
+                }
+            } else {
+                for (uint32_t j = 0; j < cols; j++) {
+                    tmp[j] = wr[j];
+                    m = std::max(m, std::fabs(wr[j]));
+                }
+            }
+            const float sc = m == 0.0f ? 1.0f : m / 127.0f;
+            row_scale[i] = sc;
+            int8_t *qr = q + i * cols;
+            for (uint32_t j = 0; j < cols; j++) {
+                float r = std::nearbyintf(tmp[j] / sc); // round-half-even in the default mode
+                r = std::min(127.0f, std::max(-127.0f, r));
+                int v = (int)r;
+                if (v <= thr && v >= -thr) v = 0;
+                qr[j] = (int8_t)v;
+            }
+        }
+    });
+    return DC_OK;
+}
+
+extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, uint64_t *max_blob_bytes,
+                                 uint64_t *n_chunks)
+{
+    if (!params_ok(params) || raw_bytes == 0) return DC_E_ARG;
+    const uint32_t C = params->chunk_bytes, S = params->n_streams;
+    const uint64_t nc = (raw_bytes + C - 1) / C;
+    // worst Huffman payload: header, 11 bits a byte, one partial word per stream, tail padding
+    const uint64_t per_chunk = align_up(128 + 4ull * S + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + 4ull * S, 16);
+    if (max_blob_bytes) *max_blob_bytes = nc * per_chunk;
+    if (n_chunks) *n_chunks = nc;
+    return DC_OK;
+}
+
+extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, const dc_params *params,
+                                  uint8_t *blob, uint64_t blob_cap, uint64_t *blob_bytes, dc_chunk *table,
+                                  uint64_t table_cap, uint64_t *n_chunks_out)
+{
+    if (!params_ok(params) || !src_i8 || raw_bytes == 0 || !blob_bytes || !n_chunks_out) return DC_E_ARG;
+    const uint8_t *src = reinterpret_cast<const uint8_t *>(src_i8);
+    const uint32_t C = params->chunk_bytes, S = params->n_streams;
+    const uint64_t nc = (raw_bytes + C - 1) / C;
+    const uint32_t policy = params->policy;
+    if (policy > DC_POLICY_BLOCK_LAST) return DC_E_ARG;
+    if (policy == DC_POLICY_RAW_MASK && !params->raw_mask) return DC_E_ARG;
+    if (policy == DC_POLICY_BLOCK_LAST && params->block_chunks == 0) return DC_E_ARG;
+    if (policy == DC_POLICY_RAW_FRACTION && !(params->raw_fraction >= 0.0f && params->raw_fraction <= 1.0f))
+        return DC_E_ARG;
+
+    // pass 1: codebook, per-stream bits and Huffman payload size of every chunk
+    std::vector<CodeBook> books(nc);
+    std::vector<uint64_t> bits(nc * S);
+    std::vector<uint32_t> huff(nc);
+    parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
+        uint32_t cnt[256];
+        for (uint64_t k = k0; k < k1; k++) {
+            const uint32_t raw = chunk_len(raw_bytes, C, k);
+            histogram256(src + k * C, raw, cnt);
+            make_codebook(cnt, books[k]);
+            stream_bits(src + k * C, raw, S, books[k], &bits[k * S]);
+            huff[k] = huff_payload_bytes(&bits[k * S], S);
+        }
+    });
+
+    // raw selection
+    std::vector<uint8_t> is_raw(nc, 0);
+    auto gain = [&](uint64_t k) { return (int64_t)chunk_len(raw_bytes, C, k) - (int64_t)huff[k]; };
+    switch (policy) {
+    case DC_POLICY_ALL_HUFF: break;
+    case DC_POLICY_AUTO:
+        for (uint64_t k = 0; k < nc; k++) is_raw[k] = gain(k) <= 0;
+        break;
+    case DC_POLICY_RAW_MASK:
+        for (uint64_t k = 0; k < nc; k++) is_raw[k] = params->raw_mask[k] != 0;
+        break;
+    case DC_POLICY_BLOCK_LAST:
+        for (uint64_t k = 0; k < nc; k++) is_raw[k] = (k % params->block_chunks) != params->block_chunks - 1;
+        break;
+    case DC_POLICY_RAW_FRACTION: {
+        uint64_t n_raw = (uint64_t)((double)params->raw_fraction * (double)nc + 0.5);
+        n_raw = std::min(n_raw, nc);
+        std::vector<uint64_t> idx(nc);
+        for (uint64_t k = 0; k < nc; k++) idx[k] = k;
+        std::stable_sort(idx.begin(), idx.end(), [&](uint64_t a, uint64_t b) { return gain(a) < gain(b); });
+        for (uint64_t r = 0; r < n_raw; r++) is_raw[idx[r]] = 1;
+        break;
+    }
+    }
+
+    // layout
+    uint64_t total = 0;
+    for (uint64_t k = 0; k < nc; k++)
+        total += is_raw[k] ? align_up(chunk_len(raw_bytes, C, k), 16) : huff[k];
+    *blob_bytes = total;
+    *n_chunks_out = nc;
+    if (!blob || !table || blob_cap < total || table_cap < nc) return DC_E_CAP;
+    uint64_t off = 0;
+    for (uint64_t k = 0; k < nc; k++) {
+        const uint32_t raw = chunk_len(raw_bytes, C, k);
+        table[k].off = off;
+        table[k].comp_bytes = is_raw[k] ? (uint32_t)align_up(raw, 16) : huff[k];
+        table[k].raw_bytes_flags = raw | (is_raw[k] ? DC_CHUNK_RAW : 0u);
+        off += table[k].comp_bytes;
+    }
+
+    // pass 2: emit
+    parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
+        for (uint64_t k = k0; k < k1; k++) {
+            const uint32_t raw = chunk_len(raw_bytes, C, k);
+            uint8_t *out = blob + table[k].off;
+            if (is_raw[k]) {
+                std::memcpy(out, src + k * C, raw);
+                std::memset(out + raw, 0, table[k].comp_bytes - raw);
+            } else {
+                write_huff_payload(src + k * C, raw, S, books[k], &bits[k * S], out, table[k].comp_bytes);
+            }
+        }
+    });
+    return DC_OK;
+}
+
+namespace {
+
+// Checks one Huffman payload completely: header, code completeness, stream extents, and that each
+// sub-stream decodes its symbol count inside its extent.
+bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
+{
+    const uint32_t hdr = 128 + 4 * S;
+    if (comp < hdr) return false;
+    uint8_t len[256];
+    uint32_t per_len[16] = {0};
+    int used = 0;
+    for (int v = 0; v < 256; v++) {
+        len[v] = (p[v >> 1] >> (4 * (v & 1))) & 15;
+        if (len[v] > DC_MAX_CODE_LEN) return false;
+        if (len[v]) { per_len[len[v]]++; used++; }
+    }
+    if (used == 0) return false;
+    uint32_t kraft = 0;
+    for (int l = 1; l <= DC_MAX_CODE_LEN; l++) kraft += per_len[l] << (DC_MAX_CODE_LEN - l);
+    if (used == 1) { if (per_len[1] != 1) return false; }
+    else if (kraft != (1u << DC_MAX_CODE_LEN)) return false;
+
+    // length of the code that starts with the next 11 stream bits
+    std::vector<uint8_t> peek_len(1u << DC_MAX_CODE_LEN, 0);
+    {
+        uint32_t next[16], code = 0;
+        per_len[0] = 0;
+        for (int l = 1; l <= DC_MAX_CODE_LEN; l++) { code = (code + per_len[l - 1]) << 1; next[l] = code; }
+        for (int v = 0; v < 256; v++) {
+            const int l = len[v];
+            if (!l) continue;
+            const uint32_t r = bit_reverse(next[l]++, l);
+            for (uint32_t i = r; i < (1u << DC_MAX_CODE_LEN); i += 1u << l) peek_len[i] = (uint8_t)l;
+        }
+    }
+    const uint32_t groups = (raw + 15) / 16;
+    uint32_t prev_off = hdr;
+    for (uint32_t j = 0; j < S; j++) {
+        uint32_t off;
+        std::memcpy(&off, p + 128 + 4 * j, 4);
+        if (off % 4 || off < prev_off || off > comp) return false;
+        if (j == 0 && off != hdr) return false;
+        prev_off = off;
+        uint32_t end = comp;
+        if (j + 1 < S) {
+            std::memcpy(&end, p + 128 + 4 * (j + 1), 4);
+            if (end > comp || end < off) return false;
+        }
+        uint64_t nsym = 0;
+        for (uint32_t g = j; g < groups; g += S) nsym += std::min(raw, 16 * g + 16) - 16 * g;
+        const uint64_t have = (uint64_t)(end - off) * 8;
+        uint64_t bit = 0;
+        for (uint64_t s = 0; s < nsym; s++) {
+            uint32_t window = 0;
+            for (int b = 0; b < DC_MAX_CODE_LEN; b++) {
+                const uint64_t i = bit + b;
+                if (i < have) window |= (uint32_t)((p[off + (i >> 3)] >> (i & 7)) & 1u) << b;
+            }
+            const int l = peek_len[window];
+            if (l == 0 || bit + l > have) return false;
+            bit += l;
+        }
+        if (j + 1 < S && (bit + 31) / 32 * 4 != end - off) return false;
+    }
+    return true;
+}
+
+} // namespace
+
+extern "C" int dc_validate(const uint8_t *blob, uint64_t blob_bytes, const dc_chunk *table, uint64_t n_chunks,
+                           const dc_params *params, uint64_t *bad_chunk)
+{
+    if (!params_ok(params) || !blob || !table || n_chunks == 0) return DC_E_ARG;
+    const uint32_t C = params->chunk_bytes, S = params->n_streams;
+    std::atomic<uint64_t> first_bad{UINT64_MAX};
+    parallel_ranges(n_chunks, [&](uint64_t k0, uint64_t k1) {
+        for (uint64_t k = k0; k < k1; k++) {
+            const dc_chunk &e = table[k];
+            const uint32_t raw = e.raw_bytes_flags & ~DC_CHUNK_RAW;
+            bool ok = raw >= 1 && raw <= C && (k + 1 == n_chunks || raw == C) && e.off % 16 == 0 &&
+                      e.comp_bytes % 16 == 0 && e.off <= blob_bytes && e.comp_bytes <= blob_bytes - e.off;
+            if (ok && k > 0) ok = e.off == table[k - 1].off + table[k - 1].comp_bytes;
+            if (ok && k == 0) ok = e.off == 0;
+            if (ok) {
+                if (e.raw_bytes_flags & DC_CHUNK_RAW) ok = e.comp_bytes == align_up(raw, 16);
+                else ok = huff_payload_ok(blob + e.off, e.comp_bytes, raw, S);
+            }
+            if (!ok) {
+                uint64_t cur = first_bad.load();
+                while (k < cur && !first_bad.compare_exchange_weak(cur, k)) {}
+            }
+        }
+    });
+    if (first_bad.load() != UINT64_MAX) {
+        if (bad_chunk) *bad_chunk = first_bad.load();
+        return DC_E_FORMAT;
+    }
+    return DC_OK;
+}

@@ -1,0 +1,175 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+Bar: decoded int8 bytes and bf16 dequantised values are bit-exact; fused GEMV outputs satisfy
+|y - y_ref| <= 1e-2*|y_ref| + 1e-2*rms(y_ref) against the fp64 reference.
+"""
+import numpy as np
+import pytest
+
+import oracle.codec as oc
+import oracle.quant as oq
+import paper_2502_15443_amd as dc
+import synth
+from tests.helpers import oracle_matrix, weightlike_bytes
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1).copy()).cuda()
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def gpu_decode(blob, table, params, n, fill=0xAB):
+    blob_d, table_d = dev(blob), dev(table)
+    dst = torch.full((n,), fill, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, blob.size, table_d, len(table), params, dst, n, stream())
+    torch.cuda.synchronize()
+    return dst.cpu().numpy()
+
+
+@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("n,C", [(3 * 65536, 65536), (5 * 16384 + 777, 16384), (7 * 4096 + 4095, 4096),
+                                 (65536 + 16, 65536), (100, 65536), (1, 4096), (9 * 2048 + 1, 2048),
+                                 (2 * 262144 + 12345, 262144)])
+def test_decode_matches_oracle_bytes(S, n, C):
+    print(f"case S={S} n={n} C={C}", flush=True)
+    data = weightlike_bytes(n, 1000 + n % 977 + S)
+    c = oc.compress(data, C, S)  # the oracle's blob
+    out = gpu_decode(c.blob, c.table, dc.Params(C, S), n)
+    assert np.array_equal(out, data)
+    assert np.array_equal(out, oc.decompress(c.blob, c.table, C, S, n))
+
+
+@pytest.mark.parametrize("S", [32, 64, 128])
+def test_decode_degenerate_chunks(S):
+    print(f"case degenerate S={S}", flush=True)
+    C = 4096
+    r = np.random.default_rng(0)
+    skew = np.clip(np.rint(r.standard_cauchy(C) * 2), -127, 127).astype(np.int8).view(np.uint8)  # 11-bit codes
+    data = np.concatenate([np.zeros(C, np.uint8), np.full(C, 0x81, np.uint8), r.integers(0, 256, C, dtype=np.uint8),
+                           np.tile(np.array([3, 250], np.uint8), C // 2), np.arange(C, dtype=np.uint32).astype(np.uint8),
+                           skew, np.array([7], np.uint8)])
+    for policy in (oc.ALL_HUFF, oc.AUTO):
+        c = oc.compress(data, C, S, policy)
+        out = gpu_decode(c.blob, c.table, dc.Params(C, S), data.size)
+        assert np.array_equal(out, data)
+
+
+@pytest.mark.parametrize("S", [32, 64])
+@pytest.mark.parametrize("f", [0.0, 0.25, 0.5, 0.75, 1.0])
+def test_decode_with_raw_fraction(S, f):
+    print(f"case raw fraction S={S} f={f}", flush=True)
+    C = 16384
+    data = weightlike_bytes(41 * C + 333, 17)
+    p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, f)
+    blob, table = dc.compress_chunks(data, p)  # the library's compressor ...
+    c = oc.compress(data, C, S, oc.RAW_FRACTION, f)
+    assert np.array_equal(blob, c.blob) and np.array_equal(table, c.table)  # ... equals the oracle's
+    assert np.array_equal(gpu_decode(blob, table, p, data.size), data)
+
+
+def test_decode_block_last_policy():
+    C, S = 8192, 32
+    data = weightlike_bytes(23 * C, 19)
+    c = oc.compress(data, C, S, oc.BLOCK_LAST, block=5)
+    assert np.array_equal(gpu_decode(c.blob, c.table, dc.Params(C, S), data.size), data)
+
+
+def test_destination_untouched_beyond_decoded_bytes():
+    C, S, n = 4096, 32, 3 * 4096 + 100
+    data = weightlike_bytes(n, 23)
+    c = oc.compress(data, C, S)
+    blob_d, table_d = dev(c.blob), dev(c.table)
+    dst = torch.full((4 * C,), 0x5A, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, c.blob.size, table_d, 4, dc.Params(C, S), dst, 4 * C, stream())
+    torch.cuda.synchronize()
+    out = dst.cpu().numpy()
+    assert np.array_equal(out[:n], data) and (out[n:] == 0x5A).all()
+
+
+def test_host_argument_checks_on_device_entry_points():
+    C, S, n = 4096, 32, 2 * 4096
+    data = weightlike_bytes(n, 29)
+    c = oc.compress(data, C, S)
+    blob_d, table_d = dev(c.blob), dev(c.table)
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dc.DCError) as e:
+        dc.decompress_chunks(blob_d, c.blob.size, table_d, 2, dc.Params(C, S), dst, C, stream())
+    assert e.value.code == -2
+    with pytest.raises(dc.DCError) as e:
+        dc.decompress_chunks(blob_d, c.blob.size, table_d, 2, dc.Params(C, 48), dst, n, stream())
+    assert e.value.code == -1
+    with pytest.raises(dc.DCError) as e:
+        dc.decompress_chunks(blob_d.data_ptr() + 4, c.blob.size - 4, table_d, 2, dc.Params(C, S), dst, n, stream())
+    assert e.value.code == -1
+
+
+# ------------------------------------------------------------------ matrices: configs at reduced and full size
+
+def matrix_case(rows, cols, seed, rescale, C, S):
+    q, scale = oracle_matrix(rows, cols, seed, rescale)
+    c = oc.compress(q, C, S, threads=8)
+    return q, scale, c
+
+
+@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("rows,cols,rescale", [(160, 1024, False), (96, 2752, True), (33, 5120, False)])
+def test_dequant_bf16_bit_exact(S, rows, cols, rescale):
+    print(f"case bf16 S={S} {rows}x{cols}", flush=True)
+    C = 16384
+    q, scale, c = matrix_case(rows, cols, synth.matrix_seed(1, 4), rescale, C, S)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    out = torch.zeros(rows * cols, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, out,
+                               rows * cols, stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16).reshape(rows, cols)
+    assert np.array_equal(got, oq.dequant_bf16(q, scale))
+
+
+def gemv_check(y, y_ref):
+    rms = float(np.sqrt(np.mean(y_ref ** 2)))
+    err = np.abs(y.astype(np.float64) - y_ref)
+    assert (err <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all(), float(err.max())
+    return float(err.max() / np.abs(y_ref).max())
+
+
+@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("rows,cols,C,f", [(160, 1024, 16384, 0.0), (50, 5120, 65536, 0.0), (37, 13824, 65536, 0.3),
+                                           (64, 2752, 16384, 0.5)])
+def test_gemv_within_tolerance(S, rows, cols, C, f):
+    print(f"case gemv S={S} {rows}x{cols} C={C} f={f}", flush=True)
+    seed = synth.matrix_seed(2, 5)
+    q, scale = oracle_matrix(rows, cols, seed, False)
+    c = oc.compress(q, C, S, oc.RAW_FRACTION, f)
+    x = synth.gen_activation_bf16(cols, seed)
+    y_ref = oq.gemv_ref(q, scale, x)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    x_d = torch.from_numpy(x.view(np.int16)).cuda()
+    y32 = torch.full((rows,), 7.0, dtype=torch.float32, device="cuda")  # the call must zero it itself
+    y16 = torch.zeros(rows, dtype=torch.int16, device="cuda")
+    dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, x_d, y32, y16,
+                       stream())
+    torch.cuda.synchronize()
+    norm_err = gemv_check(y32.cpu().numpy(), y_ref)
+    assert norm_err < 1e-4  # fp32 accumulation: far inside the 1e-2 bar
+    y16f = oq.bf16_to_f64(y16.cpu().numpy().view(np.uint16))
+    gemv_check(y16f, y_ref)
+    assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
+
+
+def test_config1_full_size_bit_exact_and_ratio():
+    """4096x4096, 64 KiB chunks, 32 sub-streams, all chunks Huffman coded."""
+    q, scale = oracle_matrix(4096, 4096, synth.matrix_seed(0, 0), False)
+    p = dc.Params(65536, 32)
+    blob, table = dc.compress_chunks(q, p)
+    c = oc.compress(q, 65536, 32, threads=8)
+    assert np.array_equal(blob, c.blob) and np.array_equal(table, c.table)
+    assert q.size / (blob.size + table.nbytes) == c.ratio
+    out = gpu_decode(blob, table, p, q.size)
+    assert np.array_equal(out, q.view(np.uint8).ravel())

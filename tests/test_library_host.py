@@ -1,0 +1,195 @@
+"""CPU tests of the library: exported symbols, host-side quantiser / compressor / validator against
+the oracle.  No GPU call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle.codec as oc
+import oracle.quant as oq
+import paper_2502_15443_amd as dc
+import synth
+from tests.helpers import weightlike_bytes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "dc.h")).read()
+    names = set(re.findall(r"\b(dc_[a-z0-9_]+)\s*\(", header))
+    assert {"dc_compress_chunks", "dc_decompress_chunks", "dc_decompress_dequant_bf16",
+            "dc_decompress_gemv", "dc_quantize_rows", "dc_validate"} <= names
+    lib = ctypes.CDLL(dc.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert "gfx950" in dc.version()
+
+
+@pytest.mark.parametrize("rescale", [False, True])
+def test_quantize_rows_matches_oracle_bit_for_bit(rescale):
+    rows, cols, seed = 192, 1024, synth.matrix_seed(3, 2)
+    w = synth.gen_weight(rows, cols, seed)
+    w[5] = 0  # an all-zero row
+    a = synth.gen_act_absmax(cols, seed) if rescale else None
+    q, rs, cs = dc.quantize_rows(w, a, 0.5, 1)
+    w2 = oq.rescale(w, oq.channel_scale(a, 0.5)) if rescale else w
+    q_ref, rs_ref = oq.quantise_rows(w2)
+    q_ref = oq.prune(q_ref)
+    assert np.array_equal(q, q_ref) and np.array_equal(rs, rs_ref)
+    if rescale:
+        assert np.array_equal(cs, oq.channel_scale(a, 0.5))
+    else:
+        assert (cs == 1).all()
+    q0, _, _ = dc.quantize_rows(w, a, 0.5, 0)  # no pruning
+    assert np.array_equal(q0, oq.quantise_rows(w2)[0])
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.3, 1.0])
+def test_quantize_rows_other_exponents(alpha):
+    rows, cols, seed = 64, 512, 99
+    w = synth.gen_weight(rows, cols, seed)
+    a = synth.gen_act_absmax(cols, seed)
+    q, rs, cs = dc.quantize_rows(w, a, alpha, 1)
+    s = oq.channel_scale(a, alpha)
+    q_ref, rs_ref = oq.quantise_rows(oq.rescale(w, s))
+    assert np.array_equal(cs, s) and np.array_equal(q, oq.prune(q_ref)) and np.array_equal(rs, rs_ref)
+
+
+@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("n,C", [(5 * 16384 + 777, 16384), (3 * 65536, 65536), (100, 65536), (65536 + 16, 65536),
+                                 (7 * 4096 + 4095, 4096)])
+def test_compress_is_byte_identical_to_oracle(S, n, C):
+    data = weightlike_bytes(n, n + S)
+    p = dc.Params(C, S)
+    blob, table = dc.compress_chunks(data, p)
+    c = oc.compress(data, C, S)
+    assert np.array_equal(table, c.table)
+    assert np.array_equal(blob, c.blob)
+    dc.validate(blob, table, p)
+    assert np.array_equal(oc.decompress(blob, table, C, S, n), data)
+
+
+def test_compress_degenerate_chunks():
+    C, S = 4096, 32
+    r = np.random.default_rng(0)
+    data = np.concatenate([np.zeros(C, np.uint8), np.full(C, 0x81, np.uint8), r.integers(0, 256, C, dtype=np.uint8),
+                           np.tile(np.array([3, 250], np.uint8), C // 2), np.arange(C, dtype=np.uint32).astype(np.uint8),
+                           np.array([7], np.uint8)])
+    for policy in (dc.POLICY_ALL_HUFF, dc.POLICY_AUTO):
+        p = dc.Params(C, S, policy)
+        blob, table = dc.compress_chunks(data, p)
+        c = oc.compress(data, C, S, policy)
+        assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob)
+        dc.validate(blob, table, p)
+
+
+@pytest.mark.parametrize("policy,kw", [(dc.POLICY_RAW_FRACTION, dict(raw_fraction=0.0)),
+                                       (dc.POLICY_RAW_FRACTION, dict(raw_fraction=0.25)),
+                                       (dc.POLICY_RAW_FRACTION, dict(raw_fraction=0.5)),
+                                       (dc.POLICY_RAW_FRACTION, dict(raw_fraction=0.75)),
+                                       (dc.POLICY_RAW_FRACTION, dict(raw_fraction=1.0)),
+                                       (dc.POLICY_AUTO, {}), (dc.POLICY_BLOCK_LAST, dict(block_chunks=5)),
+                                       (dc.POLICY_BLOCK_LAST, dict(block_chunks=1))])
+def test_raw_policies_match_oracle(policy, kw):
+    C, S = 8192, 32
+    data = weightlike_bytes(37 * C + 100, 5)
+    p = dc.Params(C, S, policy, **kw)
+    blob, table = dc.compress_chunks(data, p)
+    c = oc.compress(data, C, S, policy, raw_fraction=kw.get("raw_fraction", 0.0), block=kw.get("block_chunks", 0))
+    assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob)
+    ratio = data.size / (blob.size + table.nbytes)
+    assert abs(ratio - c.ratio) < 1e-15  # compression ratio equal to the oracle's
+    dc.validate(blob, table, p)
+
+
+def test_raw_mask_policy():
+    C, S = 4096, 64
+    data = weightlike_bytes(10 * C, 6)
+    mask = np.array([1, 0, 0, 1, 1, 0, 1, 0, 0, 1], dtype=np.uint8)
+    p = dc.Params(C, S, dc.POLICY_RAW_MASK, raw_mask=mask)
+    blob, table = dc.compress_chunks(data, p)
+    c = oc.compress(data, C, S, oc.RAW_MASK, mask=mask)
+    assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob)
+
+
+def test_result_independent_of_thread_count():
+    data = weightlike_bytes(20 * 16384 + 5, 7)
+    p = dc.Params(16384, 32, dc.POLICY_RAW_FRACTION, 0.3)
+    prev = dc.set_num_threads(1)
+    try:
+        b1, t1 = dc.compress_chunks(data, p)
+        dc.set_num_threads(5)
+        b5, t5 = dc.compress_chunks(data, p)
+    finally:
+        dc.set_num_threads(prev)
+    assert np.array_equal(b1, b5) and np.array_equal(t1, t5)
+
+
+def test_argument_errors():
+    data = weightlike_bytes(4096, 1)
+    for bad in (dc.Params(1000, 32), dc.Params(4096, 33), dc.Params(1 << 21, 32), dc.Params(4096, 32, 9),
+                dc.Params(4096, 32, dc.POLICY_RAW_FRACTION, 1.5), dc.Params(4096, 32, dc.POLICY_BLOCK_LAST),
+                dc.Params(4096, 32, dc.POLICY_RAW_MASK)):
+        with pytest.raises(dc.DCError) as e:
+            dc.compress_chunks(data, bad)
+        assert e.value.code == -1
+
+
+def test_compress_reports_required_capacity():
+    lib = ctypes.CDLL(dc.lib_path())
+    data = weightlike_bytes(3 * 4096, 2)
+    p = dc.Params(4096, 32)
+    blob, table = dc.compress_chunks(data, p)
+    used, n = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    small = np.zeros(16, np.uint8)
+    tab = np.zeros(3, dc.CHUNK_DTYPE)
+    cp = p._c()
+    rc = lib.dc_compress_chunks(ctypes.c_void_p(data.ctypes.data), ctypes.c_uint64(data.size), ctypes.byref(cp),
+                                ctypes.c_void_p(small.ctypes.data), ctypes.c_uint64(16), ctypes.byref(used),
+                                ctypes.c_void_p(tab.ctypes.data), ctypes.c_uint64(3), ctypes.byref(n))
+    assert rc == -2 and used.value == blob.size and n.value == 3
+
+
+def test_validate_catches_corruption():
+    C, S = 4096, 32
+    data = weightlike_bytes(6 * C + 9, 8)
+    p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, 0.34)
+    blob, table = dc.compress_chunks(data, p)
+    dc.validate(blob, table, p)
+    huff = [k for k in range(len(table)) if not table["raw_bytes_flags"][k] & dc.CHUNK_RAW]
+    k = huff[1]
+    o = int(table["off"][k])
+
+    def expect_bad(b, t, chunk):
+        with pytest.raises(dc.DCError) as e:
+            dc.validate(b, t, p)
+        assert e.value.code == -3 and f"chunk {chunk})" in str(e.value)
+
+    b = blob.copy(); b[o] = 0xFF  # code lengths 15
+    expect_bad(b, table, k)
+    b = blob.copy(); b[o + 3] ^= 0x01  # Kraft sum no longer 1
+    expect_bad(b, table, k)
+    b = blob.copy(); b[o + 128 + 8:o + 128 + 12] = np.frombuffer(np.uint32(1 << 24).tobytes(), np.uint8)  # offset outside
+    expect_bad(b, table, k)
+    b = blob.copy(); b[o + 128 + 8] ^= 0x02  # misaligned offset
+    expect_bad(b, table, k)
+    t = table.copy(); t["raw_bytes_flags"][2] = (t["raw_bytes_flags"][2] & dc.CHUNK_RAW) | (C + 16)  # too long
+    expect_bad(blob, t, 2)
+    t = table.copy(); t["off"][3] += 16  # payloads no longer back to back
+    expect_bad(blob, t, 3)
+    t = table.copy(); t["comp_bytes"][-1] += 1 << 20  # beyond the blob
+    expect_bad(blob, t, len(t) - 1)
+    expect_bad(blob[:o + 64].copy(), table, k)  # truncated blob
+
+
+def test_compress_bound_holds_on_worst_case():
+    C, S = 4096, 128
+    r = np.random.default_rng(3)
+    # skewed enough to get 11-bit codes, noisy enough to use many of them
+    data = np.clip(np.rint(r.standard_cauchy(8 * C) * 2), -127, 127).astype(np.int8).view(np.uint8)
+    p = dc.Params(C, S)
+    cap, nc = dc.compress_bound(data.size, p)
+    blob, table = dc.compress_chunks(data, p)
+    assert nc == 8 and blob.size <= cap
