@@ -100,6 +100,8 @@ typedef struct {
 const char *dc_version(void);
 /* Name of a DC_E_* code (static storage). */
 const char *dc_strerror(int code);
+/* Text of the HIP status behind the calling thread's most recent DC_E_HIP (static storage). */
+const char *dc_last_hip_error(void);
 /* Host worker threads used by dc_quantize_rows / dc_compress_chunks / dc_validate; 0 = all cores.
  * Returns the previous setting. */
 int dc_set_num_threads(int n);

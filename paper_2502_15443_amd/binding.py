@@ -59,12 +59,20 @@ def _load():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2502_15443_amd.build` "
             "(there is no fallback path)")
+    # Device memory and streams come from PyTorch, so the library must run on the HIP runtime that
+    # PyTorch loaded: bring PyTorch in first so that the shared runtime is resolved to its copy.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(_LIB_PATH)
     vp, u64, u32, i32 = C.c_void_p, C.c_uint64, C.c_uint32, C.c_int
     pp = C.POINTER(_CParams)
     pu64 = C.POINTER(C.c_uint64)
     L.dc_version.restype = C.c_char_p
     L.dc_version.argtypes = []
+    L.dc_last_hip_error.restype = C.c_char_p
+    L.dc_last_hip_error.argtypes = []
     L.dc_strerror.restype = C.c_char_p
     L.dc_strerror.argtypes = [i32]
     L.dc_set_num_threads.restype = i32
@@ -92,7 +100,10 @@ _L = _load()
 
 
 def version_safe_strerror(code: int) -> str:
-    return _L.dc_strerror(code).decode()
+    msg = _L.dc_strerror(code).decode()
+    if code == -4:
+        msg += " (" + _L.dc_last_hip_error().decode() + ")"
+    return msg
 
 
 def version() -> str:

@@ -430,6 +430,15 @@ __global__ __launch_bounds__(256) void dc_copy_kernel(const u32x4 *__restrict__ 
         __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+// Records the launch status of the calling thread; DC_E_HIP callers can ask dc_last_hip_error().
+int launch_status()
+{
+    g_last_hip_error = hipGetLastError();
+    return g_last_hip_error == hipSuccess ? DC_OK : DC_E_HIP;
+}
+
 bool decode_params_ok(const dc_params *p)
 {
     if (!p) return false;
@@ -448,7 +457,7 @@ template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream
     } else {
         hipLaunchKernelGGL((dc_decode_kernel<128, MODE>), dim3((uint32_t)a.n_chunks), dim3(64), 0, stream, a);
     }
-    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+    return launch_status();
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -528,8 +537,10 @@ extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, 
     if (rc != DC_OK) return rc;
     hipLaunchKernelGGL(dc_gemv_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, y_accum_dev, y_bf16_dev,
                        row_scale_dev, x_bf16_dev, rows, cols);
-    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+    return launch_status();
 }
+
+extern "C" const char *dc_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 extern "C" int dc_device_copy(const void *src_dev, void *dst_dev, uint64_t bytes, void *hip_stream)
 {
@@ -539,5 +550,5 @@ extern "C" int dc_device_copy(const void *src_dev, void *dst_dev, uint64_t bytes
     if (blocks > 256ull * 32) blocks = 256ull * 32;
     hipLaunchKernelGGL(dc_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<const u32x4 *>(src_dev), static_cast<u32x4 *>(dst_dev), n16);
-    return hipGetLastError() == hipSuccess ? DC_OK : DC_E_HIP;
+    return launch_status();
 }
