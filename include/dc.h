@@ -33,6 +33,9 @@
  *                        bit 31 set = payload is the raw bytes (DC_CHUNK_RAW)
  *     chunk k decodes to bytes [k*chunk_bytes, k*chunk_bytes + raw_bytes) of the
  *     destination; only the last chunk may be shorter than chunk_bytes.
+ *   blob                 the payloads back to back in chunk order, followed by DC_BLOB_TAIL_BYTES
+ *                        zero bytes (the decoder fetches sub-streams ahead in 32-byte blocks and
+ *                        must never need bytes past the end of the blob); blob_bytes counts them
  *   raw payload          the bytes, zero padded to a multiple of 16
  *   Huffman payload
  *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
@@ -70,6 +73,7 @@ extern "C" {
 #define DC_CHUNK_RAW 0x80000000u
 #define DC_MAX_CODE_LEN 11
 #define DC_MAX_CHUNK_BYTES (1u << 20)
+#define DC_BLOB_TAIL_BYTES 64
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */

@@ -19,6 +19,9 @@
  *     u64 off          payload offset in the blob, multiple of 16
  *     u32 comp_bytes   payload size including padding, multiple of 16
  *     u32 raw_bytes | RAW<<31
+ *   blob              the payloads back to back in chunk order, then 64 zero
+ *                     bytes (so that a reader fetching ahead in 32-byte blocks
+ *                     never needs bytes past the end of the blob)
  *   raw payload       raw_bytes bytes, zero padded to 16
  *   Huffman payload
  *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
@@ -47,6 +50,7 @@
 #define ORC_E_FORMAT (-3)
 
 #define ORC_RAW_FLAG 0x80000000u
+#define ORC_BLOB_TAIL 64
 
 enum { ORC_ALL_HUFF = 0, ORC_AUTO = 1, ORC_RAW_FRACTION = 2, ORC_RAW_MASK = 3, ORC_BLOCK_LAST = 4 };
 
@@ -431,7 +435,8 @@ int orc_select_raw(const uint32_t *huff_bytes, uint64_t n, uint32_t C, uint64_t 
     return ORC_E_ARG;
 }
 
-/* Offsets and sizes of every payload, laid out back to back.  Returns the blob size. */
+/* Offsets and sizes of every payload, laid out back to back.  Returns the blob size, which
+ * includes the 64 zero bytes that close the blob. */
 uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t n, uint32_t C,
                     uint64_t n_chunks, orc_chunk *table)
 {
@@ -448,7 +453,7 @@ uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t 
         }
         off += table[k].comp_bytes;
     }
-    return off;
+    return off + ORC_BLOB_TAIL;
 }
 
 /* Write the payloads of chunks k0 <= k < k1 at the offsets the table gives. */

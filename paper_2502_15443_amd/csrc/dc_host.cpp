@@ -297,7 +297,7 @@ extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, ui
     const uint64_t nc = (raw_bytes + C - 1) / C;
     // worst Huffman payload: header, 11 bits a byte, one partial word per stream, tail padding
     const uint64_t per_chunk = align_up(128 + 4ull * S + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + 4ull * S, 16);
-    if (max_blob_bytes) *max_blob_bytes = nc * per_chunk;
+    if (max_blob_bytes) *max_blob_bytes = nc * per_chunk + DC_BLOB_TAIL_BYTES;
     if (n_chunks) *n_chunks = nc;
     return DC_OK;
 }
@@ -361,6 +361,7 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
     uint64_t total = 0;
     for (uint64_t k = 0; k < nc; k++)
         total += is_raw[k] ? align_up(chunk_len(raw_bytes, C, k), 16) : huff[k];
+    total += DC_BLOB_TAIL_BYTES;
     *blob_bytes = total;
     *n_chunks_out = nc;
     if (!blob || !table || blob_cap < total || table_cap < nc) return DC_E_CAP;
@@ -372,6 +373,8 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
         table[k].raw_bytes_flags = raw | (is_raw[k] ? DC_CHUNK_RAW : 0u);
         off += table[k].comp_bytes;
     }
+
+    std::memset(blob + off, 0, DC_BLOB_TAIL_BYTES);
 
     // pass 2: emit
     parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
@@ -463,6 +466,15 @@ extern "C" int dc_validate(const uint8_t *blob, uint64_t blob_bytes, const dc_ch
 {
     if (!params_ok(params) || !blob || !table || n_chunks == 0) return DC_E_ARG;
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
+    {
+        // the blob must extend DC_BLOB_TAIL_BYTES beyond the last payload
+        const dc_chunk &last = table[n_chunks - 1];
+        if (last.off > blob_bytes || last.comp_bytes > blob_bytes - last.off ||
+            blob_bytes - last.off - last.comp_bytes < DC_BLOB_TAIL_BYTES) {
+            if (bad_chunk) *bad_chunk = n_chunks - 1;
+            return DC_E_FORMAT;
+        }
+    }
     std::atomic<uint64_t> first_bad{UINT64_MAX};
     parallel_ranges(n_chunks, [&](uint64_t k0, uint64_t k1) {
         for (uint64_t k = k0; k < k1; k++) {

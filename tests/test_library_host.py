@@ -181,7 +181,8 @@ def test_validate_catches_corruption():
     expect_bad(blob, t, 3)
     t = table.copy(); t["comp_bytes"][-1] += 1 << 20  # beyond the blob
     expect_bad(blob, t, len(t) - 1)
-    expect_bad(blob[:o + 64].copy(), table, k)  # truncated blob
+    expect_bad(blob[:o + 64].copy(), table, len(table) - 1)  # truncated blob
+    expect_bad(blob[:-1].copy(), table, len(table) - 1)  # closing 64 zero bytes incomplete
 
 
 def test_compress_bound_holds_on_worst_case():

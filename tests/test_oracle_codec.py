@@ -297,7 +297,8 @@ def test_whole_buffer_round_trip_ragged_tail():
     assert (c.table["off"] % 16 == 0).all() and (c.table["comp_bytes"] % 16 == 0).all()
     assert int(c.table["raw_bytes_flags"][-1]) == 777
     assert (np.diff(c.table["off"].astype(np.int64)) == c.table["comp_bytes"][:-1]).all()
-    assert c.blob.size == int(c.table["off"][-1]) + int(c.table["comp_bytes"][-1])
+    assert c.blob.size == int(c.table["off"][-1]) + int(c.table["comp_bytes"][-1]) + 64
+    assert not c.blob[-64:].any()  # the blob closes with 64 zero bytes
     out = oc.decompress(c.blob, c.table, 16384, 32, data.size)
     assert (out == data).all()
     out2 = oc.decompress(c.blob, c.table, 16384, 32, data.size, threads=3)
@@ -317,10 +318,10 @@ def test_raw_fraction_picks_lowest_gain_and_ratio_closed_form(f):
     want = np.zeros(64, dtype=bool)
     want[np.argsort(gain, kind="stable")[:n_raw]] = True  # lowest gain, lower index first among equals
     assert (is_raw == want).all()
-    size = int(np.where(is_raw, C, allh.table["comp_bytes"]).sum()) + 16 * 64
+    size = int(np.where(is_raw, C, allh.table["comp_bytes"]).sum()) + 16 * 64 + 64  # payloads, table, blob tail
     assert abs(c.ratio - data.size / size) < 1e-12
     if f == 1.0:
-        assert abs(c.ratio - C / (C + 16)) < 1e-12
+        assert abs(c.ratio - 64 * C / (64 * (C + 16) + 64)) < 1e-12
     assert (oc.decompress(c.blob, c.table, C, S, data.size) == data).all()
     for k in np.nonzero(is_raw)[0]:  # a raw payload is the bytes themselves
         o = int(c.table["off"][k])
