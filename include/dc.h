@@ -92,7 +92,7 @@ typedef struct {
 
 typedef struct {
     uint32_t chunk_bytes;   /* decoded bytes per chunk: multiple of 16, 16..DC_MAX_CHUNK_BYTES */
-    uint32_t n_streams;     /* S: sub-streams per chunk, one of 32, 64, 128 */
+    uint32_t n_streams;     /* S: sub-streams per chunk, one of 32, 64, 128, 256 */
     uint32_t policy;        /* DC_POLICY_*; only the compressor reads it */
     float raw_fraction;     /* DC_POLICY_RAW_FRACTION: share of chunks kept raw, 0..1 */
     uint32_t block_chunks;  /* DC_POLICY_BLOCK_LAST: chunks per block, >= 1 */

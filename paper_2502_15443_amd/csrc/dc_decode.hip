@@ -4,11 +4,13 @@
 // memory are decompressed by the GPU into a decompression buffer; "Speed Adaptive Partial
 // Compression": some chunks are raw and only need a copy.  The stored format is in include/dc.h.
 //
-// Work decomposition: one wavefront owns 64 sub-streams.  With S = 32 sub-streams per chunk a wave
-// owns two chunks (lanes 0-31 / 32-63), with S = 64 one chunk, with S = 128 one chunk and every lane
-// owns two sub-streams.  The decode table of a chunk (2048 x u16: symbol << 8 | length, indexed by
-// the next 11 stream bits) lives in LDS.  A lane packs 16 decoded bytes and writes them with one
-// 128-bit store; the lanes of a chunk write S*16 contiguous bytes per round.
+// Work decomposition: a lane owns one sub-stream, a workgroup owns one chunk (S/64 wavefronts; with
+// S = 32 one wavefront owns two chunks, lanes 0-31 / 32-63).  Per chunk the LDS holds the decode
+// table (2048 x u16: symbol << 8 | length, indexed by the next 11 stream bits).  Per wavefront the
+// LDS holds a ring of 16 stream words per lane: the bitstream is fetched from memory in 32-byte
+// blocks, one block ahead of the ring, so that the per-symbol loop never waits on memory.  A lane
+// packs 16 decoded bytes and writes them with one 128-bit store; the lanes of a chunk write S*16
+// contiguous bytes per round.
 #include <hip/hip_runtime.h>
 
 #include "dc.h"
@@ -17,13 +19,15 @@ namespace {
 
 constexpr int kPeekBits = DC_MAX_CODE_LEN;
 constexpr int kTableEntries = 1 << kPeekBits;
+constexpr int kRingWords = 16;                 // per lane
+constexpr uint32_t kBlockBytes = 32;           // bitstream fetch granule
+constexpr uint32_t kBlockWords = kBlockBytes / 4;
 
 enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// 128-bit streaming accesses: data that is touched once should not displace the bitstream lines
-// that the lanes keep re-reading from L2.
+// 128-bit streaming accesses for data that is touched once.
 __device__ __forceinline__ void store16_stream(void *p, uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
     u32x4 v = {a, b, c, d};
@@ -35,10 +39,12 @@ __device__ __forceinline__ u32x4 load16_stream(const void *p)
 }
 
 template <int S> struct Geometry {
-    static constexpr int kLanesPerChunk = S >= 64 ? 64 : S;
-    static constexpr int kChunksPerWave = 64 / kLanesPerChunk;
-    static constexpr int kStreamsPerLane = S / kLanesPerChunk;
-    static constexpr int kSymbolsPerLane = 256 / kLanesPerChunk; // header values handled by a lane
+    static constexpr int kLanesPerChunk = S < 64 ? S : 64;       // lanes of one wave that serve a chunk
+    static constexpr int kChunksPerWave = 64 / kLanesPerChunk;   // 2 when S = 32
+    static constexpr int kWaves = S <= 64 ? 1 : S / 64;          // wavefronts of the workgroup
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kThreadsPerChunk = S < 64 ? S : kThreads;
+    static constexpr int kSymbolsPerLane = 256 / kLanesPerChunk; // header values a lane handles in the table build
 };
 
 struct DecodeArgs {
@@ -56,50 +62,100 @@ struct DecodeArgs {
     float *y_accum;         // kModeGemv
 };
 
-// One sub-stream as a lane sees it: a 64-bit LSB-first bit buffer, one prefetched word, and the
-// index of the next word to fetch (relative to the chunk payload, clamped to the blob).
-struct BitReader {
-    uint64_t buf;
+// One sub-stream as its lane sees it.  Stream words travel memory -> (blk0, blk1) -> LDS ring -> next
+// -> buf.  Ring word j of the lane sits at ring[(j % 16) * 64 + lane], so the lanes of a wave never
+// collide on a bank.  rdw and wrw count ring words taken and put, times 256 (the byte stride between
+// two ring words of a lane).
+struct Stream {
+    uint64_t buf;   // LSB-first bit buffer
     uint32_t avail; // valid bits in buf; only the low 8 bits are meaningful between refills
-    uint32_t next;
-    uint32_t word;
-
-    __device__ __forceinline__ uint32_t fetch(const uint32_t *__restrict__ payload, uint32_t max_word)
-    {
-        const uint32_t w = word < max_word ? word : max_word;
-        word++;
-        return payload[w];
-    }
-    __device__ __forceinline__ void init(const uint32_t *__restrict__ payload, uint32_t first, uint32_t max_word)
-    {
-        word = first;
-        const uint32_t lo = fetch(payload, max_word);
-        const uint32_t hi = fetch(payload, max_word);
-        buf = (uint64_t)lo | ((uint64_t)hi << 32);
-        next = fetch(payload, max_word);
-        avail = 64;
-    }
-    // After this at least 33 bits are valid: enough for three codes of 11 bits.
-    __device__ __forceinline__ void refill(const uint32_t *__restrict__ payload, uint32_t max_word)
-    {
-        uint32_t a = avail & 0xFFu;
-        if (a <= 32) {
-            buf |= (uint64_t)next << a;
-            a += 32;
-            next = fetch(payload, max_word);
-        }
-        avail = a;
-    }
-    // Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount
-    // and `avail` is only read through its low 8 bits, so the entry is used unmasked for both.
-    __device__ __forceinline__ uint32_t symbol(const uint16_t *__restrict__ tbl)
-    {
-        const uint32_t e = tbl[(uint32_t)buf & (kTableEntries - 1)];
-        buf >>= (e & 63u);
-        avail -= e;
-        return e;
-    }
+    uint32_t next;  // the word that follows buf
+    uint32_t rdw;
+    uint32_t wrw;
+    uint32_t base;  // payload byte offset of ring word 0, multiple of 32
+    u32x4 blk0, blk1; // block in flight: payload bytes [base + wrw/64, +32)
 };
+
+__device__ __forceinline__ void fetch_block(Stream &s, const uint8_t *__restrict__ payload8, uint32_t max_off)
+{
+    uint32_t off = s.base + (s.wrw >> 6);
+    off = off < max_off ? off : max_off;
+    s.blk0 = *reinterpret_cast<const u32x4 *>(payload8 + off);
+    s.blk1 = *reinterpret_cast<const u32x4 *>(payload8 + off + 16);
+}
+
+__device__ __forceinline__ void push_block(Stream &s, uint32_t *__restrict__ ring_lane)
+{
+    uint32_t *w = ring_lane + ((s.wrw & 0xF00u) >> 2);
+    w[0] = s.blk0[0];
+    w[64] = s.blk0[1];
+    w[128] = s.blk0[2];
+    w[192] = s.blk0[3];
+    w[256] = s.blk1[0];
+    w[320] = s.blk1[1];
+    w[384] = s.blk1[2];
+    w[448] = s.blk1[3];
+    s.wrw += kBlockWords * 256;
+}
+
+__device__ __forceinline__ uint32_t ring_pop(Stream &s, const uint32_t *__restrict__ ring_lane)
+{
+    const uint32_t w = ring_lane[(s.rdw & 0xF00u) >> 2];
+    s.rdw += 256;
+    return w;
+}
+
+// Start of a sub-stream at payload byte `off` (multiple of 4): two blocks into the ring, a third in flight.
+__device__ __forceinline__ void stream_init(Stream &s, uint32_t off, const uint8_t *__restrict__ payload8,
+                                            uint32_t max_off, uint32_t *__restrict__ ring_lane)
+{
+    s.base = off & ~(kBlockBytes - 1);
+    s.wrw = 0;
+    s.rdw = ((off & (kBlockBytes - 1)) / 4) * 256;
+    fetch_block(s, payload8, max_off);
+    push_block(s, ring_lane);
+    fetch_block(s, payload8, max_off);
+    push_block(s, ring_lane);
+    fetch_block(s, payload8, max_off);
+    const uint32_t lo = ring_pop(s, ring_lane);
+    const uint32_t hi = ring_pop(s, ring_lane);
+    s.buf = (uint64_t)lo | ((uint64_t)hi << 32);
+    s.next = ring_pop(s, ring_lane);
+    s.avail = 64;
+}
+
+// Once per group of 16 symbols: a group takes at most six words out of the ring, and afterwards the
+// ring holds at least eight.
+__device__ __forceinline__ void stream_service(Stream &s, const uint8_t *__restrict__ payload8, uint32_t max_off,
+                                               uint32_t *__restrict__ ring_lane)
+{
+    if (s.wrw - s.rdw <= (kRingWords - kBlockWords) * 256u) {
+        push_block(s, ring_lane);
+        fetch_block(s, payload8, max_off);
+    }
+}
+
+// After this at least 33 bits are valid: enough for three codes of 11 bits.
+__device__ __forceinline__ void refill(Stream &s, const uint32_t *__restrict__ ring_lane)
+{
+    uint32_t a = s.avail & 0xFFu;
+    if (a <= 32) {
+        s.buf |= (uint64_t)s.next << a;
+        a += 32;
+        s.next = ring_pop(s, ring_lane);
+    }
+    s.avail = a;
+}
+
+// Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount and
+// `avail` is only read through its low 8 bits, so the entry is used unmasked for both.
+__device__ __forceinline__ uint32_t symbol(Stream &s, const uint16_t *__restrict__ tbl)
+{
+    const uint32_t e = tbl[(uint32_t)s.buf & (kTableEntries - 1)];
+    s.buf >>= (e & 63u);
+    s.avail -= e;
+    return e;
+}
 
 // bytes 1 of four entries -> one little-endian word of four symbols
 __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3)
@@ -109,14 +165,14 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-__device__ __forceinline__ void decode16(BitReader &br, const uint16_t *__restrict__ tbl,
-                                         const uint32_t *__restrict__ payload, uint32_t max_word, uint32_t out[4])
+__device__ __forceinline__ void decode16(Stream &s, const uint16_t *__restrict__ tbl,
+                                         const uint32_t *__restrict__ ring_lane, uint32_t out[4])
 {
     uint32_t e[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) {
-        if (i % 3 == 0) br.refill(payload, max_word);
-        e[i] = br.symbol(tbl);
+        if (i % 3 == 0) refill(s, ring_lane);
+        e[i] = symbol(s, tbl);
     }
 #pragma unroll
     for (int i = 0; i < 4; i++) out[i] = pack4(e[4 * i], e[4 * i + 1], e[4 * i + 2], e[4 * i + 3]);
@@ -145,21 +201,25 @@ __device__ __forceinline__ void word_to_scaled_f32(uint32_t w, float s, float bi
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 template <int S, int MODE>
-__global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
+__global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(DecodeArgs a)
 {
     using G = Geometry<S>;
     constexpr int LPC = G::kLanesPerChunk;
     constexpr int CPW = G::kChunksPerWave;
-    constexpr int NS = G::kStreamsPerLane;
+    constexpr int WAVES = G::kWaves;
+    constexpr int TPC = G::kThreadsPerChunk;
     constexpr int SPL = G::kSymbolsPerLane;
     constexpr uint32_t kHeader = 128 + 4 * S;
 
-    __shared__ uint16_t lds_table[CPW][kTableEntries];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_table[CPW][kTableEntries];
     __shared__ uint32_t lds_first[CPW][16]; // left-aligned first code of each length
+    __shared__ uint32_t lds_ring[WAVES][kRingWords * 64];
 
-    const uint32_t lane = threadIdx.x;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
     const uint32_t sub = lane / LPC;
-    const uint32_t cl = lane % LPC;
+    const uint32_t cl = lane % LPC;              // lane inside the chunk's share of the wave
+    const uint32_t ct = wave * 64 + cl;          // thread inside the chunk = sub-stream number
     const uint64_t k = (uint64_t)blockIdx.x * CPW + sub;
 
     // ---- chunk table entry, checked so that nothing below can leave the blob or the destination
@@ -171,17 +231,20 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
     const uint64_t dst_pos = k * (uint64_t)a.chunk_bytes; // first decoded byte of the chunk
     active = active && raw >= 1 && raw <= a.chunk_bytes && (ent.off & 15) == 0 && ent.off <= a.blob_bytes &&
              ent.comp_bytes <= a.blob_bytes - ent.off && ent.comp_bytes >= 16 && dst_pos + raw <= a.dst_cap &&
+             a.blob_bytes - ent.off >= 2 * kBlockBytes &&
              (is_raw ? ent.comp_bytes >= ((raw + 15u) & ~15u) : ent.comp_bytes >= kHeader);
     const uint8_t *payload8 = a.blob + (active ? ent.off : 0);
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(payload8);
     const bool huff = active && !is_raw;
 
     uint16_t *tbl = lds_table[sub];
+    uint32_t *ring_lane = &lds_ring[wave][lane];
 
-    // ---- decode table (all lanes walk through this block; inactive chunks contribute nothing)
+    // ---- decode table.  Every wave ranks the 256 code lengths by itself (LPC lanes, SPL values a
+    // lane); the waves of a workgroup share the writing of the 2048 entries.
     {
         uint4 *z = reinterpret_cast<uint4 *>(tbl);
-        for (uint32_t i = cl; i < kTableEntries * 2 / 16; i += LPC) z[i] = make_uint4(0, 0, 0, 0);
+        for (uint32_t i = ct; i < kTableEntries * 2 / 16; i += TPC) z[i] = make_uint4(0, 0, 0, 0);
 
         // this lane's SPL code lengths, values v = cl*SPL + s
         uint32_t nib = 0;
@@ -214,7 +277,7 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
             total[r] = __shfl(v, LPC - 1, LPC);
         }
         // left-aligned (11-bit) first code of every length
-        if (cl == 0) {
+        if (ct == 0) {
             uint32_t first = 0;
 #pragma unroll
             for (int l = 1; l <= DC_MAX_CODE_LEN; l++) {
@@ -241,23 +304,24 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
                 if (start < (uint32_t)kTableEntries) {
                     const uint32_t rev = __brev(start) >> (32 - kPeekBits); // code bits in stream order
                     const uint16_t entry = (uint16_t)(l | ((cl * SPL + s) << 8));
-                    for (uint32_t i = rev; i < (uint32_t)kTableEntries; i += 1u << l) tbl[i] = entry;
+                    for (uint32_t i = rev + (wave << l); i < (uint32_t)kTableEntries; i += (uint32_t)WAVES << l)
+                        tbl[i] = entry;
                 }
             }
         }
         __syncthreads();
     }
 
-    // ---- raw chunks: the lanes of the chunk copy it 16 bytes at a time
+    // ---- raw chunks: the threads of the chunk copy it 16 bytes at a time
     if (active && is_raw) {
         if (MODE == kModeI8) {
             uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
             const uint32_t n16 = raw / 16;
-            for (uint32_t i = cl; i < n16; i += LPC) {
+            for (uint32_t i = ct; i < n16; i += TPC) {
                 const u32x4 v = load16_stream(payload8 + 16 * (size_t)i);
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d8 + 16 * (size_t)i));
             }
-            for (uint32_t i = n16 * 16 + cl; i < raw; i += LPC) d8[i] = payload8[i];
+            for (uint32_t i = n16 * 16 + ct; i < raw; i += TPC) d8[i] = payload8[i];
         }
     }
 
@@ -265,17 +329,15 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
     if (MODE == kModeI8 && !huff) return;
 
     // ---- sub-stream set-up
-    const uint64_t last_word = (a.blob_bytes - ent.off) / 4 - 1; // last whole word of the blob, from this payload
-    const uint32_t max_word = last_word > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)last_word;
-    BitReader br[NS];
-    uint32_t stream_id[NS];
-#pragma unroll
-    for (int t = 0; t < NS; t++) {
-        stream_id[t] = cl + t * LPC;
+    // last position a 32-byte block may be fetched from, counted from this payload
+    const uint64_t last_block = (a.blob_bytes - ent.off - kBlockBytes) & ~(uint64_t)15;
+    const uint32_t max_off = last_block > 0xFFFFFFE0ull ? 0xFFFFFFE0u : (uint32_t)last_block;
+    Stream st;
+    {
         uint32_t off = kHeader;
-        if (huff) off = payload[32 + stream_id[t]];
+        if (huff) off = payload[32 + ct];
         if ((off & 3u) || off > ent.comp_bytes) off = kHeader;
-        if (huff) br[t].init(payload, off / 4, max_word);
+        if (huff) stream_init(st, off, payload8, max_off, ring_lane);
     }
 
     const uint32_t round_bytes = 16 * S;
@@ -283,23 +345,21 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
     const uint32_t rem = raw - full_rounds * round_bytes;
 
     if (MODE == kModeI8) {
-        uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
+        uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos + ct * 16;
         for (uint32_t r = 0; r < full_rounds; r++) {
-#pragma unroll
-            for (int t = 0; t < NS; t++) {
-                uint32_t w[4];
-                decode16(br[t], tbl, payload, max_word, w);
-                store16_stream(d8 + (size_t)r * round_bytes + stream_id[t] * 16, w[0], w[1], w[2], w[3]);
-            }
+            uint32_t w[4];
+            stream_service(st, payload8, max_off, ring_lane);
+            decode16(st, tbl, ring_lane, w);
+            store16_stream(d8 + (size_t)r * round_bytes, w[0], w[1], w[2], w[3]);
         }
-#pragma unroll
-        for (int t = 0; t < NS; t++) {
-            const uint32_t start = stream_id[t] * 16;
-            const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
-            uint8_t *d = d8 + (size_t)full_rounds * round_bytes + start;
+        const uint32_t start = ct * 16;
+        const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
+        if (n) {
+            stream_service(st, payload8, max_off, ring_lane);
+            uint8_t *d = d8 + (size_t)full_rounds * round_bytes;
             for (uint32_t i = 0; i < n; i++) {
-                br[t].refill(payload, max_word);
-                d[i] = (uint8_t)(br[t].symbol(tbl) >> 8);
+                refill(st, ring_lane);
+                d[i] = (uint8_t)(symbol(st, tbl) >> 8);
             }
         }
         return;
@@ -307,43 +367,42 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
 
     // ---- fused consumers walk the matrix: group position -> (row, column)
     const uint32_t cols = a.cols;
+    const uint32_t rounds = full_rounds + (rem ? 1 : 0);
+    uint64_t pos = dst_pos + ct * 16;
+    uint32_t row = (uint32_t)(pos / cols);
+    uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
+
     if (MODE == kModeBf16) {
         uint16_t *out = static_cast<uint16_t *>(a.dst);
-        const uint32_t rounds = full_rounds + (rem ? 1 : 0);
-#pragma unroll
-        for (int t = 0; t < NS; t++) {
-            uint64_t pos = dst_pos + stream_id[t] * 16;
-            uint32_t row = (uint32_t)(pos / cols);
-            uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
-            for (uint32_t r = 0; r < rounds; r++) {
-                const uint32_t start = r * round_bytes + stream_id[t] * 16;
-                // the matrix size is a multiple of 16, so a group is whole or absent
-                const bool whole = raw >= start + 16;
-                uint32_t w[4] = {0, 0, 0, 0};
-                if (whole) {
-                    if (is_raw) {
-                        const u32x4 v = load16_stream(payload8 + start);
-                        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-                    } else {
-                        decode16(br[t], tbl, payload, max_word, w);
-                    }
-                    const float s = a.row_scale[row];
-                    const float bias = -128.0f * s;
-                    uint32_t o[8];
-#pragma unroll
-                    for (int i = 0; i < 4; i++) {
-                        float f[4];
-                        word_to_scaled_f32(w[i], s, bias, f);
-                        o[2 * i] = bf16x2(f[0], f[1]);
-                        o[2 * i + 1] = bf16x2(f[2], f[3]);
-                    }
-                    uint16_t *d = out + (pos + (uint64_t)r * round_bytes);
-                    store16_stream(d, o[0], o[1], o[2], o[3]);
-                    store16_stream(d + 8, o[4], o[5], o[6], o[7]);
+        for (uint32_t r = 0; r < rounds; r++) {
+            const uint32_t start = r * round_bytes + ct * 16;
+            // the matrix size is a multiple of 16, so a group is whole or absent
+            const bool whole = raw >= start + 16;
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (whole) {
+                if (is_raw) {
+                    const u32x4 v = load16_stream(payload8 + start);
+                    w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+                } else {
+                    stream_service(st, payload8, max_off, ring_lane);
+                    decode16(st, tbl, ring_lane, w);
                 }
-                col += round_bytes;
-                while (col >= cols) { col -= cols; row++; }
+                const float s = a.row_scale[row];
+                const float bias = -128.0f * s;
+                uint32_t o[8];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    float f[4];
+                    word_to_scaled_f32(w[i], s, bias, f);
+                    o[2 * i] = bf16x2(f[0], f[1]);
+                    o[2 * i + 1] = bf16x2(f[2], f[3]);
+                }
+                uint16_t *d = out + (pos + (uint64_t)r * round_bytes);
+                store16_stream(d, o[0], o[1], o[2], o[3]);
+                store16_stream(d + 8, o[4], o[5], o[6], o[7]);
             }
+            col += round_bytes;
+            while (col >= cols) { col -= cols; row++; }
         }
         return;
     }
@@ -351,47 +410,41 @@ __global__ __launch_bounds__(64) void dc_decode_kernel(DecodeArgs a)
     if (MODE == kModeGemv) {
         // Partial dot products of byte^0x80 (1..255) with x; the -128*sum(x) term and the row scale
         // are applied once per row by dc_gemv_finish_kernel.
-        const uint32_t rounds = full_rounds + (rem ? 1 : 0);
-#pragma unroll
-        for (int t = 0; t < NS; t++) {
-            uint64_t pos = dst_pos + stream_id[t] * 16;
-            uint32_t row = (uint32_t)(pos / cols);
-            uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
-            uint32_t cur_row = row;
-            float acc = 0.0f;
-            for (uint32_t r = 0; r < rounds; r++) {
-                const uint32_t start = r * round_bytes + stream_id[t] * 16;
-                const bool whole = raw >= start + 16;
-                if (whole) {
-                    uint32_t w[4];
-                    if (is_raw) {
-                        const u32x4 v = load16_stream(payload8 + start);
-                        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-                    } else {
-                        decode16(br[t], tbl, payload, max_word, w);
-                    }
-                    if (row != cur_row) {
-                        atomicAdd(a.y_accum + cur_row, acc);
-                        acc = 0.0f;
-                        cur_row = row;
-                    }
-                    const uint4 *xp = reinterpret_cast<const uint4 *>(a.x_bf16 + col);
-                    const uint4 xa = xp[0], xb = xp[1];
-                    const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
-#pragma unroll
-                    for (int i = 0; i < 4; i++) {
-                        const uint32_t u = w[i] ^ 0x80808080u;
-                        acc = __builtin_fmaf((float)(u & 0xFFu), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
-                        acc = __builtin_fmaf((float)((u >> 8) & 0xFFu), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
-                        acc = __builtin_fmaf((float)((u >> 16) & 0xFFu), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
-                        acc = __builtin_fmaf((float)(u >> 24), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
-                    }
+        uint32_t cur_row = row;
+        float acc = 0.0f;
+        for (uint32_t r = 0; r < rounds; r++) {
+            const uint32_t start = r * round_bytes + ct * 16;
+            const bool whole = raw >= start + 16;
+            if (whole) {
+                uint32_t w[4];
+                if (is_raw) {
+                    const u32x4 v = load16_stream(payload8 + start);
+                    w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+                } else {
+                    stream_service(st, payload8, max_off, ring_lane);
+                    decode16(st, tbl, ring_lane, w);
                 }
-                col += round_bytes;
-                while (col >= cols) { col -= cols; row++; }
+                if (row != cur_row) {
+                    if (cur_row < a.rows) atomicAdd(a.y_accum + cur_row, acc);
+                    acc = 0.0f;
+                    cur_row = row;
+                }
+                const uint4 *xp = reinterpret_cast<const uint4 *>(a.x_bf16 + col);
+                const uint4 xa = xp[0], xb = xp[1];
+                const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const uint32_t u = w[i] ^ 0x80808080u;
+                    acc = __builtin_fmaf((float)(u & 0xFFu), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
+                    acc = __builtin_fmaf((float)((u >> 8) & 0xFFu), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
+                    acc = __builtin_fmaf((float)((u >> 16) & 0xFFu), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
+                    acc = __builtin_fmaf((float)(u >> 24), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
+                }
             }
-            atomicAdd(a.y_accum + cur_row, acc);
+            col += round_bytes;
+            while (col >= cols) { col -= cols; row++; }
         }
+        if (cur_row < a.rows) atomicAdd(a.y_accum + cur_row, acc);
     }
 }
 
@@ -443,19 +496,25 @@ bool decode_params_ok(const dc_params *p)
 {
     if (!p) return false;
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
-    return p->n_streams == 32 || p->n_streams == 64 || p->n_streams == 128;
+    return p->n_streams == 32 || p->n_streams == 64 || p->n_streams == 128 || p->n_streams == 256;
+}
+
+template <int S, int MODE> void launch_one(const DecodeArgs &a, hipStream_t stream)
+{
+    using G = Geometry<S>;
+    const uint32_t grid = (uint32_t)((a.n_chunks + G::kChunksPerWave - 1) / G::kChunksPerWave);
+    hipLaunchKernelGGL((dc_decode_kernel<S, MODE>), dim3(grid), dim3(G::kThreads), 0, stream, a);
 }
 
 template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream_t stream)
 {
     if (a.n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
-    if (S == 32) {
-        const uint32_t grid = (uint32_t)((a.n_chunks + 1) / 2);
-        hipLaunchKernelGGL((dc_decode_kernel<32, MODE>), dim3(grid), dim3(64), 0, stream, a);
-    } else if (S == 64) {
-        hipLaunchKernelGGL((dc_decode_kernel<64, MODE>), dim3((uint32_t)a.n_chunks), dim3(64), 0, stream, a);
-    } else {
-        hipLaunchKernelGGL((dc_decode_kernel<128, MODE>), dim3((uint32_t)a.n_chunks), dim3(64), 0, stream, a);
+    switch (S) {
+    case 32: launch_one<32, MODE>(a, stream); break;
+    case 64: launch_one<64, MODE>(a, stream); break;
+    case 128: launch_one<128, MODE>(a, stream); break;
+    case 256: launch_one<256, MODE>(a, stream); break;
+    default: return DC_E_ARG;
     }
     return launch_status();
 }

@@ -50,7 +50,7 @@ bool params_ok(const dc_params *p)
 {
     if (!p) return false;
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
-    if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128) return false;
+    if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128 && p->n_streams != 256) return false;
     return true;
 }
 

@@ -32,7 +32,7 @@ def gpu_decode(blob, table, params, n, fill=0xAB):
     return dst.cpu().numpy()
 
 
-@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("n,C", [(3 * 65536, 65536), (5 * 16384 + 777, 16384), (7 * 4096 + 4095, 4096),
                                  (65536 + 16, 65536), (100, 65536), (1, 4096), (9 * 2048 + 1, 2048),
                                  (2 * 262144 + 12345, 262144)])
@@ -45,7 +45,7 @@ def test_decode_matches_oracle_bytes(S, n, C):
     assert np.array_equal(out, oc.decompress(c.blob, c.table, C, S, n))
 
 
-@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
 def test_decode_degenerate_chunks(S):
     print(f"case degenerate S={S}", flush=True)
     C = 4096
@@ -117,7 +117,7 @@ def matrix_case(rows, cols, seed, rescale, C, S):
     return q, scale, c
 
 
-@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("rows,cols,rescale", [(160, 1024, False), (96, 2752, True), (33, 5120, False)])
 def test_dequant_bf16_bit_exact(S, rows, cols, rescale):
     print(f"case bf16 S={S} {rows}x{cols}", flush=True)
@@ -139,7 +139,7 @@ def gemv_check(y, y_ref):
     return float(err.max() / np.abs(y_ref).max())
 
 
-@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("rows,cols,C,f", [(160, 1024, 16384, 0.0), (50, 5120, 65536, 0.0), (37, 13824, 65536, 0.3),
                                            (64, 2752, 16384, 0.5)])
 def test_gemv_within_tolerance(S, rows, cols, C, f):

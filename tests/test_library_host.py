@@ -57,7 +57,7 @@ def test_quantize_rows_other_exponents(alpha):
     assert np.array_equal(cs, s) and np.array_equal(q, oq.prune(q_ref)) and np.array_equal(rs, rs_ref)
 
 
-@pytest.mark.parametrize("S", [32, 64, 128])
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("n,C", [(5 * 16384 + 777, 16384), (3 * 65536, 65536), (100, 65536), (65536 + 16, 65536),
                                  (7 * 4096 + 4095, 4096)])
 def test_compress_is_byte_identical_to_oracle(S, n, C):
