@@ -8,7 +8,8 @@
  * about to be used, into a caller-owned decompression buffer; a speed-adaptive
  * share of the chunks is stored raw.  The lossless coder is a per-chunk
  * canonical Huffman code over the 256 byte values (code length <= 11) with S
- * symbol-interleaved sub-bitstreams per chunk; its layout is given below.
+ * symbol-interleaved sub-bitstreams per chunk, stored block-interleaved; the
+ * layout is given below.
  *
  * Conventions for every entry point
  *   - extern "C", plain pointers and sizes.  "_host" pointers are ordinary
@@ -34,22 +35,39 @@
  *     chunk k decodes to bytes [k*chunk_bytes, k*chunk_bytes + raw_bytes) of the
  *     destination; only the last chunk may be shorter than chunk_bytes.
  *   blob                 the payloads back to back in chunk order, followed by DC_BLOB_TAIL_BYTES
- *                        zero bytes (the decoder fetches sub-streams ahead in 32-byte blocks and
- *                        must never need bytes past the end of the blob); blob_bytes counts them
+ *                        zero bytes; blob_bytes counts them
  *   raw payload          the bytes, zero padded to a multiple of 16
  *   Huffman payload
  *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
  *                        byte v >> 1; 0 = value absent, otherwise 1..11
- *       [128,128+4S)     u32 off[j], j < S: first byte of sub-stream j counted
- *                        from the payload start, multiple of 4, non-decreasing
+ *       [128,128+2S)     u16 nb[j], j < S: number of 16-byte blocks of sub-stream j
+ *       [128+2S, +4*S/W) u32 set_off[w]: first byte of the block region of stream set w, counted
+ *                        from the payload start, multiple of 16; then zero padding to a multiple
+ *                        of 16.  A stream set is W = min(S, 64) consecutive sub-streams (the
+ *                        streams one wavefront decodes): set w = streams [W*w, W*w + W).
  *       sub-streams      the chunk is cut in 16-byte groups; group g belongs to
  *                        sub-stream g mod S; a sub-stream is the concatenated
  *                        codes of its bytes in increasing position, zero padded
- *                        to a whole number of 32-bit words.  No end marker:
+ *                        to a whole number of 16-byte blocks.  No end marker:
  *                        symbol counts follow from raw_bytes.
  *       bit order        stream bit i is bit (i mod 32) of little-endian u32
  *                        word i / 32; a code is written most significant code
  *                        bit first.
+ *       block regions    one per stream set, back to back after the header.  A region holds
+ *                        the blocks of its streams interleaved in the order in which a decoder
+ *                        that works through all streams in step asks for them, so that it
+ *                        reads the region front to back.  The order is fixed by this rule.
+ *                        Decoding goes in steps h = 0, 1, ...; step h comes before symbols
+ *                        8*(h mod 2) .. 8*(h mod 2)+7 of group number (h div 2) of every stream.
+ *                        Let c[j] be the stream bits used by the symbols of stream j that come
+ *                        before step h, and f[j] the blocks of stream j placed so far.  At a
+ *                        step, for j ascending over the set: if f[j] < nb[j] and
+ *                        128*f[j] - c[j] < DC_LOOKAHEAD_BITS, block f[j] of stream j is placed
+ *                        next in the region and f[j] grows by one.  Step 0 is carried out three
+ *                        times in a row, every later step once.  (Half a group uses at most 88
+ *                        bits, so after every step a stream has at least DC_LOOKAHEAD_BITS bits
+ *                        placed beyond its position, or all of its blocks; every block is
+ *                        placed by the last step.)
  *       codes            canonical: lengths from package-merge with limit 11
  *                        (leaves ordered by count then byte value, a leaf before
  *                        a package of equal weight); codes numbered in order of
@@ -74,6 +92,8 @@ extern "C" {
 #define DC_MAX_CODE_LEN 11
 #define DC_MAX_CHUNK_BYTES (1u << 20)
 #define DC_BLOB_TAIL_BYTES 64
+#define DC_BLOCK_BYTES 16
+#define DC_LOOKAHEAD_BITS 320
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */

@@ -20,22 +20,35 @@
  *     u32 comp_bytes   payload size including padding, multiple of 16
  *     u32 raw_bytes | RAW<<31
  *   blob              the payloads back to back in chunk order, then 64 zero
- *                     bytes (so that a reader fetching ahead in 32-byte blocks
- *                     never needs bytes past the end of the blob)
+ *                     bytes
  *   raw payload       raw_bytes bytes, zero padded to 16
  *   Huffman payload
  *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
  *                      (0 = value absent, else 1..11)
- *     [128,128+4S)     u32 off[j]: start of sub-stream j from payload start,
- *                      multiple of 4
+ *     [128,128+2S)     u16 nb[j]: number of 16-byte blocks of sub-stream j
+ *     then             u32 set_off[w], one per stream set: start of the set's
+ *                      block region from payload start; then zeros to a
+ *                      multiple of 16.  A stream set is W = min(S,64)
+ *                      consecutive sub-streams.
  *     sub-streams      stream j = codes of the bytes of the 16-byte groups
  *                      g = j, j+S, j+2S, ... of the chunk, in increasing
  *                      position; a stream is padded with zero bits to a whole
- *                      number of 32-bit words; payload zero padded to 16
+ *                      number of 16-byte blocks
+ *     block regions    one per stream set, back to back after the header; the
+ *                      blocks of the set's streams in the order of the
+ *                      placement rule below (orc_step)
  *   bit order          stream bit i is bit (i mod 8) of stream byte i/8; a code
  *                      is written most significant code bit first
  *   codes              canonical: lengths by package-merge (below), codes
  *                      numbered in order of (length, byte value)
+ *
+ * Placement rule.  Decoding goes in steps h = 0, 1, ...: step h comes before
+ * symbols 8*(h%2) .. 8*(h%2)+7 of group number h/2 of every stream.  With c[j]
+ * the stream bits used by the symbols of stream j before step h and f[j] the
+ * blocks of stream j placed so far: at a step, for j ascending over the set, if
+ * f[j] < nb[j] and 128*f[j] - c[j] < 320 then block f[j] of stream j is placed
+ * next in the region and f[j] grows by one.  Step 0 is carried out three times,
+ * every later step once.
  *
  * Every function is written for a reader to check by eye, not for speed:
  * one bit at a time, explicit item lists, no tables.
@@ -216,10 +229,45 @@ uint32_t orc_stream_symbols(uint32_t raw_bytes, uint32_t S, uint32_t j)
 
 static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
-/* Upper bound of a Huffman payload: header + 11 bits a symbol + stream padding + tail. */
+#define ORC_BLOCK 16u        /* bytes of a block */
+#define ORC_LOOKAHEAD 320u   /* bits a stream keeps placed beyond its position */
+
+/* Streams of a set, number of sets, header size. */
+static uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
+static uint32_t header_bytes(uint32_t S)
+{
+    return (uint32_t)round_up(128 + 2 * (uint64_t)S + 4 * (uint64_t)(S / set_width(S)), 16);
+}
+
+/* Upper bound of a Huffman payload: header + 11 bits a symbol + one partial block a stream. */
 uint64_t orc_huff_bound(uint32_t raw_bytes, uint32_t S)
 {
-    return round_up(128 + 4 * (uint64_t)S + ((uint64_t)raw_bytes * 11 + 7) / 8 + 4 * (uint64_t)S, 16);
+    return round_up(header_bytes(S) + ((uint64_t)raw_bytes * 11 + 7) / 8 + ORC_BLOCK * (uint64_t)S, 16);
+}
+
+/* Number of symbols of stream j that come before step h: all of its groups before group h/2,
+ * plus up to 8 symbols of group h/2 when h is odd. */
+static uint32_t symbols_before_step(uint32_t raw_bytes, uint32_t S, uint32_t j, uint32_t h)
+{
+    uint32_t groups = (raw_bytes + 15) / 16;
+    uint32_t n = 0;
+    uint32_t r = 0;
+    for (uint32_t g = j; g < groups; g += S, r++) {
+        uint32_t lo = 16 * g;
+        uint32_t size = (lo + 16 < raw_bytes ? lo + 16 : raw_bytes) - lo;
+        if (r < h / 2)
+            n += size;
+        else if (r == h / 2 && (h & 1))
+            n += size < 8 ? size : 8;
+    }
+    return n;
+}
+
+/* Number of steps of a chunk: two for every round of S groups. */
+static uint32_t step_count(uint32_t raw_bytes, uint32_t S)
+{
+    uint32_t groups = (raw_bytes + 15) / 16;
+    return 2 * ((groups + S - 1) / S);
 }
 
 /* ------------------------------------------------------------------ chunk encode */
@@ -235,52 +283,101 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
     uint64_t cnt[256];
     uint8_t len[256];
     uint16_t code[256];
-    if (raw_bytes == 0 || S == 0 || max_len > 11)
+    if (raw_bytes == 0 || S == 0 || max_len > 11 || S % set_width(S) != 0)
         return 0;
     orc_histogram(src, raw_bytes, cnt);
     if (orc_code_lengths(cnt, max_len, len) != ORC_OK)
         return 0;
     orc_canonical_codes(len, code);
 
-    /* size: header, then each stream rounded up to whole 32-bit words */
-    uint64_t pos = 128 + 4 * (uint64_t)S;
+    /* size: header, then each stream rounded up to whole blocks */
     uint32_t groups = (raw_bytes + 15) / 16;
+    uint32_t W = set_width(S), n_sets = S / W, hdr = header_bytes(S);
+    uint64_t *nb = calloc(S, sizeof(uint64_t));
+    if (!nb)
+        return 0;
+    uint64_t total = hdr;
     for (uint32_t j = 0; j < S; j++) {
         uint64_t bits = 0;
         for (uint32_t g = j; g < groups; g += S)
             for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
                 bits += len[src[p]];
-        pos += (bits + 31) / 32 * 4;
+        nb[j] = (bits + 8 * ORC_BLOCK - 1) / (8 * ORC_BLOCK);
+        total += nb[j] * ORC_BLOCK;
     }
-    uint64_t total = round_up(pos, 16);
-    if (!out)
+    if (!out) {
+        free(nb);
         return total;
-    if (cap < total)
+    }
+    if (cap < total) {
+        free(nb);
         return 0;
+    }
     memset(out, 0, total);
-
     for (int v = 0; v < 256; v++)
         out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
-
-    pos = 128 + 4 * (uint64_t)S;
     for (uint32_t j = 0; j < S; j++) {
-        uint32_t off32 = (uint32_t)pos;
-        memcpy(out + 128 + 4 * (uint64_t)j, &off32, 4); /* little-endian host */
+        uint16_t n16 = (uint16_t)nb[j];
+        memcpy(out + 128 + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
+    }
+
+    /* every stream written out on its own, zero padded to whole blocks; used[j][k] = bits of
+     * stream j taken by its first k symbols */
+    uint8_t **st = calloc(S, sizeof(uint8_t *));
+    uint64_t **used = calloc(S, sizeof(uint64_t *));
+    for (uint32_t j = 0; j < S; j++) {
+        uint32_t nsym = orc_stream_symbols(raw_bytes, S, j);
+        st[j] = calloc(nb[j] * ORC_BLOCK + 1, 1);
+        used[j] = calloc((size_t)nsym + 1, sizeof(uint64_t));
         uint64_t bit = 0;
-        uint8_t *st = out + pos;
+        uint32_t k = 0;
         for (uint32_t g = j; g < groups; g += S) {
             for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
                 int l = len[src[p]];
                 unsigned c = code[src[p]];
-                for (int k = l - 1; k >= 0; k--) { /* most significant code bit first */
-                    if ((c >> k) & 1)
-                        st[bit >> 3] |= (uint8_t)(1u << (bit & 7));
+                for (int b = l - 1; b >= 0; b--) { /* most significant code bit first */
+                    if ((c >> b) & 1)
+                        st[j][bit >> 3] |= (uint8_t)(1u << (bit & 7));
                     bit++;
+                }
+                used[j][++k] = bit;
+            }
+        }
+    }
+
+    /* block regions: the placement rule, set by set */
+    uint64_t pos = hdr;
+    uint32_t steps = step_count(raw_bytes, S);
+    for (uint32_t w = 0; w < n_sets; w++) {
+        uint32_t off32 = (uint32_t)pos;
+        memcpy(out + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, &off32, 4);
+        uint64_t *f = calloc(W, sizeof(uint64_t));
+        for (uint32_t h = 0; h < steps; h++) {
+            int times = h == 0 ? 3 : 1;
+            for (int t = 0; t < times; t++) {
+                for (uint32_t i = 0; i < W; i++) {
+                    uint32_t j = w * W + i;
+                    uint64_t c = used[j][symbols_before_step(raw_bytes, S, j, h)];
+                    if (f[i] < nb[j] && 128 * f[i] < c + ORC_LOOKAHEAD) {
+                        memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
+                        pos += ORC_BLOCK;
+                        f[i]++;
+                    }
                 }
             }
         }
-        pos += (bit + 31) / 32 * 4;
+        for (uint32_t i = 0; i < W; i++)
+            if (f[i] != nb[w * W + i])
+                total = 0; /* cannot happen: every block is placed by the last step */
+        free(f);
     }
+    if (pos != total)
+        total = 0;
+    for (uint32_t j = 0; j < S; j++) {
+        free(st[j]);
+        free(used[j]);
+    }
+    free(st); free(used); free(nb);
     return total;
 }
 
@@ -289,7 +386,8 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
 /*
  * Decode one Huffman payload bit by bit: grow the code one bit at a time and
  * stop when it falls inside the range of codes of its length.  Symbol counts
- * come from raw_bytes, never from the stream.
+ * come from raw_bytes, never from the stream.  The blocks of a stream are
+ * collected from its set's region by the placement rule as decoding goes.
  */
 int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_bytes, uint32_t S,
                      uint8_t *dst)
@@ -297,7 +395,7 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
     uint8_t len[256];
     unsigned count[16] = {0}, first[16] = {0}, base[16] = {0};
     uint8_t sorted[256];
-    if (S == 0 || comp_bytes < 128 + 4 * (uint64_t)S)
+    if (S == 0 || S % set_width(S) != 0 || comp_bytes < header_bytes(S))
         return ORC_E_FORMAT;
     for (int v = 0; v < 256; v++) {
         len[v] = (payload[v >> 1] >> (4 * (v & 1))) & 15;
@@ -323,34 +421,76 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
             return ORC_E_FORMAT;
     }
     uint32_t groups = (raw_bytes + 15) / 16;
-    for (uint32_t j = 0; j < S; j++) {
+    uint32_t W = set_width(S), n_sets = S / W;
+    uint32_t steps = step_count(raw_bytes, S);
+    int rc = ORC_OK;
+    for (uint32_t w = 0; w < n_sets && rc == ORC_OK; w++) {
         uint32_t off32;
-        memcpy(&off32, payload + 128 + 4 * (uint64_t)j, 4);
-        const uint8_t *st = payload + off32;
-        uint64_t avail_bits = off32 <= comp_bytes ? (comp_bytes - off32) * 8 : 0;
-        uint64_t bit = 0;
-        for (uint32_t g = j; g < groups; g += S) {
-            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
-                unsigned code = 0;
-                int l = 0, found = 0;
-                while (l < 11) {
-                    if (bit >= avail_bits)
-                        return ORC_E_FORMAT;
-                    code = (code << 1) | ((st[bit >> 3] >> (bit & 7)) & 1u);
-                    bit++;
-                    l++;
-                    if (code >= first[l] && code - first[l] < count[l]) {
-                        dst[p] = sorted[base[l] + (code - first[l])];
-                        found = 1;
-                        break;
+        memcpy(&off32, payload + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, 4);
+        uint64_t pos = off32;
+        /* per stream of the set: its blocks collected so far, bits used, symbols decoded */
+        uint8_t **st = calloc(W, sizeof(uint8_t *));
+        uint64_t *f = calloc(W, sizeof(uint64_t));
+        uint64_t *bit = calloc(W, sizeof(uint64_t));
+        for (uint32_t i = 0; i < W; i++) {
+            uint16_t n16;
+            memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
+            st[i] = calloc((size_t)n16 * ORC_BLOCK + 1, 1);
+        }
+        for (uint32_t h = 0; h < steps && rc == ORC_OK; h++) {
+            int times = h == 0 ? 3 : 1;
+            for (int t = 0; t < times && rc == ORC_OK; t++) {
+                for (uint32_t i = 0; i < W; i++) {
+                    uint16_t n16;
+                    memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
+                    if (f[i] < n16 && 128 * f[i] < bit[i] + ORC_LOOKAHEAD) {
+                        if (pos + ORC_BLOCK > comp_bytes) {
+                            rc = ORC_E_FORMAT;
+                            break;
+                        }
+                        memcpy(st[i] + f[i] * ORC_BLOCK, payload + pos, ORC_BLOCK);
+                        pos += ORC_BLOCK;
+                        f[i]++;
                     }
                 }
-                if (!found)
-                    return ORC_E_FORMAT;
+            }
+            /* the symbols between step h and step h+1: half of group h/2 of every stream */
+            for (uint32_t i = 0; i < W && rc == ORC_OK; i++) {
+                uint32_t j = w * W + i;
+                uint32_t g = j + (h / 2) * S;
+                if (g >= groups)
+                    continue;
+                uint32_t lo = 16 * g + 8 * (h & 1);
+                uint32_t hi = 16 * g + 8 * (h & 1) + 8;
+                if (hi > raw_bytes)
+                    hi = raw_bytes;
+                for (uint32_t p = lo; p < hi && rc == ORC_OK; p++) {
+                    unsigned code = 0;
+                    int l = 0, found = 0;
+                    while (l < 11) {
+                        if (bit[i] >= 8 * ORC_BLOCK * f[i]) {
+                            rc = ORC_E_FORMAT;
+                            break;
+                        }
+                        code = (code << 1) | ((st[i][bit[i] >> 3] >> (bit[i] & 7)) & 1u);
+                        bit[i]++;
+                        l++;
+                        if (code >= first[l] && code - first[l] < count[l]) {
+                            dst[p] = sorted[base[l] + (code - first[l])];
+                            found = 1;
+                            break;
+                        }
+                    }
+                    if (!found)
+                        rc = ORC_E_FORMAT;
+                }
             }
         }
+        for (uint32_t i = 0; i < W; i++)
+            free(st[i]);
+        free(st); free(f); free(bit);
     }
-    return ORC_OK;
+    return rc;
 }
 
 /* ------------------------------------------------------- whole-buffer operations */

@@ -4,13 +4,16 @@
 // memory are decompressed by the GPU into a decompression buffer; "Speed Adaptive Partial
 // Compression": some chunks are raw and only need a copy.  The stored format is in include/dc.h.
 //
-// Work decomposition: a lane owns one sub-stream, a workgroup owns one chunk (S/64 wavefronts; with
-// S = 32 one wavefront owns two chunks, lanes 0-31 / 32-63).  Per chunk the LDS holds the decode
-// table (2048 x u16: symbol << 8 | length, indexed by the next 11 stream bits).  Per wavefront the
-// LDS holds a ring of 16 stream words per lane: the bitstream is fetched from memory in 32-byte
-// blocks, one block ahead of the ring, so that the per-symbol loop never waits on memory.  A lane
-// packs 16 decoded bytes and writes them with one 128-bit store; the lanes of a chunk write S*16
-// contiguous bytes per round.
+// Work decomposition: a lane owns one sub-stream, a wavefront owns one stream set (64 sub-streams
+// whose 16-byte blocks are stored interleaved in the order the wavefront asks for them), a workgroup
+// owns one chunk (S/64 wavefronts; with S = 32 one wavefront owns two chunks, lanes 0-31 / 32-63).
+// Per chunk the LDS holds the decode table (2048 x u16: symbol << 8 | length, indexed by the next 11
+// stream bits).  Per wavefront the LDS holds a ring of 16 stream words per lane.  Before every
+// half group of 8 symbols the lanes that are short of look-ahead each take the next block of the
+// wavefront's region (consecutive lanes, consecutive blocks: one coalesced load, and the region is
+// read front to back exactly once); the block goes into the ring one step later, so the per-symbol
+// loop never waits on memory.  A lane packs 16 decoded bytes and writes them with one 128-bit
+// store; the lanes of a chunk write S*16 contiguous bytes per round.
 #include <hip/hip_runtime.h>
 
 #include "dc.h"
@@ -20,7 +23,7 @@ namespace {
 constexpr int kPeekBits = DC_MAX_CODE_LEN;
 constexpr int kTableEntries = 1 << kPeekBits;
 constexpr int kRingWords = 16;                 // per lane
-constexpr uint32_t kBlockBytes = 32;           // bitstream fetch granule
+constexpr uint32_t kBlockBytes = DC_BLOCK_BYTES; // bitstream fetch granule
 constexpr uint32_t kBlockWords = kBlockBytes / 4;
 
 enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
@@ -62,39 +65,36 @@ struct DecodeArgs {
     float *y_accum;         // kModeGemv
 };
 
-// One sub-stream as its lane sees it.  Stream words travel memory -> (blk0, blk1) -> LDS ring -> next
-// -> buf.  Ring word j of the lane sits at ring[(j % 16) * 64 + lane], so the lanes of a wave never
-// collide on a bank.  rdw and wrw count ring words taken and put, times 256 (the byte stride between
-// two ring words of a lane).
+// One sub-stream as its lane sees it.  Stream words travel memory -> blk -> LDS ring -> next -> buf.
+// Ring word j of the lane sits at ring[(j % 16) * 64 + lane], so the lanes of a wave never collide
+// on a bank.  rdw and wrw count ring words taken and put, times 256 (the byte stride between two
+// ring words of a lane).
 struct Stream {
     uint64_t buf;   // LSB-first bit buffer
     uint32_t avail; // valid bits in buf; only the low 8 bits are meaningful between refills
     uint32_t next;  // the word that follows buf
     uint32_t rdw;
     uint32_t wrw;
-    uint32_t base;  // payload byte offset of ring word 0, multiple of 32
-    u32x4 blk0, blk1; // block in flight: payload bytes [base + wrw/64, +32)
+    uint32_t taken; // blocks asked for so far (f of the placement rule)
+    uint32_t nb;    // blocks of the stream
+    u32x4 blk;      // block asked for at the last step, not yet in the ring when taken*1024 != wrw
 };
 
-__device__ __forceinline__ void fetch_block(Stream &s, const uint8_t *__restrict__ payload8, uint32_t max_off)
-{
-    uint32_t off = s.base + (s.wrw >> 6);
-    off = off < max_off ? off : max_off;
-    s.blk0 = *reinterpret_cast<const u32x4 *>(payload8 + off);
-    s.blk1 = *reinterpret_cast<const u32x4 *>(payload8 + off + 16);
-}
+// What the lanes of one stream set share: where the set's region stands.
+struct Region {
+    const uint8_t *payload8;
+    uint32_t next_block; // in 16-byte units from the payload start
+    uint32_t max_off;    // last payload offset a block may be loaded from
+    uint64_t lanes;      // the lanes of the wave that belong to the set
+};
 
-__device__ __forceinline__ void push_block(Stream &s, uint32_t *__restrict__ ring_lane)
+__device__ __forceinline__ void push_block(Stream &s, const u32x4 &blk, uint32_t *__restrict__ ring_lane)
 {
     uint32_t *w = ring_lane + ((s.wrw & 0xF00u) >> 2);
-    w[0] = s.blk0[0];
-    w[64] = s.blk0[1];
-    w[128] = s.blk0[2];
-    w[192] = s.blk0[3];
-    w[256] = s.blk1[0];
-    w[320] = s.blk1[1];
-    w[384] = s.blk1[2];
-    w[448] = s.blk1[3];
+    w[0] = blk[0];
+    w[64] = blk[1];
+    w[128] = blk[2];
+    w[192] = blk[3];
     s.wrw += kBlockWords * 256;
 }
 
@@ -105,34 +105,54 @@ __device__ __forceinline__ uint32_t ring_pop(Stream &s, const uint32_t *__restri
     return w;
 }
 
-// Start of a sub-stream at payload byte `off` (multiple of 4): two blocks into the ring, a third in flight.
-__device__ __forceinline__ void stream_init(Stream &s, uint32_t off, const uint8_t *__restrict__ payload8,
-                                            uint32_t max_off, uint32_t *__restrict__ ring_lane)
+// The lanes with `want` each take the next block of the region, in lane order.
+__device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u32x4 &dst)
 {
-    s.base = off & ~(kBlockBytes - 1);
+    const uint64_t m = __ballot(want) & rg.lanes;
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if (want) {
+        uint32_t off = (rg.next_block + rank) * kBlockBytes;
+        off = off < rg.max_off ? off : rg.max_off;
+        dst = *reinterpret_cast<const u32x4 *>(rg.payload8 + off);
+        s.taken++;
+    }
+    rg.next_block += (uint32_t)__popcll(m);
+}
+
+// One step of the placement rule (before every half group): the block asked for at the step before
+// goes into the ring, then the lanes short of look-ahead ask for their next block.
+__device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t *__restrict__ ring_lane)
+{
+    if (s.taken * (kBlockWords * 256) != s.wrw) push_block(s, s.blk, ring_lane);
+    // stream bits used so far: the words taken out of the ring, less what buf and next still hold
+    const uint32_t used = (s.rdw >> 3) - 32u - (s.avail & 0xFFu);
+    const bool want = s.taken < s.nb && s.taken * (8 * kBlockBytes) < used + DC_LOOKAHEAD_BITS;
+    take_blocks(s, rg, want, s.blk);
+}
+
+// Start of a sub-stream: step 0 of the rule runs three times (nothing is used yet, so every stream
+// with blocks left takes one each time), then buf and next are loaded.
+__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t nb, uint32_t *__restrict__ ring_lane)
+{
+    s.nb = nb;
+    s.taken = 0;
     s.wrw = 0;
-    s.rdw = ((off & (kBlockBytes - 1)) / 4) * 256;
-    fetch_block(s, payload8, max_off);
-    push_block(s, ring_lane);
-    fetch_block(s, payload8, max_off);
-    push_block(s, ring_lane);
-    fetch_block(s, payload8, max_off);
+    s.rdw = 0;
+    u32x4 b[3];
+    bool got[3];
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+        got[t] = s.taken < s.nb;
+        take_blocks(s, rg, got[t], b[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < 3; t++)
+        if (got[t]) push_block(s, b[t], ring_lane);
     const uint32_t lo = ring_pop(s, ring_lane);
     const uint32_t hi = ring_pop(s, ring_lane);
     s.buf = (uint64_t)lo | ((uint64_t)hi << 32);
     s.next = ring_pop(s, ring_lane);
     s.avail = 64;
-}
-
-// Once per group of 16 symbols: a group takes at most six words out of the ring, and afterwards the
-// ring holds at least eight.
-__device__ __forceinline__ void stream_service(Stream &s, const uint8_t *__restrict__ payload8, uint32_t max_off,
-                                               uint32_t *__restrict__ ring_lane)
-{
-    if (s.wrw - s.rdw <= (kRingWords - kBlockWords) * 256u) {
-        push_block(s, ring_lane);
-        fetch_block(s, payload8, max_off);
-    }
 }
 
 // After this at least 33 bits are valid: enough for three codes of 11 bits.
@@ -165,17 +185,29 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-__device__ __forceinline__ void decode16(Stream &s, const uint16_t *__restrict__ tbl,
-                                         const uint32_t *__restrict__ ring_lane, uint32_t out[4])
+// Symbols [8*HALF, 8*HALF + 8) of a group; refills before symbols 0, 3, 6 of the half.
+template <int HALF>
+__device__ __forceinline__ void decode8(Stream &s, const uint16_t *__restrict__ tbl,
+                                        const uint32_t *__restrict__ ring_lane, uint32_t out[4])
 {
-    uint32_t e[16];
+    uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
+    for (int i = 0; i < 8; i++) {
         if (i % 3 == 0) refill(s, ring_lane);
         e[i] = symbol(s, tbl);
     }
-#pragma unroll
-    for (int i = 0; i < 4; i++) out[i] = pack4(e[4 * i], e[4 * i + 1], e[4 * i + 2], e[4 * i + 3]);
+    out[2 * HALF] = pack4(e[0], e[1], e[2], e[3]);
+    out[2 * HALF + 1] = pack4(e[4], e[5], e[6], e[7]);
+}
+
+// One whole group of 16 symbols with the two steps of the placement rule that precede its halves.
+__device__ __forceinline__ void decode16(Stream &s, Region &rg, const uint16_t *__restrict__ tbl,
+                                         uint32_t *__restrict__ ring_lane, bool has_group, uint32_t out[4])
+{
+    stream_step(s, rg, ring_lane);
+    if (has_group) decode8<0>(s, tbl, ring_lane, out);
+    stream_step(s, rg, ring_lane);
+    if (has_group) decode8<1>(s, tbl, ring_lane, out);
 }
 
 __device__ __forceinline__ uint32_t bf16x2(float a, float b)
@@ -209,7 +241,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr int WAVES = G::kWaves;
     constexpr int TPC = G::kThreadsPerChunk;
     constexpr int SPL = G::kSymbolsPerLane;
-    constexpr uint32_t kHeader = 128 + 4 * S;
+    constexpr uint32_t kHeader = (128 + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
 
     __shared__ __attribute__((aligned(16))) uint16_t lds_table[CPW][kTableEntries];
     __shared__ uint32_t lds_first[CPW][16]; // left-aligned first code of each length
@@ -231,7 +263,6 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     const uint64_t dst_pos = k * (uint64_t)a.chunk_bytes; // first decoded byte of the chunk
     active = active && raw >= 1 && raw <= a.chunk_bytes && (ent.off & 15) == 0 && ent.off <= a.blob_bytes &&
              ent.comp_bytes <= a.blob_bytes - ent.off && ent.comp_bytes >= 16 && dst_pos + raw <= a.dst_cap &&
-             a.blob_bytes - ent.off >= 2 * kBlockBytes &&
              (is_raw ? ent.comp_bytes >= ((raw + 15u) & ~15u) : ent.comp_bytes >= kHeader);
     const uint8_t *payload8 = a.blob + (active ? ent.off : 0);
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(payload8);
@@ -328,16 +359,15 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     if (MODE != kModeI8 && !(active)) return;
     if (MODE == kModeI8 && !huff) return;
 
-    // ---- sub-stream set-up
-    // last position a 32-byte block may be fetched from, counted from this payload
-    const uint64_t last_block = (a.blob_bytes - ent.off - kBlockBytes) & ~(uint64_t)15;
-    const uint32_t max_off = last_block > 0xFFFFFFE0ull ? 0xFFFFFFE0u : (uint32_t)last_block;
+    // ---- sub-stream set-up: all lanes of a stream set are here together or not at all
+    Region rg;
     Stream st;
-    {
-        uint32_t off = kHeader;
-        if (huff) off = payload[32 + ct];
-        if ((off & 3u) || off > ent.comp_bytes) off = kHeader;
-        if (huff) stream_init(st, off, payload8, max_off, ring_lane);
+    if (huff) {
+        rg.payload8 = payload8;
+        rg.max_off = ent.comp_bytes - kBlockBytes;
+        rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
+        rg.next_block = payload[(128 + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
+        stream_init(st, rg, reinterpret_cast<const uint16_t *>(payload8)[64 + ct], ring_lane);
     }
 
     const uint32_t round_bytes = 16 * S;
@@ -348,16 +378,21 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos + ct * 16;
         for (uint32_t r = 0; r < full_rounds; r++) {
             uint32_t w[4];
-            stream_service(st, payload8, max_off, ring_lane);
-            decode16(st, tbl, ring_lane, w);
+            decode16(st, rg, tbl, ring_lane, true, w);
             store16_stream(d8 + (size_t)r * round_bytes, w[0], w[1], w[2], w[3]);
         }
-        const uint32_t start = ct * 16;
-        const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
-        if (n) {
-            stream_service(st, payload8, max_off, ring_lane);
+        if (rem) {
+            // last, partial round: lanes hold 16, fewer or no symbols; bytes are written one by one
+            const uint32_t start = ct * 16;
+            const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
             uint8_t *d = d8 + (size_t)full_rounds * round_bytes;
-            for (uint32_t i = 0; i < n; i++) {
+            stream_step(st, rg, ring_lane);
+            for (uint32_t i = 0; i < (n < 8 ? n : 8); i++) {
+                refill(st, ring_lane);
+                d[i] = (uint8_t)(symbol(st, tbl) >> 8);
+            }
+            stream_step(st, rg, ring_lane);
+            for (uint32_t i = 8; i < n; i++) {
                 refill(st, ring_lane);
                 d[i] = (uint8_t)(symbol(st, tbl) >> 8);
             }
@@ -379,14 +414,13 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             // the matrix size is a multiple of 16, so a group is whole or absent
             const bool whole = raw >= start + 16;
             uint32_t w[4] = {0, 0, 0, 0};
+            if (huff) {
+                decode16(st, rg, tbl, ring_lane, whole, w);
+            } else if (whole) {
+                const u32x4 v = load16_stream(payload8 + start);
+                w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+            }
             if (whole) {
-                if (is_raw) {
-                    const u32x4 v = load16_stream(payload8 + start);
-                    w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-                } else {
-                    stream_service(st, payload8, max_off, ring_lane);
-                    decode16(st, tbl, ring_lane, w);
-                }
                 const float s = a.row_scale[row];
                 const float bias = -128.0f * s;
                 uint32_t o[8];
@@ -415,15 +449,14 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         for (uint32_t r = 0; r < rounds; r++) {
             const uint32_t start = r * round_bytes + ct * 16;
             const bool whole = raw >= start + 16;
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (huff) {
+                decode16(st, rg, tbl, ring_lane, whole, w);
+            } else if (whole) {
+                const u32x4 v = load16_stream(payload8 + start);
+                w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+            }
             if (whole) {
-                uint32_t w[4];
-                if (is_raw) {
-                    const u32x4 v = load16_stream(payload8 + start);
-                    w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
-                } else {
-                    stream_service(st, payload8, max_off, ring_lane);
-                    decode16(st, tbl, ring_lane, w);
-                }
                 if (row != cur_row) {
                     if (cur_row < a.rows) atomicAdd(a.y_accum + cur_row, acc);
                     acc = 0.0f;

@@ -164,6 +164,12 @@ void histogram256(const uint8_t *p, uint32_t n, uint32_t out[256])
     for (int v = 0; v < 256; v++) out[v] = h[0][v] + h[1][v] + h[2][v] + h[3][v];
 }
 
+constexpr uint32_t kBlock = DC_BLOCK_BYTES;
+constexpr uint32_t kBlockBits = 8 * DC_BLOCK_BYTES;
+
+inline uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
+inline uint32_t header_bytes(uint32_t S) { return (uint32_t)align_up(128 + 2ull * S + 4ull * (S / set_width(S)), 16); }
+
 // Bits of every sub-stream of a chunk under a codebook.
 void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb, uint64_t *bits)
 {
@@ -179,41 +185,82 @@ void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &c
     }
 }
 
+inline uint32_t blocks_of(uint64_t bits) { return (uint32_t)((bits + kBlockBits - 1) / kBlockBits); }
+
 uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
 {
-    uint64_t pos = 128 + 4ull * S;
-    for (uint32_t j = 0; j < S; j++) pos += (bits[j] + 31) / 32 * 4;
-    return (uint32_t)align_up(pos, 16);
+    uint64_t pos = header_bytes(S);
+    for (uint32_t j = 0; j < S; j++) pos += (uint64_t)blocks_of(bits[j]) * kBlock;
+    return (uint32_t)pos;
 }
 
-// Writes one Huffman payload (header, offsets, sub-streams); `out` has comp_bytes bytes.
+// Writes one Huffman payload; `out` has comp_bytes bytes.  Every sub-stream is first coded on its
+// own (whole blocks, zero padded) while the bits it has used before each step are noted; then the
+// blocks are placed, stream set by stream set, in the order of the placement rule of the format.
 void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb,
                         const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
 {
     std::memset(out, 0, comp_bytes);
     for (int v = 0; v < 256; v++) out[v >> 1] |= (uint8_t)(cb.len[v] << (4 * (v & 1)));
-    uint32_t pos = 128 + 4 * S;
     const uint32_t groups = (raw + 15) / 16;
+    const uint32_t rounds = (groups + S - 1) / S;
+    const uint32_t steps = 2 * rounds;
+    const uint32_t W = set_width(S);
+
+    std::vector<uint32_t> nb(S), first_block(S + 1, 0);
     for (uint32_t j = 0; j < S; j++) {
-        std::memcpy(out + 128 + 4 * j, &pos, 4);
-        uint32_t *w = reinterpret_cast<uint32_t *>(out + pos);
+        nb[j] = blocks_of(bits[j]);
+        first_block[j + 1] = first_block[j] + nb[j];
+        const uint16_t n16 = (uint16_t)nb[j];
+        std::memcpy(out + 128 + 2 * j, &n16, 2);
+    }
+    std::vector<uint8_t> coded((size_t)first_block[S] * kBlock + 8, 0);
+    std::vector<uint32_t> used((size_t)S * (steps + 1), 0); // used[j*(steps+1) + h]: bits before step h
+
+    for (uint32_t j = 0; j < S; j++) {
+        uint32_t *w = reinterpret_cast<uint32_t *>(coded.data() + (size_t)first_block[j] * kBlock);
+        uint32_t *u = &used[(size_t)j * (steps + 1)];
         uint64_t acc = 0;
         int fill = 0;
+        uint32_t total = 0, h = 0;
         for (uint32_t g = j; g < groups; g += S) {
-            const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16);
+            const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16), mid = std::min(hi, lo + 8);
+            u[h++] = total;
             for (uint32_t p = lo; p < hi; p++) {
+                if (p == mid) u[h++] = total;
                 const uint8_t v = src[p];
                 acc |= (uint64_t)cb.rev[v] << fill;
                 fill += cb.len[v];
+                total += cb.len[v];
                 if (fill >= 32) {
                     *w++ = (uint32_t)acc;
                     acc >>= 32;
                     fill -= 32;
                 }
             }
+            if (mid == hi) u[h++] = total;
         }
+        for (; h <= steps; h++) u[h] = total;
         if (fill > 0) *w++ = (uint32_t)acc;
-        pos += (uint32_t)((bits[j] + 31) / 32 * 4);
+    }
+
+    uint32_t pos = header_bytes(S);
+    std::vector<uint32_t> f(W);
+    for (uint32_t s0 = 0, w = 0; s0 < S; s0 += W, w++) {
+        std::memcpy(out + 128 + 2 * S + 4 * w, &pos, 4);
+        std::fill(f.begin(), f.end(), 0);
+        for (uint32_t h = 0; h < steps; h++) {
+            for (int t = (h == 0 ? 3 : 1); t > 0; t--) {
+                for (uint32_t i = 0; i < W; i++) {
+                    const uint32_t j = s0 + i;
+                    if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < (uint64_t)used[(size_t)j * (steps + 1) + h] + DC_LOOKAHEAD_BITS) {
+                        std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
+                        pos += kBlock;
+                        f[i]++;
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -223,7 +270,7 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.1 (gfx950; canonical Huffman L11, LSB-first sub-streams)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.1 (gfx950; canonical Huffman L11, block-interleaved sub-streams)"; }
 
 extern "C" const char *dc_strerror(int code)
 {
@@ -295,8 +342,8 @@ extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, ui
     if (!params_ok(params) || raw_bytes == 0) return DC_E_ARG;
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
     const uint64_t nc = (raw_bytes + C - 1) / C;
-    // worst Huffman payload: header, 11 bits a byte, one partial word per stream, tail padding
-    const uint64_t per_chunk = align_up(128 + 4ull * S + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + 4ull * S, 16);
+    // worst Huffman payload: header, 11 bits a byte, one partial block per stream
+    const uint64_t per_chunk = align_up(header_bytes(S) + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + (uint64_t)kBlock * S, 16);
     if (max_blob_bytes) *max_blob_bytes = nc * per_chunk + DC_BLOB_TAIL_BYTES;
     if (n_chunks) *n_chunks = nc;
     return DC_OK;
@@ -394,11 +441,12 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
 
 namespace {
 
-// Checks one Huffman payload completely: header, code completeness, stream extents, and that each
-// sub-stream decodes its symbol count inside its extent.
+// Checks one Huffman payload completely: header, code completeness, region extents, and that each
+// sub-stream decodes its symbol count from the blocks the placement rule has given it by then.
 bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
 {
-    const uint32_t hdr = 128 + 4 * S;
+    const uint32_t hdr = header_bytes(S);
+    const uint32_t W = set_width(S), n_sets = S / W;
     if (comp < hdr) return false;
     uint8_t len[256];
     uint32_t per_len[16] = {0};
@@ -427,36 +475,62 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
             for (uint32_t i = r; i < (1u << DC_MAX_CODE_LEN); i += 1u << l) peek_len[i] = (uint8_t)l;
         }
     }
+    for (uint32_t i = 128 + 2 * S + 4 * n_sets; i < hdr; i++)
+        if (p[i]) return false;
+
     const uint32_t groups = (raw + 15) / 16;
-    uint32_t prev_off = hdr;
-    for (uint32_t j = 0; j < S; j++) {
+    const uint32_t steps = 2 * ((groups + S - 1) / S);
+    uint32_t region = hdr;
+    for (uint32_t w = 0; w < n_sets; w++) {
         uint32_t off;
-        std::memcpy(&off, p + 128 + 4 * j, 4);
-        if (off % 4 || off < prev_off || off > comp) return false;
-        if (j == 0 && off != hdr) return false;
-        prev_off = off;
-        uint32_t end = comp;
-        if (j + 1 < S) {
-            std::memcpy(&end, p + 128 + 4 * (j + 1), 4);
-            if (end > comp || end < off) return false;
+        std::memcpy(&off, p + 128 + 2 * S + 4 * w, 4);
+        if (off != region) return false;
+        std::vector<uint32_t> nb(W), f(W, 0);
+        std::vector<uint64_t> bit(W, 0);
+        std::vector<std::vector<uint32_t>> where(W); // payload offset of each placed block
+        uint64_t blocks = 0;
+        for (uint32_t i = 0; i < W; i++) {
+            uint16_t n16;
+            std::memcpy(&n16, p + 128 + 2 * (w * W + i), 2);
+            nb[i] = n16;
+            blocks += n16;
         }
-        uint64_t nsym = 0;
-        for (uint32_t g = j; g < groups; g += S) nsym += std::min(raw, 16 * g + 16) - 16 * g;
-        const uint64_t have = (uint64_t)(end - off) * 8;
-        uint64_t bit = 0;
-        for (uint64_t s = 0; s < nsym; s++) {
-            uint32_t window = 0;
-            for (int b = 0; b < DC_MAX_CODE_LEN; b++) {
-                const uint64_t i = bit + b;
-                if (i < have) window |= (uint32_t)((p[off + (i >> 3)] >> (i & 7)) & 1u) << b;
+        if (blocks * kBlock > comp - region) return false;
+        uint32_t pos = region;
+        region += (uint32_t)(blocks * kBlock);
+        for (uint32_t h = 0; h < steps; h++) {
+            for (int t = (h == 0 ? 3 : 1); t > 0; t--)
+                for (uint32_t i = 0; i < W; i++)
+                    if (f[i] < nb[i] && (uint64_t)kBlockBits * f[i] < bit[i] + DC_LOOKAHEAD_BITS) {
+                        where[i].push_back(pos);
+                        pos += kBlock;
+                        f[i]++;
+                    }
+            for (uint32_t i = 0; i < W; i++) {
+                const uint32_t g = w * W + i + (h / 2) * S;
+                if (g >= groups) continue;
+                const uint32_t lo = 16 * g + 8 * (h & 1);
+                const uint32_t hi = std::min(raw, lo + 8);
+                const uint64_t have = (uint64_t)kBlockBits * f[i];
+                for (uint32_t q = lo; q < hi; q++) {
+                    uint32_t window = 0;
+                    for (int b = 0; b < DC_MAX_CODE_LEN; b++) {
+                        const uint64_t x = bit[i] + b;
+                        if (x < have) {
+                            const uint32_t byte = where[i][x / kBlockBits] + (uint32_t)(x % kBlockBits) / 8;
+                            window |= (uint32_t)((p[byte] >> (x & 7)) & 1u) << b;
+                        }
+                    }
+                    const int l = peek_len[window];
+                    if (l == 0 || bit[i] + l > have) return false;
+                    bit[i] += l;
+                }
             }
-            const int l = peek_len[window];
-            if (l == 0 || bit + l > have) return false;
-            bit += l;
         }
-        if (j + 1 < S && (bit + 31) / 32 * 4 != end - off) return false;
+        for (uint32_t i = 0; i < W; i++)
+            if (f[i] != nb[i] || blocks_of(bit[i]) != nb[i]) return false;
     }
-    return true;
+    return region == comp;
 }
 
 } // namespace

@@ -96,8 +96,12 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
     """Decode one Huffman payload by walking bits, from the written format alone.
 
     header: 128 bytes of 4-bit code lengths (value v in nibble v&1 of byte v>>1), then S little-endian
-    u32 stream offsets; stream bit i = bit (i%8) of byte i/8; codes canonical by (length, value),
-    written most significant bit first; bytes of 16-byte group g go to stream g % S.
+    u16 block counts, then one u32 region offset per stream set (W = min(S, 64) streams a set), padded
+    to 16; stream bit i = bit (i%8) of stream byte i/8; codes canonical by (length, value), written
+    most significant bit first; bytes of 16-byte group g go to stream g % S.  A region holds the
+    16-byte blocks of its streams in request order: before every half group (8 symbols) of all
+    streams, each stream in turn that has blocks left and fewer than 320 placed bits beyond its
+    position takes the next block of the region; the first such step runs three times.
     """
     lens = [(payload[v >> 1] >> (4 * (v & 1))) & 15 for v in range(256)]
     book: Dict[tuple, int] = {}
@@ -110,21 +114,46 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
                     code = (code + 1) << (l - prev)
                 book[(l, code)] = v
                 prev = l
-    offs = [int.from_bytes(payload[128 + 4 * j:132 + 4 * j], "little") for j in range(S)]
+    W = min(S, 64)
+    nb = [int.from_bytes(payload[128 + 2 * j:130 + 2 * j], "little") for j in range(S)]
     out = bytearray(raw_bytes)
     groups = (raw_bytes + 15) // 16
-    for j in range(S):
-        bit = offs[j] * 8
-        for g in range(j, groups, S):
-            for p in range(16 * g, min(16 * g + 16, raw_bytes)):
-                l = 0
-                c = 0
-                while True:
-                    c = (c << 1) | ((payload[bit >> 3] >> (bit & 7)) & 1)
-                    bit += 1
-                    l += 1
-                    if (l, c) in book:
-                        out[p] = book[(l, c)]
-                        break
-                    assert l < 15, "no code matched"
+    rounds = (groups + S - 1) // S
+    for w in range(S // W):
+        o = 128 + 2 * S + 4 * w
+        pos = int.from_bytes(payload[o:o + 4], "little")
+        data = [bytearray() for _ in range(W)]  # blocks of each stream, in order
+        bit = [0] * W
+
+        def step():
+            nonlocal pos
+            for i in range(W):
+                if len(data[i]) < 16 * nb[w * W + i] and 8 * len(data[i]) - bit[i] < 320:
+                    data[i] += payload[pos:pos + 16]
+                    pos += 16
+
+        for h in range(2 * rounds):
+            step()
+            if h == 0:
+                step()
+                step()
+            for i in range(W):
+                g = w * W + i + (h // 2) * S
+                if g >= groups:
+                    continue
+                lo = 16 * g + 8 * (h % 2)
+                for p in range(lo, min(lo + 8, raw_bytes)):
+                    l = 0
+                    c = 0
+                    while True:
+                        assert bit[i] < 8 * len(data[i]), "stream ran past its placed blocks"
+                        c = (c << 1) | ((data[i][bit[i] >> 3] >> (bit[i] & 7)) & 1)
+                        bit[i] += 1
+                        l += 1
+                        if (l, c) in book:
+                            out[p] = book[(l, c)]
+                            break
+                        assert l < 15, "no code matched"
+        for i in range(W):
+            assert len(data[i]) == 16 * nb[w * W + i], "blocks left unplaced"
     return bytes(out)

@@ -171,9 +171,15 @@ def test_validate_catches_corruption():
     expect_bad(b, table, k)
     b = blob.copy(); b[o + 3] ^= 0x01  # Kraft sum no longer 1
     expect_bad(b, table, k)
-    b = blob.copy(); b[o + 128 + 8:o + 128 + 12] = np.frombuffer(np.uint32(1 << 24).tobytes(), np.uint8)  # offset outside
+    b = blob.copy(); b[o + 128 + 2 * 5] += 1  # block count of stream 5 one too many
     expect_bad(b, table, k)
-    b = blob.copy(); b[o + 128 + 8] ^= 0x02  # misaligned offset
+    b = blob.copy(); b[o + 128 + 2 * 5] -= 1  # ... one too few: the stream runs out of bits
+    expect_bad(b, table, k)
+    b = blob.copy(); b[o + 128 + 2 * S:o + 128 + 2 * S + 4] = np.frombuffer(np.uint32(1 << 24).tobytes(), np.uint8)
+    expect_bad(b, table, k)  # region offset outside the payload
+    b = blob.copy(); b[o + 128 + 2 * S] ^= 0x10  # region not right after the header
+    expect_bad(b, table, k)
+    b = blob.copy(); b[o + 128 + 2 * S + 5] = 1  # header padding not zero
     expect_bad(b, table, k)
     t = table.copy(); t["raw_bytes_flags"][2] = (t["raw_bytes_flags"][2] & dc.CHUNK_RAW) | (C + 16)  # too long
     expect_bad(blob, t, 2)

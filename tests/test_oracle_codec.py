@@ -199,24 +199,60 @@ def test_independent_decoder_full_chunk_with_long_codes():
     assert (oc.decode_chunk(payload, 65536, 32) == data).all()
 
 
-def test_header_layout_and_payload_size_closed_form():
-    raw, S = 65536, 32
+def header_bytes(S):
+    return (128 + 2 * S + 4 * (S // min(S, 64)) + 15) // 16 * 16
+
+
+def stream_bits(data, ln, S, j):
+    raw = data.size
+    groups = (raw + 15) // 16
+    idx = [np.arange(16 * g, min(16 * g + 16, raw)) for g in range(j, groups, S)]
+    return int(ln[data[np.concatenate(idx)]].sum()) if idx else 0
+
+
+@pytest.mark.parametrize("raw,S", [(65536, 32), (65536, 128), (5000, 64)])
+def test_header_layout_and_payload_size_closed_form(raw, S):
     data = gaussian_bytes(raw, 30.0, 77)
     payload = oc.encode_chunk(data, S)
     cnt = np.bincount(data, minlength=256)
     ln = oc.code_lengths(cnt.astype(np.uint64)).astype(int)
     for v in range(256):
         assert (payload[v >> 1] >> (4 * (v & 1))) & 15 == ln[v]
-    offs = np.frombuffer(payload[128:128 + 4 * S].tobytes(), dtype="<u4")
-    assert offs[0] == 128 + 4 * S and (offs % 4 == 0).all() and (np.diff(offs.astype(np.int64)) >= 0).all()
-    pos = 128 + 4 * S
-    for j in range(S):  # each stream is its bits rounded up to 32-bit words
-        assert offs[j] == pos
-        idx = np.concatenate([np.arange(16 * g, min(16 * g + 16, raw)) for g in range(j, raw // 16, S)])
-        bits = int(ln[data[idx]].sum())
-        pos += (bits + 31) // 32 * 4
-    assert payload.size == (pos + 15) // 16 * 16
-    assert not payload[pos:].any()
+    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    W = min(S, 64)
+    set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
+    for j in range(S):  # each stream is its bits rounded up to 16-byte blocks
+        assert nb[j] == (stream_bits(data, ln, S, j) + 127) // 128
+    pos = header_bytes(S)
+    assert not payload[128 + 2 * S + 4 * (S // W):pos].any()
+    for w in range(S // W):  # regions back to back after the header
+        assert set_off[w] == pos
+        pos += 16 * int(nb[w * W:(w + 1) * W].sum())
+    assert payload.size == pos
+
+
+def test_first_blocks_of_a_region_are_the_streams_in_turn():
+    """Step 0 runs three times: the region opens with block 0 of every stream in stream order, then
+    block 1 of every stream, then block 2 (all streams here are longer than three blocks)."""
+    raw, S = 16384, 32
+    data = gaussian_bytes(raw, 20.0, 5)
+    payload = oc.encode_chunk(data, S)
+    ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
+    code = oc.canonical_codes(ln.astype(np.uint8)).astype(int)
+    pos = header_bytes(S)
+    for b in range(3):
+        for j in range(S):
+            # bits of block b of stream j, written out independently
+            bits = []
+            for g in range(j, raw // 16, S):
+                for p in range(16 * g, 16 * g + 16):
+                    v = int(data[p])
+                    bits += [(code[v] >> k) & 1 for k in range(ln[v] - 1, -1, -1)]
+                if len(bits) >= 128 * (b + 1):
+                    break
+            want = np.packbits(np.array(bits[128 * b:128 * (b + 1)], dtype=np.uint8), bitorder="little")
+            assert payload[pos:pos + 16].tobytes() == want.tobytes(), (b, j)
+            pos += 16
 
 
 def test_single_value_chunk_closed_form():
@@ -224,9 +260,9 @@ def test_single_value_chunk_closed_form():
     data = np.full(raw, 0xE7, dtype=np.uint8)
     payload = oc.encode_chunk(data, S)
     per_stream = raw // S  # one bit a symbol
-    want = 128 + 4 * S + S * ((per_stream + 31) // 32 * 4)
-    assert payload.size == (want + 15) // 16 * 16
-    assert not payload[128 + 4 * S:].any()  # code 0 everywhere
+    want = header_bytes(S) + S * ((per_stream + 127) // 128 * 16)
+    assert payload.size == want
+    assert not payload[128 + 2 * S + 4:].any()  # code 0 everywhere
     assert (oc.decode_chunk(payload, raw, S) == data).all()
     assert pyref.parse_and_decode(payload.tobytes(), raw, S) == data.tobytes()
 
@@ -235,7 +271,7 @@ def test_uniform_bytes_do_not_compress():
     raw, S = 65536, 32
     data = np.tile(np.arange(256, dtype=np.uint8), raw // 256)
     payload = oc.encode_chunk(data, S)
-    assert payload.size == 128 + 4 * S + raw  # 8 bits a symbol, streams already whole words
+    assert payload.size == header_bytes(S) + raw  # 8 bits a symbol, streams already whole blocks
 
 
 def test_zlib_huffman_only_soft_bound():
@@ -272,7 +308,7 @@ def test_corrupt_payload_is_rejected_not_crashing():
     with pytest.raises(ValueError):
         oc.decode_chunk(bad, 4096, 32)
     bad = payload.copy()
-    bad[128:132] = np.frombuffer(np.uint32(1 << 30).tobytes(), dtype=np.uint8)  # offset far outside
+    bad[128 + 64:128 + 68] = np.frombuffer(np.uint32(1 << 30).tobytes(), dtype=np.uint8)  # region far outside
     with pytest.raises(ValueError):
         oc.decode_chunk(bad, 4096, 32)
 
