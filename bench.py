@@ -82,6 +82,8 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=int(os.environ.get("DC_BENCH_STREAMS", "64")),
                     help="sub-streams per chunk (32, 64 or 128)")
     ap.add_argument("--chunk", type=int, default=65536)
+    ap.add_argument("--tile", type=int, default=1,
+                    help="decode this many copies of the layer in one launch (input-size scaling; not the headline)")
     ap.add_argument("--no-extras", action="store_true", help="skip fused/raw-fraction/copy side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -105,6 +107,13 @@ def main() -> int:
 
     layer = build_layer("llama7b", 0, True, params, dc, synth)
     blob, table, q = layer["blob"], layer["table"], layer["q"]
+    if args.tile > 1:
+        tables = []
+        for i in range(args.tile):
+            t = table.copy()
+            t["off"] += i * blob.size
+            tables.append(t)
+        blob, table, q = np.tile(blob, args.tile), np.concatenate(tables), np.tile(q, args.tile)
     raw_bytes, n_chunks = q.size, len(table)
     ratio = raw_bytes / (blob.size + table.nbytes)
 

@@ -24,7 +24,6 @@ constexpr int kPeekBits = DC_MAX_CODE_LEN;
 constexpr int kTableEntries = 1 << kPeekBits;
 constexpr int kRingWords = 16;                 // per lane
 constexpr uint32_t kBlockBytes = DC_BLOCK_BYTES; // bitstream fetch granule
-constexpr uint32_t kBlockWords = kBlockBytes / 4;
 
 enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
 
@@ -65,19 +64,28 @@ struct DecodeArgs {
     float *y_accum;         // kModeGemv
 };
 
+// LDS accessed through 32-bit byte addresses, so that address arithmetic stays in one VALU operation.
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+__device__ __forceinline__ uint32_t lds_load32(uint32_t addr) { return *(const lds_u32 *)(uintptr_t)addr; }
+__device__ __forceinline__ uint32_t lds_load16(uint32_t addr) { return *(const lds_u16 *)(uintptr_t)addr; }
+
 // One sub-stream as its lane sees it.  Stream words travel memory -> blk -> LDS ring -> next -> buf.
-// Ring word j of the lane sits at ring[(j % 16) * 64 + lane], so the lanes of a wave never collide
-// on a bank.  rdw and wrw count ring words taken and put, times 256 (the byte stride between two
-// ring words of a lane).
+// The ring of a wave is 4 KiB, 4 KiB aligned; ring word j of the lane sits at byte
+// (j % 16) * 256 + lane * 4 of it, so the lanes of a wave never collide on a bank and the slot bits
+// (0xF00) can be OR-ed into the lane's base address.
 struct Stream {
     uint64_t buf;   // LSB-first bit buffer
-    uint32_t avail; // valid bits in buf; only the low 8 bits are meaningful between refills
+    uint32_t state; // 256 * (words taken out of the ring) + (valid bits in buf, at most 64)
     uint32_t next;  // the word that follows buf
-    uint32_t rdw;
-    uint32_t wrw;
-    uint32_t taken; // blocks asked for so far (f of the placement rule)
-    uint32_t nb;    // blocks of the stream
-    u32x4 blk;      // block asked for at the last step, not yet in the ring when taken*1024 != wrw
+    uint32_t tk10;  // 1024 * (blocks asked for so far, f of the placement rule)
+    uint32_t nb10;  // 1024 * (blocks of the stream)
+    uint32_t pend;  // != 0: blk holds the block asked for at the last step, not yet in the ring
+    u32x4 blk;
 };
 
 // What the lanes of one stream set share: where the set's region stands.
@@ -88,24 +96,23 @@ struct Region {
     uint64_t lanes;      // the lanes of the wave that belong to the set
 };
 
-__device__ __forceinline__ void push_block(Stream &s, const u32x4 &blk, uint32_t *__restrict__ ring_lane)
+// Block number b of a stream goes to ring words 4b .. 4b+3.
+__device__ __forceinline__ void push_block(uint32_t block10, const u32x4 &blk, uint32_t ring_lane)
 {
-    uint32_t *w = ring_lane + ((s.wrw & 0xF00u) >> 2);
+    lds_u32 *w = (lds_u32 *)(uintptr_t)((block10 & 0xF00u) | ring_lane);
     w[0] = blk[0];
     w[64] = blk[1];
     w[128] = blk[2];
     w[192] = blk[3];
-    s.wrw += kBlockWords * 256;
 }
 
-__device__ __forceinline__ uint32_t ring_pop(Stream &s, const uint32_t *__restrict__ ring_lane)
+__device__ __forceinline__ uint32_t ring_word(uint32_t state, uint32_t ring_lane)
 {
-    const uint32_t w = ring_lane[(s.rdw & 0xF00u) >> 2];
-    s.rdw += 256;
-    return w;
+    return lds_load32((state & 0xF00u) | ring_lane);
 }
 
 // The lanes with `want` each take the next block of the region, in lane order.
+template <bool UNIFORM>
 __device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u32x4 &dst)
 {
     const uint64_t m = __ballot(want) & rg.lanes;
@@ -114,66 +121,69 @@ __device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u3
         uint32_t off = (rg.next_block + rank) * kBlockBytes;
         off = off < rg.max_off ? off : rg.max_off;
         dst = *reinterpret_cast<const u32x4 *>(rg.payload8 + off);
-        s.taken++;
+        s.tk10 += 1024;
     }
     rg.next_block += (uint32_t)__popcll(m);
+    if (UNIFORM) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
 }
 
 // One step of the placement rule (before every half group): the block asked for at the step before
-// goes into the ring, then the lanes short of look-ahead ask for their next block.
-__device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t *__restrict__ ring_lane)
+// goes into the ring, then the lanes short of look-ahead ask for their next block.  With
+// used = 32*(words taken) - 32 - avail stream bits used so far, the rule's
+// 128*f - used < DC_LOOKAHEAD_BITS reads, times 8, tk10 + 9*avail < state + 8*(DC_LOOKAHEAD_BITS - 32).
+template <bool UNIFORM>
+__device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring_lane)
 {
-    if (s.taken * (kBlockWords * 256) != s.wrw) push_block(s, s.blk, ring_lane);
-    // stream bits used so far: the words taken out of the ring, less what buf and next still hold
-    const uint32_t used = (s.rdw >> 3) - 32u - (s.avail & 0xFFu);
-    const bool want = s.taken < s.nb && s.taken * (8 * kBlockBytes) < used + DC_LOOKAHEAD_BITS;
-    take_blocks(s, rg, want, s.blk);
+    if (s.pend) push_block(s.tk10 - 1024, s.blk, ring_lane);
+    const uint32_t avail = s.state & 0xFFu;
+    const int32_t short_of = (int32_t)(s.tk10 + 9u * avail) - (int32_t)(s.state + 8u * (DC_LOOKAHEAD_BITS - 32));
+    const int32_t left = (int32_t)s.tk10 - (int32_t)s.nb10;
+    const bool want = (short_of > left ? short_of : left) < 0; // both negative
+    take_blocks<UNIFORM>(s, rg, want, s.blk);
+    s.pend = want;
 }
 
 // Start of a sub-stream: step 0 of the rule runs three times (nothing is used yet, so every stream
 // with blocks left takes one each time), then buf and next are loaded.
-__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t nb, uint32_t *__restrict__ ring_lane)
+template <bool UNIFORM>
+__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t nb, uint32_t ring_lane)
 {
-    s.nb = nb;
-    s.taken = 0;
-    s.wrw = 0;
-    s.rdw = 0;
+    s.nb10 = nb << 10;
+    s.tk10 = 0;
+    s.pend = 0;
     u32x4 b[3];
     bool got[3];
 #pragma unroll
     for (int t = 0; t < 3; t++) {
-        got[t] = s.taken < s.nb;
-        take_blocks(s, rg, got[t], b[t]);
+        got[t] = s.tk10 < s.nb10;
+        take_blocks<UNIFORM>(s, rg, got[t], b[t]);
     }
 #pragma unroll
     for (int t = 0; t < 3; t++)
-        if (got[t]) push_block(s, b[t], ring_lane);
-    const uint32_t lo = ring_pop(s, ring_lane);
-    const uint32_t hi = ring_pop(s, ring_lane);
+        if (got[t]) push_block(t << 10, b[t], ring_lane);
+    const uint32_t lo = ring_word(0 << 8, ring_lane);
+    const uint32_t hi = ring_word(1 << 8, ring_lane);
     s.buf = (uint64_t)lo | ((uint64_t)hi << 32);
-    s.next = ring_pop(s, ring_lane);
-    s.avail = 64;
+    s.next = ring_word(2 << 8, ring_lane);
+    s.state = (3 << 8) + 64;
 }
 
 // After this at least 33 bits are valid: enough for three codes of 11 bits.
-__device__ __forceinline__ void refill(Stream &s, const uint32_t *__restrict__ ring_lane)
+__device__ __forceinline__ void refill(Stream &s, uint32_t ring_lane)
 {
-    uint32_t a = s.avail & 0xFFu;
-    if (a <= 32) {
-        s.buf |= (uint64_t)s.next << a;
-        a += 32;
-        s.next = ring_pop(s, ring_lane);
+    if ((s.state & 0xFFu) <= 32) {
+        s.buf |= (uint64_t)s.next << (s.state & 63u);
+        s.next = ring_word(s.state, ring_lane);
+        s.state += 256 + 32;
     }
-    s.avail = a;
 }
 
-// Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount and
-// `avail` is only read through its low 8 bits, so the entry is used unmasked for both.
-__device__ __forceinline__ uint32_t symbol(Stream &s, const uint16_t *__restrict__ tbl)
+// Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount, so
+// the entry is used unmasked there.
+__device__ __forceinline__ uint32_t symbol(Stream &s, uint32_t tbl)
 {
-    const uint32_t e = tbl[(uint32_t)s.buf & (kTableEntries - 1)];
+    const uint32_t e = lds_load16(tbl + (((uint32_t)s.buf & (kTableEntries - 1)) << 1));
     s.buf >>= (e & 63u);
-    s.avail -= e;
     return e;
 }
 
@@ -185,29 +195,45 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// Symbols [8*HALF, 8*HALF + 8) of a group; refills before symbols 0, 3, 6 of the half.
+// Symbols [8*HALF, 8*HALF + 8) of a group; refills before symbols 0, 3, 6 of the half.  The lengths
+// of the symbols between two refills leave `state` in one subtraction (their sum stays below 256).
 template <int HALF>
-__device__ __forceinline__ void decode8(Stream &s, const uint16_t *__restrict__ tbl,
-                                        const uint32_t *__restrict__ ring_lane, uint32_t out[4])
+__device__ __forceinline__ void decode8(Stream &s, uint32_t tbl, uint32_t ring_lane, uint32_t out[4])
 {
     uint32_t e[8];
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
-        if (i % 3 == 0) refill(s, ring_lane);
-        e[i] = symbol(s, tbl);
+    for (int i = 0; i < 8; i += 3) {
+        refill(s, ring_lane);
+        uint32_t lens = 0;
+#pragma unroll
+        for (int j = i; j < i + 3 && j < 8; j++) {
+            e[j] = symbol(s, tbl);
+            lens += e[j];
+        }
+        s.state -= lens & 0xFFu;
     }
     out[2 * HALF] = pack4(e[0], e[1], e[2], e[3]);
     out[2 * HALF + 1] = pack4(e[4], e[5], e[6], e[7]);
 }
 
 // One whole group of 16 symbols with the two steps of the placement rule that precede its halves.
-__device__ __forceinline__ void decode16(Stream &s, Region &rg, const uint16_t *__restrict__ tbl,
-                                         uint32_t *__restrict__ ring_lane, bool has_group, uint32_t out[4])
+template <bool UNIFORM>
+__device__ __forceinline__ void decode16(Stream &s, Region &rg, uint32_t tbl, uint32_t ring_lane, bool has_group,
+                                         uint32_t out[4])
 {
-    stream_step(s, rg, ring_lane);
+    stream_step<UNIFORM>(s, rg, ring_lane);
     if (has_group) decode8<0>(s, tbl, ring_lane, out);
-    stream_step(s, rg, ring_lane);
+    stream_step<UNIFORM>(s, rg, ring_lane);
     if (has_group) decode8<1>(s, tbl, ring_lane, out);
+}
+
+// One symbol at a time, for the ragged end of a chunk.
+__device__ __forceinline__ uint32_t decode1(Stream &s, uint32_t tbl, uint32_t ring_lane)
+{
+    refill(s, ring_lane);
+    const uint32_t e = symbol(s, tbl);
+    s.state -= e & 0xFFu;
+    return e >> 8;
 }
 
 __device__ __forceinline__ uint32_t bf16x2(float a, float b)
@@ -243,9 +269,13 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr int SPL = G::kSymbolsPerLane;
     constexpr uint32_t kHeader = (128 + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
 
-    __shared__ __attribute__((aligned(16))) uint16_t lds_table[CPW][kTableEntries];
-    __shared__ uint32_t lds_first[CPW][16]; // left-aligned first code of each length
-    __shared__ uint32_t lds_ring[WAVES][kRingWords * 64];
+    // One block of LDS: the rings (4 KiB a wave, 4 KiB aligned) and then the decode tables.  The
+    // first codes of the lengths are only needed while the table is built, before any ring is
+    // used, and borrow the start of ring 0.
+    __shared__ __attribute__((aligned(4096))) uint32_t lds_all[WAVES * kRingWords * 64 + CPW * kTableEntries / 2];
+    uint32_t(*lds_first)[16] = reinterpret_cast<uint32_t(*)[16]>(lds_all);
+    uint16_t(*lds_table)[kTableEntries] =
+        reinterpret_cast<uint16_t(*)[kTableEntries]>(lds_all + WAVES * kRingWords * 64);
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
@@ -269,7 +299,9 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     const bool huff = active && !is_raw;
 
     uint16_t *tbl = lds_table[sub];
-    uint32_t *ring_lane = &lds_ring[wave][lane];
+    const uint32_t tbl_addr = lds_address(tbl);
+    const uint32_t ring_lane = lds_address(lds_all + wave * (kRingWords * 64) + lane);
+    constexpr bool UNI = CPW == 1; // all lanes of the wave belong to one stream set
 
     // ---- decode table.  Every wave ranks the 256 code lengths by itself (LPC lanes, SPL values a
     // lane); the waves of a workgroup share the writing of the 2048 entries.
@@ -367,7 +399,8 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         rg.max_off = ent.comp_bytes - kBlockBytes;
         rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
         rg.next_block = payload[(128 + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
-        stream_init(st, rg, reinterpret_cast<const uint16_t *>(payload8)[64 + ct], ring_lane);
+        if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
+        stream_init<UNI>(st, rg, reinterpret_cast<const uint16_t *>(payload8)[64 + ct], ring_lane);
     }
 
     const uint32_t round_bytes = 16 * S;
@@ -378,7 +411,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos + ct * 16;
         for (uint32_t r = 0; r < full_rounds; r++) {
             uint32_t w[4];
-            decode16(st, rg, tbl, ring_lane, true, w);
+            decode16<UNI>(st, rg, tbl_addr, ring_lane, true, w);
             store16_stream(d8 + (size_t)r * round_bytes, w[0], w[1], w[2], w[3]);
         }
         if (rem) {
@@ -386,16 +419,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const uint32_t start = ct * 16;
             const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
             uint8_t *d = d8 + (size_t)full_rounds * round_bytes;
-            stream_step(st, rg, ring_lane);
-            for (uint32_t i = 0; i < (n < 8 ? n : 8); i++) {
-                refill(st, ring_lane);
-                d[i] = (uint8_t)(symbol(st, tbl) >> 8);
-            }
-            stream_step(st, rg, ring_lane);
-            for (uint32_t i = 8; i < n; i++) {
-                refill(st, ring_lane);
-                d[i] = (uint8_t)(symbol(st, tbl) >> 8);
-            }
+            stream_step<UNI>(st, rg, ring_lane);
+            for (uint32_t i = 0; i < (n < 8 ? n : 8); i++) d[i] = (uint8_t)decode1(st, tbl_addr, ring_lane);
+            stream_step<UNI>(st, rg, ring_lane);
+            for (uint32_t i = 8; i < n; i++) d[i] = (uint8_t)decode1(st, tbl_addr, ring_lane);
         }
         return;
     }
@@ -415,7 +442,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const bool whole = raw >= start + 16;
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
-                decode16(st, rg, tbl, ring_lane, whole, w);
+                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
             } else if (whole) {
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
@@ -451,7 +478,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const bool whole = raw >= start + 16;
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
-                decode16(st, rg, tbl, ring_lane, whole, w);
+                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
             } else if (whole) {
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
