@@ -28,6 +28,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the decode kernel on the headline workload, from the rocprofv3 counter runs
+# summarised under profiles/ (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the
+# same counter reads for the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).
+MEASURED_TRAFFIC_KIB = {256: (76991.0, 197632.0), 64: (73562.8, 197632.0)}
+
 
 def build_layer(kind: str, layer: int, rescale: bool, params, dc, synth, matrices=None):
     """Quantise and compress every matrix of a decoder layer with the library.  Returns a dict with the
@@ -79,8 +84,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--streams", type=int, default=int(os.environ.get("DC_BENCH_STREAMS", "64")),
-                    help="sub-streams per chunk (32, 64 or 128)")
+    ap.add_argument("--streams", type=int, default=int(os.environ.get("DC_BENCH_STREAMS", "256")),
+                    help="sub-streams per chunk (32, 64, 128 or 256)")
     ap.add_argument("--chunk", type=int, default=65536)
     ap.add_argument("--tile", type=int, default=1,
                     help="decode this many copies of the layer in one launch (input-size scaling; not the headline)")
@@ -138,6 +143,11 @@ def main() -> int:
     algo_bytes = raw_bytes + blob.size + table.nbytes
     achieved = algo_bytes / ms / 1e6
 
+    traffic = None
+    if S in MEASURED_TRAFFIC_KIB and args.tile == 1 and C == 65536:
+        f_kib, w_kib = MEASURED_TRAFFIC_KIB[S]
+        traffic = int((2.0 * f_kib + 1.0 * w_kib) * 1024)
+
     out = {
         "metric": "decoded weight GB/s on 1 MI355X (and % HBM roofline); compression ratio",
         "value": round(decoded_gbps, 2),
@@ -156,7 +166,7 @@ def main() -> int:
                    "n_streams": S, "n_chunks": n_chunks, "blob_bytes": int(blob.size),
                    "compression_ratio": round(ratio, 5), "buffers_rotated": nbuf},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel": f"dc_decode_kernel<{S},int8>", "algorithmic_bytes_per_launch": int(algo_bytes),
                      "avg_launch_ms": round(ms, 5)},
         "wall_ms_per_step": round(wall_ms, 5),
@@ -171,6 +181,26 @@ def main() -> int:
                                50, 5)
         extras["copy_kernel_GBps_read_plus_write"] = round(2 * n_copy / cms / 1e6, 1)
         extras["decode_frac_of_copy_bandwidth"] = round(achieved / (2 * n_copy / cms / 1e6), 4)
+
+        # sub-stream count: compression ratio against parallelism, same layer
+        sweep_s = []
+        for s2 in (64, 128, 256):
+            if s2 == S:
+                sweep_s.append({"n_streams": s2, "decoded_GBps": round(decoded_gbps, 1), "compression_ratio": round(ratio, 5)})
+                continue
+            p2 = dc.Params(C, s2)
+            l2 = build_layer("llama7b", 0, True, p2, dc, synth)
+            b2 = [up(l2["blob"]) for _ in range(nbuf)]
+            t2 = up(l2["table"])
+            ms2, _ = time_launches(
+                torch, lambda i: dc.decompress_chunks(b2[i % nbuf], l2["blob"].size, t2, len(l2["table"]), p2,
+                                                      dsts[i % nbuf], raw_bytes, stream), 50, 5)
+            good = bool(torch.equal(dsts[(50 + 5 - 1) % nbuf].cpu(), torch.from_numpy(l2["q"].view(np.uint8))))
+            sweep_s.append({"n_streams": s2, "decoded_GBps": round(raw_bytes / ms2 / 1e6, 1),
+                            "compression_ratio": round(raw_bytes / (l2["blob"].size + l2["table"].nbytes), 5),
+                            "exact": good})
+            del b2, t2, l2
+        extras["n_streams_sweep"] = sweep_s
 
         # fused dequantisation to bf16, matrix by matrix
         scales_d = [torch.from_numpy(s).cuda() for s in layer["scales"]]

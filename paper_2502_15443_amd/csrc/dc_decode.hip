@@ -46,7 +46,7 @@ template <int S> struct Geometry {
     static constexpr int kWaves = S <= 64 ? 1 : S / 64;          // wavefronts of the workgroup
     static constexpr int kThreads = 64 * kWaves;
     static constexpr int kThreadsPerChunk = S < 64 ? S : kThreads;
-    static constexpr int kSymbolsPerLane = 256 / kLanesPerChunk; // header values a lane handles in the table build
+    static constexpr int kSymbolsPerLane = 256 / kThreadsPerChunk; // header values a thread ranks in the table build
 };
 
 struct DecodeArgs {
@@ -73,6 +73,41 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
 }
 __device__ __forceinline__ uint32_t lds_load32(uint32_t addr) { return *(const lds_u32 *)(uintptr_t)addr; }
 __device__ __forceinline__ uint32_t lds_load16(uint32_t addr) { return *(const lds_u16 *)(uintptr_t)addr; }
+
+// Value of another lane through the data-parallel primitives; lanes without a source (and rows that
+// the row mask leaves out) read 0.  0x110 + n: n lanes to the right inside a row of 16; 0x142 / 0x143:
+// lane 15 of a row to the next row / lane 31 to rows 2 and 3; 0x138: one lane to the right over
+// the whole wave.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Inclusive prefix sum over the 64 lanes (HALVES: over each half of 32 lanes on its own).
+template <bool HALVES> __device__ __forceinline__ uint32_t lanes_prefix_sum(uint32_t v)
+{
+    v += dpp_or_zero<0x111, 0xF>(v);
+    v += dpp_or_zero<0x112, 0xF>(v);
+    v += dpp_or_zero<0x114, 0xF>(v);
+    v += dpp_or_zero<0x118, 0xF>(v);
+    v += dpp_or_zero<0x142, 0xA>(v);
+    if (!HALVES) v += dpp_or_zero<0x143, 0xC>(v);
+    return v;
+}
+
+// For every lane the last non-zero value among the lanes below it (0 if none).
+template <bool HALVES> __device__ __forceinline__ uint32_t lanes_last_nonzero_below(uint32_t v)
+{
+    uint32_t t;
+    v = dpp_or_zero<0x138, 0xF>(v);
+    t = dpp_or_zero<0x111, 0xF>(v); v = v ? v : t;
+    t = dpp_or_zero<0x112, 0xF>(v); v = v ? v : t;
+    t = dpp_or_zero<0x114, 0xF>(v); v = v ? v : t;
+    t = dpp_or_zero<0x118, 0xF>(v); v = v ? v : t;
+    t = dpp_or_zero<0x142, 0xA>(v); v = v ? v : t;
+    if (!HALVES) { t = dpp_or_zero<0x143, 0xC>(v); v = v ? v : t; }
+    return v;
+}
 
 // One sub-stream as its lane sees it.  Stream words travel memory -> blk -> LDS ring -> next -> buf.
 // The ring of a wave is 4 KiB, 4 KiB aligned; ring word j of the lane sits at byte
@@ -269,13 +304,15 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr int SPL = G::kSymbolsPerLane;
     constexpr uint32_t kHeader = (128 + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
 
-    // One block of LDS: the rings (4 KiB a wave, 4 KiB aligned) and then the decode tables.  The
-    // first codes of the lengths are only needed while the table is built, before any ring is
-    // used, and borrow the start of ring 0.
-    __shared__ __attribute__((aligned(4096))) uint32_t lds_all[WAVES * kRingWords * 64 + CPW * kTableEntries / 2];
-    uint32_t(*lds_first)[16] = reinterpret_cast<uint32_t(*)[16]>(lds_all);
-    uint16_t(*lds_table)[kTableEntries] =
-        reinterpret_cast<uint16_t(*)[kTableEntries]>(lds_all + WAVES * kRingWords * 64);
+    // One block of LDS: the rings (4 KiB a wave, 4 KiB aligned) and then the decode tables.  While
+    // the tables are built, before any ring is used, the front part holds the slot markers (one
+    // u16 per table slot in code order, 4 KiB a chunk) and the start of the table part holds the
+    // first codes of the lengths and the per-wave length counts.
+    constexpr int kFrontWords = (WAVES > CPW ? WAVES : CPW) * kRingWords * 64;
+    __shared__ __attribute__((aligned(4096))) uint32_t lds_all[kFrontWords + CPW * kTableEntries / 2];
+    uint16_t(*lds_table)[kTableEntries] = reinterpret_cast<uint16_t(*)[kTableEntries]>(lds_all + kFrontWords);
+    uint32_t(*lds_first)[16] = reinterpret_cast<uint32_t(*)[16]>(lds_all + kFrontWords); // [wave * CPW + sub][length]
+    uint32_t(*lds_counts)[4] = reinterpret_cast<uint32_t(*)[4]>(lds_all + kFrontWords + 16 * WAVES * CPW); // [wave]
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
@@ -303,17 +340,27 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     const uint32_t ring_lane = lds_address(lds_all + wave * (kRingWords * 64) + lane);
     constexpr bool UNI = CPW == 1; // all lanes of the wave belong to one stream set
 
-    // ---- decode table.  Every wave ranks the 256 code lengths by itself (LPC lanes, SPL values a
-    // lane); the waves of a workgroup share the writing of the 2048 entries.
+    // ---- decode table.  Slot p of the table in code order (p = the next 11 stream bits, first bit
+    // most significant) belongs to the code that covers p; codes in canonical order cover
+    // consecutive runs of 2^(11-length) slots.  (1) The threads of the chunk rank the 256 code
+    // lengths (packed per-length counters, prefix sum over lanes and waves) and every symbol marks
+    // the first slot of its run with its table entry.  (2) Every thread takes 2048/threads
+    // consecutive slots, extends the marks forward over them, and writes the entries to the table
+    // at the bit-reversed slot numbers (the stream is read least significant bit first).
     {
-        uint4 *z = reinterpret_cast<uint4 *>(tbl);
-        for (uint32_t i = ct; i < kTableEntries * 2 / 16; i += TPC) z[i] = make_uint4(0, 0, 0, 0);
-
-        // this lane's SPL code lengths, values v = cl*SPL + s
+        constexpr int EPT = kTableEntries / TPC; // slots a thread fills
+        uint16_t *marks = reinterpret_cast<uint16_t *>(lds_all) + sub * kTableEntries;
+        {
+            uint4 *z = reinterpret_cast<uint4 *>(marks);
+            for (uint32_t i = ct; i < kTableEntries * 2 / 16; i += TPC) z[i] = make_uint4(0, 0, 0, 0);
+        }
+        // this thread's SPL code lengths, values v = ct*SPL + s
         uint32_t nib = 0;
         if (huff) {
-            if (SPL == 8) nib = payload[cl];
-            else nib = reinterpret_cast<const uint16_t *>(payload8)[cl];
+            if (SPL == 8) nib = payload[ct];
+            else if (SPL == 4) nib = reinterpret_cast<const uint16_t *>(payload8)[ct];
+            else if (SPL == 2) nib = payload8[ct];
+            else nib = (payload8[ct >> 1] >> (4 * (ct & 1))) & 15u;
         }
         // counts per length, packed three 10-bit fields a register: length l in reg (l-1)/3
         uint32_t mine[4] = {0, 0, 0, 0};
@@ -327,32 +374,43 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             for (int r = 0; r < 4; r++)
                 if (l != 0 && (l - 1) / 3 == (uint32_t)r) mine[r] += 1u << (10 * ((l - 1) % 3));
         }
-        uint32_t incl[4], total[4];
+        uint32_t before[4], total[4];
 #pragma unroll
         for (int r = 0; r < 4; r++) {
-            uint32_t v = mine[r];
-#pragma unroll
-            for (int d = 1; d < LPC; d <<= 1) {
-                const uint32_t t = __shfl_up(v, d, LPC);
-                if (cl >= (uint32_t)d) v += t;
+            const uint32_t incl = lanes_prefix_sum<CPW == 2>(mine[r]);
+            before[r] = incl - mine[r];
+            if (WAVES > 1) {
+                if (lane == 63) lds_counts[wave][r] = incl;
+            } else if (CPW == 1) {
+                total[r] = __builtin_amdgcn_readlane(incl, 63);
+            } else {
+                total[r] = __shfl(incl, LPC - 1, LPC);
             }
-            incl[r] = v;
-            total[r] = __shfl(v, LPC - 1, LPC);
         }
-        // left-aligned (11-bit) first code of every length
-        if (ct == 0) {
+        __syncthreads();
+        if (WAVES > 1) {
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                total[r] = 0;
+#pragma unroll
+                for (int w = 0; w < WAVES; w++) {
+                    const uint32_t c = lds_counts[w][r];
+                    if ((uint32_t)w < wave) before[r] += c;
+                    total[r] += c;
+                }
+            }
+        }
+        // left-aligned (11-bit) first code of every length, once per wave and chunk
+        uint32_t *first_of = lds_first[wave * CPW + sub];
+        if (cl == 0) {
             uint32_t first = 0;
 #pragma unroll
             for (int l = 1; l <= DC_MAX_CODE_LEN; l++) {
-                lds_first[sub][l] = first;
+                first_of[l] = first;
                 const uint32_t c = (total[(l - 1) / 3] >> (10 * ((l - 1) % 3))) & 1023u;
                 first += c << (kPeekBits - l);
             }
         }
-        __syncthreads();
-        uint32_t before[4];
-#pragma unroll
-        for (int r = 0; r < 4; r++) before[r] = incl[r] - mine[r];
 #pragma unroll
         for (int s = 0; s < SPL; s++) {
             const uint32_t l = len_of[s];
@@ -363,14 +421,43 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     if (r == (uint32_t)q) before[q] += 1u << sh;
-                const uint32_t start = lds_first[sub][l] + (rank << (kPeekBits - l)); // MSB-first slot
-                if (start < (uint32_t)kTableEntries) {
-                    const uint32_t rev = __brev(start) >> (32 - kPeekBits); // code bits in stream order
-                    const uint16_t entry = (uint16_t)(l | ((cl * SPL + s) << 8));
-                    for (uint32_t i = rev + (wave << l); i < (uint32_t)kTableEntries; i += (uint32_t)WAVES << l)
-                        tbl[i] = entry;
-                }
+                const uint32_t run = 1u << (kPeekBits - l);
+                const uint32_t start = first_of[l] + rank * run;
+                const uint16_t entry = (uint16_t)(l | ((ct * SPL + s) << 8));
+                // also at the first slot of every later wave that the run reaches into, so that no
+                // wave needs a mark from another wave's slots
+                for (uint32_t p = start; p < start + run && p < (uint32_t)kTableEntries; p += kTableEntries / WAVES)
+                    marks[p] = entry;
             }
+        }
+        __syncthreads();
+        uint32_t w[EPT / 2];
+        {
+            const uint4 *m4 = reinterpret_cast<const uint4 *>(marks + EPT * ct);
+#pragma unroll
+            for (int i = 0; i < EPT / 8; i++) {
+                const uint4 v = m4[i];
+                w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+            }
+        }
+        uint32_t tail = 0; // last mark among this thread's slots
+#pragma unroll
+        for (int i = 0; i < EPT / 2; i++) {
+            const uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
+            tail = lo ? lo : tail;
+            tail = hi ? hi : tail;
+        }
+        uint32_t cur = lanes_last_nonzero_below<CPW == 2>(tail);
+        // slot EPT*ct + j in code order = slot bitrev(j) << (11-e) | bitrev(ct) in stream order, EPT = 2^e
+        constexpr int E = EPT == 64 ? 6 : EPT == 32 ? 5 : EPT == 16 ? 4 : 3;
+        const uint32_t out = lds_address(lds_table[sub]) + 2 * (__brev(ct) >> (32 - (kPeekBits - E)));
+#pragma unroll
+        for (int i = 0; i < EPT / 2; i++) {
+            const uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
+            cur = lo ? lo : cur;
+            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)cur;
+            cur = hi ? hi : cur;
+            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i + 1)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)cur;
         }
         __syncthreads();
     }
