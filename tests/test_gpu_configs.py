@@ -1,0 +1,156 @@
+"""GPU parity at the full sizes of the workloads, in the launch configurations bench.py times.
+
+Whole outputs are compared with the oracle-quantised bytes (the decode of a lossless code has one
+right answer); in addition the oracle decodes sampled chunks of the very blob the GPU decoded.
+"""
+import numpy as np
+import pytest
+
+import oracle.codec as oc
+import oracle.quant as oq
+import paper_2502_15443_amd as dc
+import synth
+from tests.helpers import oracle_matrix
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def oracle_layer(kind: str, layer: int, rescale: bool):
+    """[(spec, q int8[rows, cols], row_scale)] of one decoder layer, quantised by the oracle."""
+    out = []
+    for m in synth.layer_specs(kind):
+        q, scale = oracle_matrix(m.rows, m.cols, synth.matrix_seed(layer, m.index), rescale)
+        out.append((m, q, scale))
+    return out
+
+
+def compress_concat(qs, params):
+    """Library compression matrix by matrix, blobs and tables concatenated (as bench.py does)."""
+    blobs, tables, off = [], [], 0
+    for q in qs:
+        blob, table = dc.compress_chunks(q, params)
+        table = table.copy()
+        table["off"] += off
+        off += blob.size
+        blobs.append(blob)
+        tables.append(table)
+    return np.concatenate(blobs), np.concatenate(tables)
+
+
+def check_sampled_chunks_with_oracle(blob, table, C, S, flat, ks):
+    for k in ks:
+        t = table[k:k + 1].copy()
+        raw = int(t["raw_bytes_flags"][0] & 0x7FFFFFFF)
+        ref = oc.decompress(blob, t, C, S, raw)
+        assert np.array_equal(ref, flat[k * C:k * C + raw]), k
+
+
+def gpu_decode(blob, table, params, n):
+    blob_d, table_d = dev(blob), dev(table)
+    dst = torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, blob.size, table_d, len(table), params, dst, n, stream())
+    torch.cuda.synchronize()
+    return dst.cpu().numpy()
+
+
+@pytest.mark.parametrize("S", [256, 64])
+def test_config2_llama7b_layer_one_launch(S):
+    """The benchmark's launch: 3088 chunks of 64 KiB of the compression-aware quantised layer."""
+    print(f"case config 2 S={S}", flush=True)
+    layer = oracle_layer("llama7b", 0, True)
+    C = 65536
+    p = dc.Params(C, S)
+    # the library's quantiser must give the oracle's bytes and scales
+    m, q_ref, s_ref = layer[4]
+    w = synth.gen_weight(m.rows, m.cols, synth.matrix_seed(0, m.index))
+    a = synth.gen_act_absmax(m.cols, synth.matrix_seed(0, m.index))
+    q_lib, s_lib, _ = dc.quantize_rows(w, a, 0.5, 1)
+    assert np.array_equal(q_lib, q_ref) and np.array_equal(s_lib, s_ref)
+    blob, table = compress_concat([q for _, q, _ in layer], p)
+    flat = np.concatenate([q.reshape(-1) for _, q, _ in layer]).view(np.uint8)
+    assert len(table) == 3088 and flat.size == 202375168
+    out = gpu_decode(blob, table, p, flat.size)
+    assert np.array_equal(out, flat)
+    check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, 255, 256, 1711, 3087])
+    # one matrix compressed by the oracle: same bytes, same ratio
+    c = oc.compress(layer[0][1], C, S, threads=8)
+    b0, t0 = dc.compress_chunks(layer[0][1], p)
+    assert np.array_equal(b0, c.blob) and np.array_equal(t0, c.table)
+
+
+@pytest.mark.parametrize("C,S", [(16384, 64), (65536, 64), (262144, 64), (16384, 256), (262144, 256)])
+def test_config3_layers_into_one_buffer_chunk_sweep(C, S):
+    """Two layers of the 32-layer weight set (per-layer seeds, no rescale) decoded into one buffer by
+    one launch, for the chunk sizes of the sweep."""
+    print(f"case config 3 C={C} S={S}", flush=True)
+    qs = []
+    for layer in (0, 31):
+        qs += [q for _, q, _ in oracle_layer("llama7b", layer, False)]
+    p = dc.Params(C, S)
+    blob, table = compress_concat(qs, p)
+    flat = np.concatenate([q.reshape(-1) for q in qs]).view(np.uint8)
+    assert len(table) == 2 * 202375168 // C
+    out = gpu_decode(blob, table, p, flat.size)
+    assert np.array_equal(out, flat)
+    check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, len(table) // 2, len(table) - 1])
+
+
+@pytest.mark.parametrize("f", [0.0, 0.25, 0.5, 0.75, 1.0])
+def test_config4_raw_fraction_on_config1_matrix(f):
+    print(f"case config 4 f={f}", flush=True)
+    q, _ = oracle_matrix(4096, 4096, synth.matrix_seed(0, 0), False)
+    C, S = 65536, 32
+    p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, f)
+    blob, table = dc.compress_chunks(q, p)
+    c = oc.compress(q, C, S, oc.RAW_FRACTION, f, threads=8)
+    assert np.array_equal(blob, c.blob) and np.array_equal(table, c.table)
+    is_raw = (table["raw_bytes_flags"] & dc.CHUNK_RAW) != 0
+    assert int(is_raw.sum()) == int(f * 256)
+    # closed form of the ratio: coded payloads + raw chunks + table + closing bytes
+    size = int(table["comp_bytes"].sum()) + 64 + table.nbytes
+    assert blob.size + table.nbytes == size and int(table["comp_bytes"][is_raw].sum()) == int(is_raw.sum()) * C
+    if f == 1.0:
+        assert q.size / size < 1.0
+    out = gpu_decode(blob, table, p, q.size)
+    assert np.array_equal(out, q.view(np.uint8).ravel())
+
+
+@pytest.mark.parametrize("index", [0, 4, 6])
+def test_config5_llama13b_fused_paths(index):
+    """q_proj (5120x5120), gate_proj (13824x5120) and down_proj (5120x13824) of the 13B-shaped layer:
+    fused GEMV against the fp64 reference, fused bf16 dequantisation bit for bit on sampled rows."""
+    print(f"case config 5 matrix {index}", flush=True)
+    m = synth.layer_specs("llama13b")[index]
+    seed = synth.matrix_seed(0, m.index)
+    q, scale = oracle_matrix(m.rows, m.cols, seed, False)
+    C, S = 65536, 256
+    p = dc.Params(C, S)
+    blob, table = dc.compress_chunks(q, p)
+    blob_d, table_d, scale_d = dev(blob), dev(table), torch.from_numpy(scale).cuda()
+    x = synth.gen_activation_bf16(m.cols, seed)
+    x_d = torch.from_numpy(x.view(np.int16)).cuda()
+    y32 = torch.empty(m.rows, dtype=torch.float32, device="cuda")
+    y16 = torch.empty(m.rows, dtype=torch.int16, device="cuda")
+    dc.decompress_gemv(blob_d, blob.size, table_d, len(table), p, scale_d, m.rows, m.cols, x_d, y32, y16, stream())
+    out16 = torch.empty(q.size, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, blob.size, table_d, len(table), p, scale_d, m.rows, m.cols, out16, q.size,
+                               stream())
+    torch.cuda.synchronize()
+    y_ref = oq.gemv_ref(q, scale, x)
+    y = y32.cpu().numpy().astype(np.float64)
+    rms = float(np.sqrt(np.mean(y_ref ** 2)))
+    assert (np.abs(y - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
+    yb = oq.bf16_to_f64(y16.cpu().numpy().view(np.uint16))
+    assert (np.abs(yb - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
+    got = out16.cpu().numpy().view(np.uint16).reshape(m.rows, m.cols)
+    rows = np.unique(np.concatenate([np.arange(0, m.rows, 97), [m.rows - 1]]))
+    assert np.array_equal(got[rows], oq.dequant_bf16(q[rows], scale[rows]))
