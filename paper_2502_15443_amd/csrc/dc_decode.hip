@@ -109,6 +109,30 @@ template <bool HALVES> __device__ __forceinline__ uint32_t lanes_last_nonzero_be
     return v;
 }
 
+// Sums `val` over runs of consecutive lanes with equal `key` (keys do not decrease with the lane;
+// key 0xFFFFFFFF = lane takes no part) and adds each run's sum to y[key] with one atomic, issued by
+// the last lane of the run.
+template <bool HALVES> __device__ __forceinline__ void lanes_add_by_key(float *__restrict__ y, uint32_t key, float val)
+{
+#define DC_SEG_STEP(CTRL, MASK)                                                                              \
+    {                                                                                                        \
+        const uint32_t k2 = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, CTRL, MASK, 0xF, false);     \
+        const float v2 = __uint_as_float(dpp_or_zero<CTRL, MASK>(__float_as_uint(val)));                     \
+        val += k2 == key ? v2 : 0.0f;                                                                        \
+    }
+    DC_SEG_STEP(0x111, 0xF)
+    DC_SEG_STEP(0x112, 0xF)
+    DC_SEG_STEP(0x114, 0xF)
+    DC_SEG_STEP(0x118, 0xF)
+    DC_SEG_STEP(0x142, 0xA)
+    if (!HALVES) DC_SEG_STEP(0x143, 0xC)
+#undef DC_SEG_STEP
+    // 0x130: the value of the lane above (lane 63 reads the fill value)
+    uint32_t above = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, 0x130, 0xF, 0xF, false);
+    if (HALVES && (threadIdx.x & 31u) == 31u) above = 0xFFFFFFFFu;
+    if (key != 0xFFFFFFFFu && above != key) atomicAdd(y + key, val);
+}
+
 // One sub-stream as its lane sees it.  Stream words travel memory -> blk -> LDS ring -> next -> buf.
 // The ring of a wave is 4 KiB, 4 KiB aligned; ring word j of the lane sits at byte
 // (j % 16) * 256 + lane * 4 of it, so the lanes of a wave never collide on a bank and the slot bits
@@ -557,8 +581,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
 
     if (MODE == kModeGemv) {
         // Partial dot products of byte^0x80 (1..255) with x; the -128*sum(x) term and the row scale
-        // are applied once per row by dc_gemv_finish_kernel.
-        uint32_t cur_row = row;
+        // are applied once per row by dc_gemv_finish_kernel.  A lane keeps the sum of its groups of
+        // one row; when some lane of the wave moves to another row, the wave adds its sums to y, one
+        // atomic per row it holds.
+        uint32_t cur_row = 0xFFFFFFFFu;
         float acc = 0.0f;
         for (uint32_t r = 0; r < rounds; r++) {
             const uint32_t start = r * round_bytes + ct * 16;
@@ -570,12 +596,13 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
+            if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) {
+                lanes_add_by_key<CPW == 2>(a.y_accum, cur_row < a.rows ? cur_row : 0xFFFFFFFFu, acc);
+                acc = 0.0f;
+                cur_row = 0xFFFFFFFFu;
+            }
             if (whole) {
-                if (row != cur_row) {
-                    if (cur_row < a.rows) atomicAdd(a.y_accum + cur_row, acc);
-                    acc = 0.0f;
-                    cur_row = row;
-                }
+                cur_row = row;
                 const uint4 *xp = reinterpret_cast<const uint4 *>(a.x_bf16 + col);
                 const uint4 xa = xp[0], xb = xp[1];
                 const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
@@ -591,7 +618,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             col += round_bytes;
             while (col >= cols) { col -= cols; row++; }
         }
-        if (cur_row < a.rows) atomicAdd(a.y_accum + cur_row, acc);
+        lanes_add_by_key<CPW == 2>(a.y_accum, cur_row < a.rows ? cur_row : 0xFFFFFFFFu, acc);
     }
 }
 
