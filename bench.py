@@ -234,7 +234,7 @@ def main() -> int:
         sweep = []
         for f in (0.0, 0.25, 0.5, 0.75, 1.0):
             pf = dc.Params(C, S, dc.POLICY_RAW_FRACTION, f)
-            lf = build_layer("llama7b", 0, True, pf, dc, synth, matrices=(0, 4))
+            lf = build_layer("llama7b", 0, True, pf, dc, synth)
             bd = [up(lf["blob"]) for _ in range(nbuf)]
             td = up(lf["table"])
             nb, nc = lf["q"].size, len(lf["table"])
@@ -246,7 +246,7 @@ def main() -> int:
                           "compression_ratio": round(nb / (lf["blob"].size + lf["table"].nbytes), 5),
                           "hbm_frac": round((nb + lf["blob"].size) / fms / 1e6 / HBM_PEAK_GBPS, 4), "exact": good})
             del bd, td
-        extras["raw_fraction_sweep_q_proj_plus_gate_proj"] = sweep
+        extras["raw_fraction_sweep"] = sweep
         out["extras"] = extras
 
     if not args.no_cpu:

@@ -364,6 +364,29 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     const uint32_t ring_lane = lds_address(lds_all + wave * (kRingWords * 64) + lane);
     constexpr bool UNI = CPW == 1; // all lanes of the wave belong to one stream set
 
+    // ---- raw chunks: the threads of the chunk copy it, eight 16-byte loads in flight per thread
+    if (MODE == kModeI8 && active && is_raw) {
+        uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
+        const uint32_t n16 = raw / 16;
+        for (uint32_t base = ct; base < n16; base += 8 * TPC) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (base + j * TPC < n16) v[j] = load16_stream(payload8 + 16 * (size_t)(base + j * TPC));
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (base + j * TPC < n16)
+                    __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4 *>(d8 + 16 * (size_t)(base + j * TPC)));
+        }
+        for (uint32_t i = n16 * 16 + ct; i < raw; i += TPC) d8[i] = payload8[i];
+    }
+    if (MODE != kModeI8 && !(active)) return;
+    if (MODE == kModeI8 && !huff) return;
+
+    // The table is only needed where a chunk of the workgroup is Huffman coded; the condition is the
+    // same for every thread that is still here, so the barriers inside are reached together.
+    const bool build_table = CPW == 1 ? huff : (bool)__any(huff);
+
     // ---- decode table.  Slot p of the table in code order (p = the next 11 stream bits, first bit
     // most significant) belongs to the code that covers p; codes in canonical order cover
     // consecutive runs of 2^(11-length) slots.  (1) The threads of the chunk rank the 256 code
@@ -371,7 +394,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     // the first slot of its run with its table entry.  (2) Every thread takes 2048/threads
     // consecutive slots, extends the marks forward over them, and writes the entries to the table
     // at the bit-reversed slot numbers (the stream is read least significant bit first).
-    {
+    if (build_table) {
         constexpr int EPT = kTableEntries / TPC; // slots a thread fills
         uint16_t *marks = reinterpret_cast<uint16_t *>(lds_all) + sub * kTableEntries;
         {
@@ -485,22 +508,6 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         }
         __syncthreads();
     }
-
-    // ---- raw chunks: the threads of the chunk copy it 16 bytes at a time
-    if (active && is_raw) {
-        if (MODE == kModeI8) {
-            uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
-            const uint32_t n16 = raw / 16;
-            for (uint32_t i = ct; i < n16; i += TPC) {
-                const u32x4 v = load16_stream(payload8 + 16 * (size_t)i);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d8 + 16 * (size_t)i));
-            }
-            for (uint32_t i = n16 * 16 + ct; i < raw; i += TPC) d8[i] = payload8[i];
-        }
-    }
-
-    if (MODE != kModeI8 && !(active)) return;
-    if (MODE == kModeI8 && !huff) return;
 
     // ---- sub-stream set-up: all lanes of a stream set are here together or not at all
     Region rg;
