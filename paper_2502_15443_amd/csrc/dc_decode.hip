@@ -7,8 +7,8 @@
 // Work decomposition: a lane owns one sub-stream, a wavefront owns one stream set (64 sub-streams
 // whose 16-byte blocks are stored interleaved in the order the wavefront asks for them), a workgroup
 // owns one chunk (S/64 wavefronts; with S = 32 one wavefront owns two chunks, lanes 0-31 / 32-63).
-// Per chunk the LDS holds the decode table (2048 x u16: symbol << 8 | length, indexed by the next 11
-// stream bits).  Per wavefront the LDS holds a ring of 16 stream words per lane.  Before every
+// Per chunk the LDS holds the decode table (2048 x u16: symbol << 8 | length - 1, indexed by the next
+// 11 stream bits).  Per wavefront the LDS holds a ring of 16 stream words per lane.  Before every
 // half group of 8 symbols the lanes that are short of look-ahead each take the next block of the
 // wavefront's region (consecutive lanes, consecutive blocks: one coalesced load, and the region is
 // read front to back exactly once); the block goes into the ring one step later, so the per-symbol
@@ -237,13 +237,30 @@ __device__ __forceinline__ void refill(Stream &s, uint32_t ring_lane)
     }
 }
 
-// Table entry = length | symbol << 8.  The shift unit reads only the low 6 bits of its amount, so
-// the entry is used unmasked there.
-__device__ __forceinline__ uint32_t symbol(Stream &s, uint32_t tbl)
+// Table entry = (length - 1) | symbol << 8: the field a 32-bit shift reads (its low 5 bits) is the
+// amount that turns "the next 11 bits, times 2" (the byte offset of the next table entry) into a
+// single shift and mask.
+__device__ __forceinline__ uint32_t table_entry(uint32_t tbl, uint32_t window_times_2)
 {
-    const uint32_t e = lds_load16(tbl + (((uint32_t)s.buf & (kTableEntries - 1)) << 1));
-    s.buf >>= (e & 63u);
-    return e;
+    return lds_load16(tbl + (window_times_2 & (2 * kTableEntries - 2)));
+}
+
+// The next N (2 or 3) symbols; at least 11*N bits are valid in buf.  With m_i = length_i - 1:
+// the offsets of the three entries are (lo << 1), (lo >> m_0) and (buf >> (m_0 + m_1 + 1)), each masked
+// to 0xFFE; the bits used are sum(m_i) + N.
+template <int N> __device__ __forceinline__ void symbols(Stream &s, uint32_t tbl, uint32_t *e)
+{
+    const uint32_t lo = (uint32_t)s.buf, hi = (uint32_t)(s.buf >> 32);
+    e[0] = table_entry(tbl, lo << 1);
+    e[1] = table_entry(tbl, lo >> (e[0] & 31u));
+    uint32_t used = e[0] + e[1] + 1;
+    if (N == 3) {
+        e[2] = table_entry(tbl, __builtin_amdgcn_alignbit(hi, lo, used));
+        used += e[2] + 1;
+    }
+    used += 1;
+    s.buf >>= (used & 63u);
+    s.state -= used & 0xFFu;
 }
 
 // bytes 1 of four entries -> one little-endian word of four symbols
@@ -254,23 +271,17 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// Symbols [8*HALF, 8*HALF + 8) of a group; refills before symbols 0, 3, 6 of the half.  The lengths
-// of the symbols between two refills leave `state` in one subtraction (their sum stays below 256).
+// Symbols [8*HALF, 8*HALF + 8) of a group: three refills, 3 + 3 + 2 symbols.
 template <int HALF>
 __device__ __forceinline__ void decode8(Stream &s, uint32_t tbl, uint32_t ring_lane, uint32_t out[4])
 {
     uint32_t e[8];
-#pragma unroll
-    for (int i = 0; i < 8; i += 3) {
-        refill(s, ring_lane);
-        uint32_t lens = 0;
-#pragma unroll
-        for (int j = i; j < i + 3 && j < 8; j++) {
-            e[j] = symbol(s, tbl);
-            lens += e[j];
-        }
-        s.state -= lens & 0xFFu;
-    }
+    refill(s, ring_lane);
+    symbols<3>(s, tbl, e);
+    refill(s, ring_lane);
+    symbols<3>(s, tbl, e + 3);
+    refill(s, ring_lane);
+    symbols<2>(s, tbl, e + 6);
     out[2 * HALF] = pack4(e[0], e[1], e[2], e[3]);
     out[2 * HALF + 1] = pack4(e[4], e[5], e[6], e[7]);
 }
@@ -290,8 +301,10 @@ __device__ __forceinline__ void decode16(Stream &s, Region &rg, uint32_t tbl, ui
 __device__ __forceinline__ uint32_t decode1(Stream &s, uint32_t tbl, uint32_t ring_lane)
 {
     refill(s, ring_lane);
-    const uint32_t e = symbol(s, tbl);
-    s.state -= e & 0xFFu;
+    const uint32_t e = table_entry(tbl, (uint32_t)s.buf << 1);
+    const uint32_t used = (e & 15u) + 1;
+    s.buf >>= used;
+    s.state -= used;
     return e >> 8;
 }
 
@@ -470,11 +483,12 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                     if (r == (uint32_t)q) before[q] += 1u << sh;
                 const uint32_t run = 1u << (kPeekBits - l);
                 const uint32_t start = first_of[l] + rank * run;
-                const uint16_t entry = (uint16_t)(l | ((ct * SPL + s) << 8));
+                const uint16_t entry = (uint16_t)((l - 1) | ((ct * SPL + s) << 8));
                 // also at the first slot of every later wave that the run reaches into, so that no
                 // wave needs a mark from another wave's slots
+                // (marks hold entry + 1, so that 0 means "no mark")
                 for (uint32_t p = start; p < start + run && p < (uint32_t)kTableEntries; p += kTableEntries / WAVES)
-                    marks[p] = entry;
+                    marks[p] = (uint16_t)(entry + 1);
             }
         }
         __syncthreads();
@@ -502,9 +516,9 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         for (int i = 0; i < EPT / 2; i++) {
             const uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
             cur = lo ? lo : cur;
-            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)cur;
+            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)(cur - 1);
             cur = hi ? hi : cur;
-            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i + 1)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)cur;
+            *(lds_u16 *)(uintptr_t)(out + 2 * ((__brev((uint32_t)(2 * i + 1)) >> (32 - E)) << (kPeekBits - E))) = (uint16_t)(cur - 1);
         }
         __syncthreads();
     }
