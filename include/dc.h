@@ -148,6 +148,23 @@ int dc_quantize_rows(const float *w_host, uint32_t rows, uint32_t cols, const fl
                      float *col_scale_host);
 
 /*
+ * The paper's own form of the compression stage (Section 3.2; Section 4.5 "scaled-tensor"): one
+ * scale for the whole tensor, and pruning by the importance score of Eq. 5.
+ *   W' = W * s with s_j = act_absmax_j ^ alpha (fp32 product; s = 1 when act_absmax_host is NULL),
+ *   m = max |W'_ij| over the tensor, scale = m / 127 (fp32; 1 if m == 0),
+ *   q_ij = clamp(round-half-even(W'_ij / scale), -127, 127),
+ *   score_ij = act_absmax_j * |q_ij| (evaluated in fp64; |q_ij| alone when act_absmax_host is NULL),
+ *   k = floor(sparsity * rows * cols); if k > 0 every q_ij whose score is <= the k-th smallest score
+ *   becomes 0 (scores equal to the threshold are pruned together).
+ *   tensor_scale_host  out: the one fp32 scale; dequantised weight = q * scale
+ *   col_scale_host     out, may be NULL: the s_j that were applied
+ * Errors: DC_E_ARG for null pointers, zero sizes, sparsity outside [0, 1).
+ */
+int dc_quantize_tensor(const float *w_host, uint32_t rows, uint32_t cols, const float *act_absmax_host,
+                       double alpha, double sparsity, int8_t *q_host, float *tensor_scale_host,
+                       float *col_scale_host);
+
+/*
  * Worst-case blob size and number of chunks for raw_bytes input bytes (Section 3.3: the weight
  * data is divided into data chunks).  Either output pointer may be NULL.
  */

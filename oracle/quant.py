@@ -37,6 +37,16 @@ def quantise_rows(w: np.ndarray):
     return q, scale
 
 
+def quantise_tensor(w: np.ndarray):
+    """Symmetric per-tensor absmax INT8 (Eq. 4 with the paper's own granularity, Section 4.5
+    "scaled-tensor"): scale = max |W'| / 127 (fp32), q = clip(rint(W'/scale), -127, 127)."""
+    assert w.dtype == np.float32
+    m = np.max(np.abs(w))
+    scale = np.float32(1.0) if m == 0 else np.float32(m / np.float32(127.0))
+    q = np.clip(np.rint(w / scale), -127, 127).astype(np.int8)
+    return q, scale
+
+
 def prune(q: np.ndarray) -> np.ndarray:
     """Quantised weights of magnitude <= 1 become 0 (fixed-threshold form of the score rule, Eq. 5)."""
     out = q.copy()

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     version,
     set_num_threads,
     quantize_rows,
+    quantize_tensor,
     compress_bound,
     compress_chunks,
     validate,

@@ -79,6 +79,8 @@ def _load():
     L.dc_set_num_threads.argtypes = [i32]
     L.dc_quantize_rows.restype = i32
     L.dc_quantize_rows.argtypes = [vp, u32, u32, vp, C.c_double, u32, vp, vp, vp]
+    L.dc_quantize_tensor.restype = i32
+    L.dc_quantize_tensor.argtypes = [vp, u32, u32, vp, C.c_double, C.c_double, vp, vp, vp]
     L.dc_compress_bound.restype = i32
     L.dc_compress_bound.argtypes = [u64, pp, pu64, pu64]
     L.dc_compress_chunks.restype = i32
@@ -146,6 +148,22 @@ def quantize_rows(w: np.ndarray, act_absmax: Optional[np.ndarray] = None, alpha:
     _check(_L.dc_quantize_rows(_host(w), rows, cols, None if a is None else _host(a), float(alpha),
                                int(prune_abs), _host(q), _host(rs), _host(cs)), "dc_quantize_rows")
     return q, rs, cs
+
+
+def quantize_tensor(w: np.ndarray, act_absmax: Optional[np.ndarray] = None, alpha: float = 0.5,
+                    sparsity: float = 0.0) -> Tuple[np.ndarray, float, np.ndarray]:
+    """dc_quantize_tensor: fp32 W[rows, cols] -> (int8 q, fp32 tensor scale, fp32 col_scale[cols])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    rows, cols = w.shape
+    a = None if act_absmax is None else np.ascontiguousarray(act_absmax, dtype=np.float32)
+    if a is not None and a.shape != (cols,):
+        raise ValueError("act_absmax must have one value per column")
+    q = np.empty((rows, cols), dtype=np.int8)
+    ts = np.empty(1, dtype=np.float32)
+    cs = np.empty(cols, dtype=np.float32)
+    _check(_L.dc_quantize_tensor(_host(w), rows, cols, None if a is None else _host(a), float(alpha),
+                                 float(sparsity), _host(q), _host(ts), _host(cs)), "dc_quantize_tensor")
+    return q, float(ts[0]), cs
 
 
 def compress_bound(raw_bytes: int, params: Params) -> Tuple[int, int]:

@@ -336,6 +336,68 @@ extern "C" int dc_quantize_rows(const float *w, uint32_t rows, uint32_t cols, co
     return DC_OK;
 }
 
+extern "C" int dc_quantize_tensor(const float *w, uint32_t rows, uint32_t cols, const float *act_absmax,
+                                  double alpha, double sparsity, int8_t *q, float *tensor_scale,
+                                  float *col_scale_out)
+{
+    if (!w || !q || !tensor_scale || rows == 0 || cols == 0 || !(sparsity >= 0.0 && sparsity < 1.0)) return DC_E_ARG;
+    std::vector<float> s(cols, 1.0f);
+    if (act_absmax)
+        for (uint32_t j = 0; j < cols; j++) s[j] = (float)std::pow((double)act_absmax[j], alpha);
+    if (col_scale_out) std::copy(s.begin(), s.end(), col_scale_out);
+    const uint64_t n = (uint64_t)rows * cols;
+
+    // pass 1: maximum of the rescaled tensor
+    std::vector<float> row_max(rows, 0.0f);
+    parallel_ranges(rows, [&](uint64_t r0, uint64_t r1) {
+        for (uint64_t i = r0; i < r1; i++) {
+            const float *wr = w + i * cols;
+            float m = 0.0f;
+            for (uint32_t j = 0; j < cols; j++) m = std::max(m, std::fabs(wr[j] * s[j]));
+            row_max[i] = m;
+        }
+    });
+    float m = 0.0f;
+    for (uint32_t i = 0; i < rows; i++) m = std::max(m, row_max[i]);
+    const float sc = m == 0.0f ? 1.0f : m / 127.0f;
+    *tensor_scale = sc;
+
+    // pass 2: quantise
+    parallel_ranges(rows, [&](uint64_t r0, uint64_t r1) {
+        for (uint64_t i = r0; i < r1; i++) {
+            const float *wr = w + i * cols;
+            int8_t *qr = q + i * cols;
+            for (uint32_t j = 0; j < cols; j++) {
+                float r = std::nearbyintf((wr[j] * s[j]) / sc);
+                r = std::min(127.0f, std::max(-127.0f, r));
+                qr[j] = (int8_t)(int)r;
+            }
+        }
+    });
+
+    // pass 3: prune the k lowest importance scores (Eq. 5)
+    const uint64_t k = (uint64_t)std::floor(sparsity * (double)n);
+    if (k == 0) return DC_OK;
+    auto score = [&](uint64_t i, uint32_t j) {
+        const double mag = (double)std::abs((int)q[i * cols + j]);
+        return act_absmax ? mag * (double)act_absmax[j] : mag;
+    };
+    std::vector<double> all(n);
+    parallel_ranges(rows, [&](uint64_t r0, uint64_t r1) {
+        for (uint64_t i = r0; i < r1; i++)
+            for (uint32_t j = 0; j < cols; j++) all[i * cols + j] = score(i, j);
+    });
+    std::nth_element(all.begin(), all.begin() + (k - 1), all.end());
+    const double thr = all[k - 1];
+    std::vector<double>().swap(all);
+    parallel_ranges(rows, [&](uint64_t r0, uint64_t r1) {
+        for (uint64_t i = r0; i < r1; i++)
+            for (uint32_t j = 0; j < cols; j++)
+                if (score(i, j) <= thr) q[i * cols + j] = 0;
+    });
+    return DC_OK;
+}
+
 extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, uint64_t *max_blob_bytes,
                                  uint64_t *n_chunks)
 {

@@ -57,6 +57,28 @@ def test_quantize_rows_other_exponents(alpha):
     assert np.array_equal(cs, s) and np.array_equal(q, oq.prune(q_ref)) and np.array_equal(rs, rs_ref)
 
 
+@pytest.mark.parametrize("alpha", [0.0, 0.5, 1.0])
+@pytest.mark.parametrize("sparsity", [0.0, 0.2, 0.4])
+def test_quantize_tensor_matches_oracle_bit_for_bit(alpha, sparsity):
+    """The paper's own front end: one scale per tensor, pruning by the importance score (Eq. 5)."""
+    rows, cols, seed = 160, 768, synth.matrix_seed(4, 1)
+    w = synth.gen_weight(rows, cols, seed)
+    a = synth.gen_act_absmax(cols, seed)
+    q, ts, cs = dc.quantize_tensor(w, a, alpha, sparsity)
+    s = oq.channel_scale(a, alpha)
+    q_ref, ts_ref = oq.quantise_tensor(oq.rescale(w, s))
+    q_ref = oq.prune_by_score(q_ref, a, sparsity)
+    assert np.array_equal(cs, s) and np.float32(ts) == ts_ref and np.array_equal(q, q_ref)
+    assert np.mean(q == 0) >= sparsity
+    # without activation statistics the score is the magnitude
+    q1, ts1, cs1 = dc.quantize_tensor(w, None, alpha, sparsity)
+    q1_ref, ts1_ref = oq.quantise_tensor(w)
+    assert (cs1 == 1).all() and np.float32(ts1) == ts1_ref
+    assert np.array_equal(q1, oq.prune_by_score(q1_ref, np.ones(cols, np.float32), sparsity))
+    with pytest.raises(dc.DCError):
+        dc.quantize_tensor(w, a, alpha, 1.0)
+
+
 @pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("n,C", [(5 * 16384 + 777, 16384), (3 * 65536, 65536), (100, 65536), (65536 + 16, 65536),
                                  (7 * 4096 + 4095, 4096)])

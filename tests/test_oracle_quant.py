@@ -70,6 +70,26 @@ def test_zero_row():
     assert s[2] == 1.0 and not q[2].any()
 
 
+def test_quantise_tensor_one_scale_for_all_rows():
+    w = small_w(64, 256, 12)
+    q, scale = oq.quantise_tensor(w)
+    assert scale.dtype == np.float32 and scale == np.float32(np.abs(w).max() / np.float32(127.0))
+    i, j = np.unravel_index(np.argmax(np.abs(w)), w.shape)
+    assert abs(int(q[i, j])) == 127  # the largest magnitude takes the end of the range
+    assert (np.abs(w - q.astype(np.float32) * scale) <= scale * 0.5000001).all()
+    # a power-of-two gain on the whole tensor changes the scale, not the codes
+    q4, scale4 = oq.quantise_tensor(w * np.float32(4.0))
+    assert np.array_equal(q4, q) and scale4 == scale * 4
+    # rows of equal largest magnitude: per-tensor and per-row quantisation coincide
+    w2 = w / np.abs(w).max(axis=1, keepdims=True)
+    qt, st = oq.quantise_tensor(w2)
+    qr, sr = oq.quantise_rows(w2)
+    assert np.array_equal(qt, qr) and (sr == st).all()
+    # an all-zero tensor
+    qz, sz = oq.quantise_tensor(np.zeros((3, 5), np.float32))
+    assert sz == 1 and not qz.any()
+
+
 def test_prune_removes_plus_minus_one_only():
     q = np.arange(-127, 128, dtype=np.int16).astype(np.int8).reshape(1, -1)
     p = oq.prune(q)
