@@ -90,6 +90,106 @@ def time_launches(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall / steps
 
 
+def layer_streaming(torch, dc, synth, params, n_layers=8, reps=3):
+    """The paper's runtime loop (Section 3.3, case (b): everything in GPU memory) on the Llama-7B-shaped
+    layer: per-layer latency of batch-1 inference (seven matrix-vector products a layer) with the
+    weights (i) resident uncompressed, (ii) decoded into the decompression buffer and then used, on one
+    stream, (iii) the same with the decode of layer l+1 on a second stream while layer l computes
+    (two buffers), (iv) through the fused decode+product call, and (iii) again with part of the chunks
+    stored raw.  Every layer uses the same weights (distinct buffers); times are wall-clock per layer."""
+    S, C = params.n_streams, params.chunk_bytes
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
+
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    out = {"n_layers": n_layers, "n_streams": S}
+    lay = build_layer("llama7b", 0, True, params, dc, synth)
+    raw_bytes = lay["q"].size
+    scales = [torch.from_numpy(s).cuda() for s in lay["scales"]]
+    xs = [torch.from_numpy(synth.gen_activation_bf16(sl["cols"], sl["seed"]).view(np.int16)).cuda() for sl in lay["slices"]]
+    ys = [torch.empty(sl["rows"], dtype=torch.float32, device="cuda") for sl in lay["slices"]]
+    bufs = [torch.empty(raw_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    offs = np.cumsum([0] + [sl["rows"] * sl["cols"] for sl in lay["slices"]])
+
+    def compute(buf, st):
+        for j, sl in enumerate(lay["slices"]):
+            dc.gemv_i8(buf.data_ptr() + int(offs[j]), scales[j], sl["rows"], sl["cols"], xs[j], ys[j], None, st.cuda_stream)
+
+    def wall(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / (reps * n_layers)
+
+    def variant(l):
+        blobs = [up(l["blob"]) for _ in range(2)]
+        table = up(l["table"])
+        nb, nc = l["blob"].size, len(l["table"])
+
+        def decode(i, st):
+            dc.decompress_chunks(blobs[i % 2], nb, table, nc, params, bufs[i % 2], raw_bytes, st.cuda_stream)
+
+        def decode_only():
+            for i in range(n_layers):
+                decode(i, main)
+
+        def serial():
+            for i in range(n_layers):
+                decode(i, main)
+                compute(bufs[i % 2], main)
+
+        def overlapped():
+            done = [None, None]  # compute that last read each buffer
+            for i in range(n_layers):
+                if done[i % 2] is not None:
+                    side.wait_event(done[i % 2])
+                decode(i, side)
+                ready = torch.cuda.Event()
+                ready.record(side)
+                main.wait_event(ready)
+                compute(bufs[i % 2], main)
+                done[i % 2] = torch.cuda.Event()
+                done[i % 2].record(main)
+            side.synchronize()
+
+        return blobs, table, wall(decode_only), wall(serial), wall(overlapped)
+
+    blobs, table, d_ms, ser_ms, ovl_ms = variant(lay)
+    # decoded weights are now in bufs: the resident case
+    i_ms = wall(lambda: [compute(bufs[i % 2], main) for i in range(n_layers)])
+
+    def fused():
+        for i in range(n_layers):
+            for j, sl in enumerate(lay["slices"]):
+                dc.decompress_gemv(blobs[i % 2], lay["blob"].size, table.data_ptr() + 16 * sl["k0"], sl["n_chunks"], params,
+                                   scales[j], sl["rows"], sl["cols"], xs[j], ys[j], None, main.cuda_stream)
+
+    f_ms = wall(fused)
+    out["ms_per_layer"] = {"resident_compute_I": round(i_ms, 4), "decode_D": round(d_ms, 4),
+                           "decode_then_compute_one_stream": round(ser_ms, 4),
+                           "decode_next_layer_on_second_stream": round(ovl_ms, 4), "fused_decode_product": round(f_ms, 4)}
+    out["model_ms_per_layer"] = {"one_stream_D_plus_I": round(d_ms + i_ms, 4), "overlapped_max_D_I": round(max(d_ms, i_ms), 4)}
+    out["overhead_vs_resident"] = {"one_stream": round(ser_ms / i_ms - 1, 3), "second_stream": round(ovl_ms / i_ms - 1, 3),
+                                   "fused": round(f_ms / i_ms - 1, 3)}
+    out["compression_ratio"] = round(raw_bytes / (lay["blob"].size + lay["table"].nbytes), 5)
+    del blobs, table
+    partial = []
+    for f in (0.5, 0.8):
+        pf = dc.Params(C, S, dc.POLICY_RAW_FRACTION, f)
+        lf = build_layer("llama7b", 0, True, pf, dc, synth)
+        _, _, dm, sm, om = variant(lf)
+        partial.append({"raw_fraction": f, "compression_ratio": round(raw_bytes / (lf["blob"].size + lf["table"].nbytes), 5),
+                        "decode_D": round(dm, 4), "one_stream": round(sm, 4), "second_stream": round(om, 4),
+                        "overhead_vs_resident_second_stream": round(om / i_ms - 1, 3)})
+    out["speed_adaptive"] = partial
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -272,6 +372,7 @@ def main() -> int:
             f = r["raw_fraction"]
             r["model_GBps"] = round(1.0 / ((1 - f) / d0 + f / d1), 1)
         extras["raw_fraction_sweep"] = sweep
+        extras["layer_streaming"] = layer_streaming(torch, dc, synth, params)
         out["extras"] = extras
 
     if not args.no_cpu:

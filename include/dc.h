@@ -232,6 +232,16 @@ int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_ch
                        uint16_t *y_bf16_dev, void *hip_stream);
 
 /*
+ * Batch-1 product on weights that are already in the decompression buffer: the "model inference
+ * computation" that reads the buffer in Section 3.3 (I_gpu of Eq. 12), Eq. 1 for one activation row:
+ *   y_i = row_scale[i] * sum_j q_ij * x_j,   q int8 row-major [rows][cols], x bf16, fp32 accumulation.
+ * q_dev and x_bf16_dev 16-byte aligned, cols a multiple of 16.  y_f32_dev receives rows fp32 values,
+ * y_bf16_dev (may be NULL) the same rounded to bf16.  One launch, asynchronous on hip_stream.
+ */
+int dc_gemv_i8(const int8_t *q_dev, const float *row_scale_dev, uint32_t rows, uint32_t cols,
+               const uint16_t *x_bf16_dev, float *y_f32_dev, uint16_t *y_bf16_dev, void *hip_stream);
+
+/*
  * Plain device copy kernel (reads n bytes, writes n bytes, 16-byte aligned): the denominator for
  * "share of achievable bandwidth" next to the decode kernels (cf. B_gpu in Eq. 11).
  */

@@ -26,5 +26,6 @@ from .binding import (  # noqa: F401
     decompress_chunks,
     decompress_dequant_bf16,
     decompress_gemv,
+    gemv_i8,
     device_copy,
 )

@@ -93,6 +93,8 @@ def _load():
     L.dc_decompress_dequant_bf16.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, u64, vp]
     L.dc_decompress_gemv.restype = i32
     L.dc_decompress_gemv.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, vp, vp, vp]
+    L.dc_gemv_i8.restype = i32
+    L.dc_gemv_i8.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
     L.dc_device_copy.restype = i32
     L.dc_device_copy.argtypes = [vp, vp, u64, vp]
     return L
@@ -218,6 +220,11 @@ def decompress_gemv(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params:
     _check(_L.dc_decompress_gemv(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
                                  _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_accum_dev),
                                  _dev(y_bf16_dev), stream), "dc_decompress_gemv")
+
+
+def gemv_i8(q_dev, row_scale_dev, rows: int, cols: int, x_bf16_dev, y_f32_dev, y_bf16_dev=None, stream: int = 0) -> None:
+    _check(_L.dc_gemv_i8(_dev(q_dev), _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_f32_dev),
+                         _dev(y_bf16_dev), stream), "dc_gemv_i8")
 
 
 def device_copy(src_dev, dst_dev, nbytes: int, stream: int = 0) -> None:

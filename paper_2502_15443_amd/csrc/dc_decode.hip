@@ -671,6 +671,78 @@ __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(float *y_accum, uin
     }
 }
 
+// Sum over the 64 lanes, result in lane 63.
+__device__ __forceinline__ float lanes_sum(float v)
+{
+#define DC_SUM_STEP(CTRL, MASK) v += __uint_as_float(dpp_or_zero<CTRL, MASK>(__float_as_uint(v)));
+    DC_SUM_STEP(0x111, 0xF)
+    DC_SUM_STEP(0x112, 0xF)
+    DC_SUM_STEP(0x114, 0xF)
+    DC_SUM_STEP(0x118, 0xF)
+    DC_SUM_STEP(0x142, 0xA)
+    DC_SUM_STEP(0x143, 0xC)
+#undef DC_SUM_STEP
+    return v;
+}
+
+// Batch-1 product on weights that are already decoded: y_i = scale_i * sum_j q_ij x_j, q int8 row-major.
+// A wave owns kGemvRows consecutive rows and walks the columns 16 bytes a lane (1 KiB a wave and row),
+// so that x is converted once for all its rows; the weights enter as byte ^ 0x80 (one conversion
+// instruction a byte) and the -128 * sum(x) term is taken out at the end.
+constexpr int kGemvRows = 4;
+__global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restrict__ q, const float *__restrict__ row_scale,
+                                                         uint32_t rows, uint32_t cols, const uint16_t *__restrict__ x_bf16,
+                                                         float *__restrict__ y_f32, uint16_t *__restrict__ y_bf16)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kGemvRows;
+    if (row0 >= rows) return;
+    const uint8_t *qr[kGemvRows];
+#pragma unroll
+    for (int r = 0; r < kGemvRows; r++) {
+        const uint32_t row = row0 + r < rows ? row0 + r : rows - 1; // rows past the end repeat the last one
+        qr[r] = q + (size_t)row * cols;
+    }
+    float acc[kGemvRows] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float xsum = 0.0f;
+    for (uint32_t c = lane * 16; c < cols; c += 1024) {
+        u32x4 w[kGemvRows];
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++) w[r] = load16_stream(qr[r] + c);
+        const uint4 *xp = reinterpret_cast<const uint4 *>(x_bf16 + c);
+        const uint4 xa = xp[0], xb = xp[1];
+        const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+        float xf[16];
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            xf[2 * i] = bf16_bits_to_f32(xs[i] & 0xFFFFu);
+            xf[2 * i + 1] = __uint_as_float(xs[i] & 0xFFFF0000u);
+            xsum += xf[2 * i] + xf[2 * i + 1];
+        }
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t u = w[r][i] ^ 0x80808080u;
+                acc[r] = __builtin_fmaf((float)(u & 0xFFu), xf[4 * i], acc[r]);
+                acc[r] = __builtin_fmaf((float)((u >> 8) & 0xFFu), xf[4 * i + 1], acc[r]);
+                acc[r] = __builtin_fmaf((float)((u >> 16) & 0xFFu), xf[4 * i + 2], acc[r]);
+                acc[r] = __builtin_fmaf((float)(u >> 24), xf[4 * i + 3], acc[r]);
+            }
+        }
+    }
+    xsum = lanes_sum(xsum);
+#pragma unroll
+    for (int r = 0; r < kGemvRows; r++) {
+        const float total = lanes_sum(acc[r]);
+        if (lane == 63 && row0 + r < rows) {
+            const float y = row_scale[row0 + r] * (total - 128.0f * xsum);
+            y_f32[row0 + r] = y;
+            if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void dc_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, uint64_t n16)
 {
     const uint64_t stride = (uint64_t)gridDim.x * 256;
@@ -795,6 +867,18 @@ extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, 
 }
 
 extern "C" const char *dc_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
+
+extern "C" int dc_gemv_i8(const int8_t *q_dev, const float *row_scale_dev, uint32_t rows, uint32_t cols,
+                          const uint16_t *x_bf16_dev, float *y_f32_dev, uint16_t *y_bf16_dev, void *hip_stream)
+{
+    if (!q_dev || !row_scale_dev || !x_bf16_dev || !y_f32_dev || rows == 0 || cols == 0 || cols % 16) return DC_E_ARG;
+    if (!aligned16(q_dev) || !aligned16(x_bf16_dev)) return DC_E_ARG;
+    const uint32_t blocks = (rows + 4 * kGemvRows - 1) / (4 * kGemvRows);
+    hipLaunchKernelGGL(dc_gemv_i8_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const uint8_t *>(q_dev), row_scale_dev, rows, cols, x_bf16_dev, y_f32_dev,
+                       y_bf16_dev);
+    return launch_status();
+}
 
 extern "C" int dc_device_copy(const void *src_dev, void *dst_dev, uint64_t bytes, void *hip_stream)
 {

@@ -163,6 +163,28 @@ def test_gemv_within_tolerance(S, rows, cols, C, f):
     assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 16), (7, 1040), (64, 4096), (37, 13824), (530, 5120)])
+def test_gemv_i8_on_decoded_weights(rows, cols):
+    """The plain product on weights in the decompression buffer against the fp64 reference."""
+    print(f"case gemv_i8 {rows}x{cols}", flush=True)
+    seed = synth.matrix_seed(3, 6)
+    q, scale = oracle_matrix(rows, cols, seed, False)
+    x = synth.gen_activation_bf16(cols, seed)
+    y_ref = oq.gemv_ref(q, scale, x)
+    q_d, scale_d = dev(q), torch.from_numpy(scale).cuda()
+    x_d = torch.from_numpy(x.view(np.int16)).cuda()
+    y32 = torch.full((rows + 3,), 7.0, dtype=torch.float32, device="cuda")
+    y16 = torch.zeros(rows, dtype=torch.int16, device="cuda")
+    dc.gemv_i8(q_d, scale_d, rows, cols, x_d, y32, y16, stream())
+    torch.cuda.synchronize()
+    y = y32.cpu().numpy()
+    assert (y[rows:] == 7.0).all()  # nothing written past the last row
+    assert gemv_check(y[:rows], y_ref) < 1e-4
+    assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y[:rows]))
+    with pytest.raises(dc.DCError):
+        dc.gemv_i8(q_d, scale_d, rows, cols + 8, x_d, y32, y16, stream())
+
+
 def test_config1_full_size_bit_exact_and_ratio():
     """4096x4096, 64 KiB chunks, 32 sub-streams, all chunks Huffman coded."""
     q, scale = oracle_matrix(4096, 4096, synth.matrix_seed(0, 0), False)
