@@ -163,11 +163,13 @@ def layer_streaming(torch, dc, synth, params, n_layers=8, reps=3):
     # decoded weights are now in bufs: the resident case
     i_ms = wall(lambda: [compute(bufs[i % 2], main) for i in range(n_layers)])
 
+    mats = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales[j], x_bf16_dev=xs[j], y_accum_dev=ys[j])
+            for j, sl in enumerate(lay["slices"])]
+
     def fused():
         for i in range(n_layers):
-            for j, sl in enumerate(lay["slices"]):
-                dc.decompress_gemv(blobs[i % 2], lay["blob"].size, table.data_ptr() + 16 * sl["k0"], sl["n_chunks"], params,
-                                   scales[j], sl["rows"], sl["cols"], xs[j], ys[j], None, main.cuda_stream)
+            dc.decompress_gemv_layer(blobs[i % 2], lay["blob"].size, table, len(lay["table"]), params, mats,
+                                     main.cuda_stream)
 
     f_ms = wall(fused)
     out["ms_per_layer"] = {"resident_compute_I": round(i_ms, 4), "decode_D": round(d_ms, 4),
@@ -340,7 +342,29 @@ def main() -> int:
                                    scales_d[j], sl["rows"], sl["cols"], xs[j], ys[j], None, stream)
 
         gms, _ = time_launches(torch, gemv, 30, 3)
+        # the same through the whole-layer calls: one launch over all 4840 chunks
+        mats_b = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales_d[j], dst_bf16_dev=None, dst_cap_elems=sl["rows"] * sl["cols"])
+                  for j, sl in enumerate(l13["slices"])]
+        layer16 = [torch.empty(raw13, dtype=torch.int16, device="cuda") for _ in range(2)]
+        offs13 = np.cumsum([0] + [sl["rows"] * sl["cols"] for sl in l13["slices"]])
+
+        def dequant_layer(i):
+            for j, m in enumerate(mats_b):
+                m.dst_bf16_dev = layer16[i % 2].data_ptr() + 2 * int(offs13[j])
+            dc.decompress_dequant_bf16_layer(b13[i % 2], blob13, t13, len(l13["table"]), params, mats_b, stream)
+
+        dlms, _ = time_launches(torch, dequant_layer, 30, 3)
+        mats_g = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales_d[j], x_bf16_dev=xs[j], y_accum_dev=ys[j])
+                  for j, sl in enumerate(l13["slices"])]
+        glms, _ = time_launches(
+            torch, lambda i: dc.decompress_gemv_layer(b13[i % 2], blob13, t13, len(l13["table"]), params, mats_g, stream),
+            30, 3)
+        del layer16
         extras["fused_llama13b_layer"] = {
+            "whole_layer_call": {"dequant_bf16_int8_GBps": round(raw13 / dlms / 1e6, 1),
+                                 "dequant_bf16_hbm_frac": round((blob13 + 2 * raw13) / dlms / 1e6 / HBM_PEAK_GBPS, 4),
+                                 "gemv_weights_GBps": round(raw13 / glms / 1e6, 1),
+                                 "gemv_hbm_frac": round(blob13 / glms / 1e6 / HBM_PEAK_GBPS, 4)},
             "raw_bytes": int(raw13), "n_chunks": len(l13["table"]),
             "compression_ratio": round(raw13 / (blob13 + l13["table"].nbytes), 5),
             "dequant_bf16_int8_GBps": round(raw13 / dms / 1e6, 1),

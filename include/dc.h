@@ -94,6 +94,7 @@ extern "C" {
 #define DC_BLOB_TAIL_BYTES 64
 #define DC_BLOCK_BYTES 16
 #define DC_LOOKAHEAD_BITS 320
+#define DC_MAX_MATRICES 16
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */
@@ -119,6 +120,19 @@ typedef struct {
     uint32_t reserved;      /* 0 */
     const uint8_t *raw_mask; /* DC_POLICY_RAW_MASK: host array of n_chunks bytes, else NULL */
 } dc_params;
+
+/* One matrix of a fused whole-layer call (host struct; the pointers inside are device pointers). */
+typedef struct {
+    uint64_t first_chunk;         /* table index of the matrix's first chunk; the matrices follow each other
+                                     in the table, each starting at a chunk of its own (compressed on its own) */
+    uint32_t rows, cols;          /* decoded bytes are int8 q[rows][cols]; cols a multiple of 16 */
+    const float *row_scale_dev;   /* fp32 scale per row */
+    uint16_t *dst_bf16_dev;       /* dequant: bf16 [rows][cols], 16-byte aligned */
+    uint64_t dst_cap_elems;       /* dequant: capacity of dst_bf16_dev in elements */
+    const uint16_t *x_bf16_dev;   /* gemv: cols bf16 activations, 16-byte aligned; cols <= 16384 */
+    float *y_accum_dev;           /* gemv: rows fp32 results (zeroed by the call) */
+    uint16_t *y_bf16_dev;         /* gemv: rows bf16 results, may be NULL */
+} dc_matrix;
 
 /* Library identification string (static storage). */
 const char *dc_version(void);
@@ -230,6 +244,20 @@ int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_ch
                        uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
                        uint32_t rows, uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev,
                        uint16_t *y_bf16_dev, void *hip_stream);
+
+/*
+ * The two fused calls for all matrices of a layer at once (Section 3.3 lets the decompression
+ * granularity be a layer; one launch over all chunks keeps the GPU filled where a single matrix
+ * cannot).  mats_host: n_mats <= DC_MAX_MATRICES descriptors in table order; the chunk counts of the
+ * matrices must add up to n_chunks.  Same arithmetic, outputs and errors as the single-matrix calls,
+ * which are these calls with one matrix.
+ */
+int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                     uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                     uint32_t n_mats, void *hip_stream);
+int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                             uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                             uint32_t n_mats, void *hip_stream);
 
 /*
  * Batch-1 product on weights that are already in the decompression buffer: the "model inference

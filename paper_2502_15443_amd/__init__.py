@@ -26,6 +26,9 @@ from .binding import (  # noqa: F401
     decompress_chunks,
     decompress_dequant_bf16,
     decompress_gemv,
+    decompress_dequant_bf16_layer,
+    decompress_gemv_layer,
+    Matrix,
     gemv_i8,
     device_copy,
 )

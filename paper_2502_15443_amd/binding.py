@@ -32,6 +32,26 @@ class _CParams(C.Structure):
                 ("raw_mask", C.c_void_p)]
 
 
+class _CMatrix(C.Structure):
+    _fields_ = [("first_chunk", C.c_uint64), ("rows", C.c_uint32), ("cols", C.c_uint32),
+                ("row_scale_dev", C.c_void_p), ("dst_bf16_dev", C.c_void_p), ("dst_cap_elems", C.c_uint64),
+                ("x_bf16_dev", C.c_void_p), ("y_accum_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p)]
+
+
+@dataclass
+class Matrix:
+    """One matrix of a whole-layer fused call (dc_matrix): device buffers are tensors or addresses."""
+    first_chunk: int
+    rows: int
+    cols: int
+    row_scale_dev: object
+    dst_bf16_dev: object = None
+    dst_cap_elems: int = 0
+    x_bf16_dev: object = None
+    y_accum_dev: object = None
+    y_bf16_dev: object = None
+
+
 @dataclass
 class Params:
     chunk_bytes: int = 65536
@@ -93,6 +113,11 @@ def _load():
     L.dc_decompress_dequant_bf16.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, u64, vp]
     L.dc_decompress_gemv.restype = i32
     L.dc_decompress_gemv.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, vp, vp, vp]
+    pm = C.POINTER(_CMatrix)
+    L.dc_decompress_dequant_bf16_layer.restype = i32
+    L.dc_decompress_dequant_bf16_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
+    L.dc_decompress_gemv_layer.restype = i32
+    L.dc_decompress_gemv_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
     L.dc_gemv_i8.restype = i32
     L.dc_gemv_i8.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
     L.dc_device_copy.restype = i32
@@ -220,6 +245,31 @@ def decompress_gemv(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params:
     _check(_L.dc_decompress_gemv(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
                                  _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_accum_dev),
                                  _dev(y_bf16_dev), stream), "dc_decompress_gemv")
+
+
+def _matrices(mats):
+    arr = (_CMatrix * len(mats))()
+    for i, m in enumerate(mats):
+        arr[i] = _CMatrix(m.first_chunk, m.rows, m.cols, _dev(m.row_scale_dev) or None, _dev(m.dst_bf16_dev) or None,
+                          m.dst_cap_elems, _dev(m.x_bf16_dev) or None, _dev(m.y_accum_dev) or None,
+                          _dev(m.y_bf16_dev) or None)
+    return arr
+
+
+def decompress_dequant_bf16_layer(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, mats,
+                                  stream: int = 0) -> None:
+    cp = params._c()
+    arr = _matrices(mats)
+    _check(_L.dc_decompress_dequant_bf16_layer(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
+                                               arr, len(mats), stream), "dc_decompress_dequant_bf16_layer")
+
+
+def decompress_gemv_layer(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, mats,
+                          stream: int = 0) -> None:
+    cp = params._c()
+    arr = _matrices(mats)
+    _check(_L.dc_decompress_gemv_layer(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp), arr,
+                                       len(mats), stream), "dc_decompress_gemv_layer")
 
 
 def gemv_i8(q_dev, row_scale_dev, rows: int, cols: int, x_bf16_dev, y_f32_dev, y_bf16_dev=None, stream: int = 0) -> None:

@@ -49,19 +49,29 @@ template <int S> struct Geometry {
     static constexpr int kSymbolsPerLane = 256 / kThreadsPerChunk; // header values a thread ranks in the table build
 };
 
+// One matrix of a fused call: its chunks are table entries [first_chunk, next matrix's first_chunk).
+struct MatrixArgs {
+    uint64_t first_chunk;
+    uint32_t rows, cols;
+    const float *row_scale;
+    void *dst;              // kModeBf16: bf16 [rows][cols]
+    const uint16_t *x_bf16; // kModeGemv
+    float *y_accum;         // kModeGemv
+    uint16_t *y_bf16;       // kModeGemv, may be null
+};
+
 struct DecodeArgs {
     const uint8_t *blob;
     uint64_t blob_bytes;
     const dc_chunk *table;
     uint64_t n_chunks;
     uint32_t chunk_bytes;
-    // kModeI8: dst = int8 bytes, dst_cap in bytes.  kModeBf16: dst = bf16, dst_cap in elements.
+    // kModeI8: all chunks decode into one buffer of dst_cap bytes
     void *dst;
     uint64_t dst_cap;
-    const float *row_scale; // kModeBf16
-    uint32_t rows, cols;    // kModeBf16 / kModeGemv
-    const uint16_t *x_bf16; // kModeGemv
-    float *y_accum;         // kModeGemv
+    // fused modes: the matrices, in table order
+    uint32_t n_mats;
+    MatrixArgs mats[DC_MAX_MATRICES];
 };
 
 // LDS accessed through 32-bit byte addresses, so that address arithmetic stays in one VALU operation.
@@ -364,9 +374,17 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     if (active) ent = a.table[k];
     const uint32_t raw = ent.raw_bytes_flags & ~DC_CHUNK_RAW;
     const bool is_raw = (ent.raw_bytes_flags & DC_CHUNK_RAW) != 0;
-    const uint64_t dst_pos = k * (uint64_t)a.chunk_bytes; // first decoded byte of the chunk
+    // fused modes: the matrix the chunk belongs to, and the chunk's number inside it
+    uint32_t mi = 0;
+    if (MODE != kModeI8)
+        for (uint32_t i = 1; i < a.n_mats; i++)
+            if (k >= a.mats[i].first_chunk) mi = i;
+    const MatrixArgs &mat = a.mats[mi];
+    const uint64_t dst_cap = MODE == kModeI8 ? a.dst_cap : (uint64_t)mat.rows * mat.cols;
+    // first decoded byte of the chunk (in the buffer, or in its matrix)
+    const uint64_t dst_pos = (MODE == kModeI8 ? k : k - mat.first_chunk) * (uint64_t)a.chunk_bytes;
     active = active && raw >= 1 && raw <= a.chunk_bytes && (ent.off & 15) == 0 && ent.off <= a.blob_bytes &&
-             ent.comp_bytes <= a.blob_bytes - ent.off && ent.comp_bytes >= 16 && dst_pos + raw <= a.dst_cap &&
+             ent.comp_bytes <= a.blob_bytes - ent.off && ent.comp_bytes >= 16 && dst_pos + raw <= dst_cap &&
              (is_raw ? ent.comp_bytes >= ((raw + 15u) & ~15u) : ent.comp_bytes >= kHeader);
     const uint8_t *payload8 = a.blob + (active ? ent.off : 0);
     const uint32_t *payload = reinterpret_cast<const uint32_t *>(payload8);
@@ -560,14 +578,14 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     }
 
     // ---- fused consumers walk the matrix: group position -> (row, column)
-    const uint32_t cols = a.cols;
+    const uint32_t cols = mat.cols;
     const uint32_t rounds = full_rounds + (rem ? 1 : 0);
     uint64_t pos = dst_pos + ct * 16;
     uint32_t row = (uint32_t)(pos / cols);
     uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
 
     if (MODE == kModeBf16) {
-        uint16_t *out = static_cast<uint16_t *>(a.dst);
+        uint16_t *out = static_cast<uint16_t *>(mat.dst);
         for (uint32_t r = 0; r < rounds; r++) {
             const uint32_t start = r * round_bytes + ct * 16;
             // the matrix size is a multiple of 16, so a group is whole or absent
@@ -580,7 +598,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
             if (whole) {
-                const float s = a.row_scale[row];
+                const float s = mat.row_scale[row];
                 const float bias = -128.0f * s;
                 uint32_t o[8];
 #pragma unroll
@@ -618,13 +636,13 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
             if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) {
-                lanes_add_by_key<CPW == 2>(a.y_accum, cur_row < a.rows ? cur_row : 0xFFFFFFFFu, acc);
+                lanes_add_by_key<CPW == 2>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
                 acc = 0.0f;
                 cur_row = 0xFFFFFFFFu;
             }
             if (whole) {
                 cur_row = row;
-                const uint4 *xp = reinterpret_cast<const uint4 *>(a.x_bf16 + col);
+                const uint4 *xp = reinterpret_cast<const uint4 *>(mat.x_bf16 + col);
                 const uint4 xa = xp[0], xb = xp[1];
                 const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
 #pragma unroll
@@ -639,23 +657,36 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             col += round_bytes;
             while (col >= cols) { col -= cols; row++; }
         }
-        lanes_add_by_key<CPW == 2>(a.y_accum, cur_row < a.rows ? cur_row : 0xFFFFFFFFu, acc);
+        lanes_add_by_key<CPW == 2>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
     }
 }
 
-__global__ __launch_bounds__(256) void dc_fill_f32_kernel(float *p, uint32_t n, float v)
+// Blocks of 256 rows of the matrices of a fused GEMV call, matrix after matrix.
+struct RowBlocks {
+    uint32_t n_mats;
+    uint32_t first_block[DC_MAX_MATRICES + 1];
+    MatrixArgs mats[DC_MAX_MATRICES];
+};
+
+__global__ __launch_bounds__(256) void dc_gemv_zero_kernel(RowBlocks rb)
 {
-    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
+    uint32_t mi = 0;
+    for (uint32_t i = 1; i < rb.n_mats; i++)
+        if (blockIdx.x >= rb.first_block[i]) mi = i;
+    const uint32_t i = (blockIdx.x - rb.first_block[mi]) * 256 + threadIdx.x;
+    if (i < rb.mats[mi].rows) rb.mats[mi].y_accum[i] = 0.0f;
 }
 
 // y_i = scale_i * (acc_i - 128 * sum_j x_j); every block re-reduces x (at most 32 KiB, cache resident).
-__global__ __launch_bounds__(256) void dc_gemv_finish_kernel(float *y_accum, uint16_t *y_bf16, const float *row_scale,
-                                                             const uint16_t *x_bf16, uint32_t rows, uint32_t cols)
+__global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
 {
+    uint32_t mi = 0;
+    for (uint32_t i = 1; i < rb.n_mats; i++)
+        if (blockIdx.x >= rb.first_block[i]) mi = i;
+    const MatrixArgs &m = rb.mats[mi];
     __shared__ float part[256];
     float s = 0.0f;
-    for (uint32_t j = threadIdx.x; j < cols; j += 256) s += bf16_bits_to_f32(x_bf16[j]);
+    for (uint32_t j = threadIdx.x; j < m.cols; j += 256) s += bf16_bits_to_f32(m.x_bf16[j]);
     part[threadIdx.x] = s;
     __syncthreads();
     for (int d = 128; d > 0; d >>= 1) {
@@ -663,11 +694,11 @@ __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(float *y_accum, uin
         __syncthreads();
     }
     const float xsum = part[0];
-    const uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i < rows) {
-        const float y = row_scale[i] * (y_accum[i] - 128.0f * xsum);
-        y_accum[i] = y;
-        if (y_bf16) y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
+    const uint32_t i = (blockIdx.x - rb.first_block[mi]) * 256 + threadIdx.x;
+    if (i < m.rows) {
+        const float y = m.row_scale[i] * (m.y_accum[i] - 128.0f * xsum);
+        m.y_accum[i] = y;
+        if (m.y_bf16) m.y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
 }
 
@@ -809,30 +840,96 @@ extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes
     return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
-                                          uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
-                                          uint32_t rows, uint32_t cols, uint16_t *dst_bf16_dev, uint64_t dst_cap_elems,
-                                          void *hip_stream)
+namespace {
+
+// Host checks shared by the fused calls, and the kernel arguments built from the matrix list.
+int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev, uint64_t n_chunks,
+               const dc_params *params, const dc_matrix *mats, uint32_t n_mats, bool gemv, DecodeArgs &a)
 {
-    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_bf16_dev || !row_scale_dev || n_chunks == 0 ||
-        blob_bytes < 16 || rows == 0 || cols == 0 || cols % 16)
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !mats || n_mats == 0 || n_mats > DC_MAX_MATRICES ||
+        n_chunks == 0 || blob_bytes < 16)
         return DC_E_ARG;
-    if (!aligned16(blob_dev) || !aligned16(dst_bf16_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
-    const uint64_t total = (uint64_t)rows * cols;
-    if ((total + params->chunk_bytes - 1) / params->chunk_bytes != n_chunks) return DC_E_ARG;
-    if (dst_cap_elems < total) return DC_E_CAP;
-    DecodeArgs a = {};
+    if (!aligned16(blob_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
+    a = DecodeArgs{};
     a.blob = blob_dev;
     a.blob_bytes = blob_bytes;
     a.table = table_dev;
     a.n_chunks = n_chunks;
     a.chunk_bytes = params->chunk_bytes;
-    a.dst = dst_bf16_dev;
-    a.dst_cap = total; // chunks may not decode past the matrix
-    a.row_scale = row_scale_dev;
-    a.rows = rows;
-    a.cols = cols;
+    a.n_mats = n_mats;
+    uint64_t next_chunk = 0;
+    for (uint32_t i = 0; i < n_mats; i++) {
+        const dc_matrix &m = mats[i];
+        if (m.rows == 0 || m.cols == 0 || m.cols % 16 || !m.row_scale_dev) return DC_E_ARG;
+        if (gemv) {
+            if (!m.x_bf16_dev || !m.y_accum_dev || m.cols > 16384 || !aligned16(m.x_bf16_dev)) return DC_E_ARG;
+        } else {
+            if (!m.dst_bf16_dev || !aligned16(m.dst_bf16_dev)) return DC_E_ARG;
+        }
+        const uint64_t total = (uint64_t)m.rows * m.cols;
+        if (!gemv && m.dst_cap_elems < total) return DC_E_CAP;
+        // the matrices follow each other in the table, each starting at a chunk of its own
+        if (m.first_chunk != next_chunk) return DC_E_ARG;
+        next_chunk += (total + params->chunk_bytes - 1) / params->chunk_bytes;
+        MatrixArgs &k = a.mats[i];
+        k.first_chunk = m.first_chunk;
+        k.rows = m.rows;
+        k.cols = m.cols;
+        k.row_scale = m.row_scale_dev;
+        k.dst = m.dst_bf16_dev;
+        k.x_bf16 = m.x_bf16_dev;
+        k.y_accum = m.y_accum_dev;
+        k.y_bf16 = m.y_bf16_dev;
+    }
+    if (next_chunk != n_chunks) return DC_E_ARG;
+    return DC_OK;
+}
+
+} // namespace
+
+extern "C" int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                                uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                                uint32_t n_mats, void *hip_stream)
+{
+    DecodeArgs a;
+    const int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, false, a);
+    if (rc != DC_OK) return rc;
     return launch_decode<kModeBf16>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                        uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                        uint32_t n_mats, void *hip_stream)
+{
+    DecodeArgs a;
+    int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, true, a);
+    if (rc != DC_OK) return rc;
+    RowBlocks rb = {};
+    rb.n_mats = n_mats;
+    for (uint32_t i = 0; i < n_mats; i++) {
+        rb.mats[i] = a.mats[i];
+        rb.first_block[i + 1] = rb.first_block[i] + (a.mats[i].rows + 255) / 256;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(dc_gemv_zero_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
+    rc = launch_decode<kModeGemv>(a, params->n_streams, stream);
+    if (rc != DC_OK) return rc;
+    hipLaunchKernelGGL(dc_gemv_finish_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
+    return launch_status();
+}
+
+extern "C" int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                          uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
+                                          uint32_t rows, uint32_t cols, uint16_t *dst_bf16_dev, uint64_t dst_cap_elems,
+                                          void *hip_stream)
+{
+    dc_matrix m = {};
+    m.rows = rows;
+    m.cols = cols;
+    m.row_scale_dev = row_scale_dev;
+    m.dst_bf16_dev = dst_bf16_dev;
+    m.dst_cap_elems = dst_cap_elems;
+    return dc_decompress_dequant_bf16_layer(blob_dev, blob_bytes, table_dev, n_chunks, params, &m, 1, hip_stream);
 }
 
 extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
@@ -840,30 +937,14 @@ extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, 
                                   uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev, uint16_t *y_bf16_dev,
                                   void *hip_stream)
 {
-    if (!decode_params_ok(params) || !blob_dev || !table_dev || !row_scale_dev || !x_bf16_dev || !y_accum_dev ||
-        n_chunks == 0 || blob_bytes < 16 || rows == 0 || cols == 0 || cols % 16 || cols > 16384)
-        return DC_E_ARG;
-    if (!aligned16(blob_dev) || !aligned16(x_bf16_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
-    const uint64_t total = (uint64_t)rows * cols;
-    if ((total + params->chunk_bytes - 1) / params->chunk_bytes != n_chunks) return DC_E_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(dc_fill_f32_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, y_accum_dev, rows, 0.0f);
-    DecodeArgs a = {};
-    a.blob = blob_dev;
-    a.blob_bytes = blob_bytes;
-    a.table = table_dev;
-    a.n_chunks = n_chunks;
-    a.chunk_bytes = params->chunk_bytes;
-    a.dst_cap = total;
-    a.rows = rows;
-    a.cols = cols;
-    a.x_bf16 = x_bf16_dev;
-    a.y_accum = y_accum_dev;
-    const int rc = launch_decode<kModeGemv>(a, params->n_streams, stream);
-    if (rc != DC_OK) return rc;
-    hipLaunchKernelGGL(dc_gemv_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, y_accum_dev, y_bf16_dev,
-                       row_scale_dev, x_bf16_dev, rows, cols);
-    return launch_status();
+    dc_matrix m = {};
+    m.rows = rows;
+    m.cols = cols;
+    m.row_scale_dev = row_scale_dev;
+    m.x_bf16_dev = x_bf16_dev;
+    m.y_accum_dev = y_accum_dev;
+    m.y_bf16_dev = y_bf16_dev;
+    return dc_decompress_gemv_layer(blob_dev, blob_bytes, table_dev, n_chunks, params, &m, 1, hip_stream);
 }
 
 extern "C" const char *dc_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }

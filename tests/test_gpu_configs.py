@@ -154,3 +154,49 @@ def test_config5_llama13b_fused_paths(index):
     got = out16.cpu().numpy().view(np.uint16).reshape(m.rows, m.cols)
     rows = np.unique(np.concatenate([np.arange(0, m.rows, 97), [m.rows - 1]]))
     assert np.array_equal(got[rows], oq.dequant_bf16(q[rows], scale[rows]))
+
+
+def test_config5_whole_layer_in_one_fused_call():
+    """All seven matrices of the 13B-shaped layer through one dc_decompress_gemv_layer and one
+    dc_decompress_dequant_bf16_layer call: same results as matrix by matrix."""
+    print("case config 5 whole layer", flush=True)
+    layer = oracle_layer("llama13b", 0, False)
+    C, S = 65536, 256
+    p = dc.Params(C, S)
+    blob, table = compress_concat([q for _, q, _ in layer], p)
+    blob_d, table_d = dev(blob), dev(table)
+    mats_g, mats_b, keep = [], [], []
+    k0 = 0
+    for m, q, scale in layer:
+        seed = synth.matrix_seed(0, m.index)
+        x = synth.gen_activation_bf16(m.cols, seed)
+        x_d = torch.from_numpy(x.view(np.int16)).cuda()
+        s_d = torch.from_numpy(scale).cuda()
+        y32 = torch.full((m.rows,), 3.0, dtype=torch.float32, device="cuda")
+        y16 = torch.zeros(m.rows, dtype=torch.int16, device="cuda")
+        o16 = torch.zeros(q.size, dtype=torch.int16, device="cuda")
+        mats_g.append(dc.Matrix(k0, m.rows, m.cols, s_d, x_bf16_dev=x_d, y_accum_dev=y32, y_bf16_dev=y16))
+        mats_b.append(dc.Matrix(k0, m.rows, m.cols, s_d, dst_bf16_dev=o16, dst_cap_elems=q.size))
+        keep.append((m, q, scale, x, y32, y16, o16))
+        k0 += q.size // C
+    assert k0 == len(table) == 4840
+    dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g, stream())
+    dc.decompress_dequant_bf16_layer(blob_d, blob.size, table_d, len(table), p, mats_b, stream())
+    torch.cuda.synchronize()
+    for m, q, scale, x, y32, y16, o16 in keep:
+        y_ref = oq.gemv_ref(q, scale, x)
+        rms = float(np.sqrt(np.mean(y_ref ** 2)))
+        y = y32.cpu().numpy().astype(np.float64)
+        assert (np.abs(y - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all(), m.name
+        assert np.abs(y - y_ref).max() / np.abs(y_ref).max() < 1e-4
+        assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
+        got = o16.cpu().numpy().view(np.uint16).reshape(m.rows, m.cols)
+        rows = np.unique(np.concatenate([np.arange(0, m.rows, 211), [m.rows - 1]]))
+        assert np.array_equal(got[rows], oq.dequant_bf16(q[rows], scale[rows])), m.name
+    # descriptor errors are caught on the host
+    bad = [dc.Matrix(mm.first_chunk + 1, mm.rows, mm.cols, mm.row_scale_dev, x_bf16_dev=mm.x_bf16_dev,
+                     y_accum_dev=mm.y_accum_dev) for mm in mats_g]
+    with pytest.raises(dc.DCError):
+        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, bad, stream())
+    with pytest.raises(dc.DCError):
+        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g[:-1], stream())
