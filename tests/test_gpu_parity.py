@@ -10,7 +10,7 @@ import oracle.codec as oc
 import oracle.quant as oq
 import paper_2502_15443_amd as dc
 import synth
-from tests.helpers import oracle_matrix, weightlike_bytes
+from tests.helpers import lopsided_bytes, oracle_matrix, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -58,6 +58,17 @@ def test_decode_degenerate_chunks(S):
         c = oc.compress(data, C, S, policy)
         out = gpu_decode(c.blob, c.table, dc.Params(C, S), data.size)
         assert np.array_equal(out, data)
+
+
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
+def test_decode_lopsided_streams(S):
+    """Sub-streams whose positions drift far apart (one all long codes, most all short codes)."""
+    print(f"case lopsided S={S}", flush=True)
+    C = 65536
+    n = 3 * C + 4096 + 50
+    data = lopsided_bytes(n, S, 7 + S)
+    c = oc.compress(data, C, S)
+    assert np.array_equal(gpu_decode(c.blob, c.table, dc.Params(C, S), n), data)
 
 
 @pytest.mark.parametrize("S", [32, 64])

@@ -186,6 +186,35 @@ def test_round_trip_and_independent_decoder_ragged(raw, S):
     assert pyref.parse_and_decode(payload.tobytes(), raw, S) == data.tobytes()
 
 
+@pytest.mark.parametrize("raw,S", [(65536, 32), (65536, 64), (40000, 128), (16384, 256), (5000, 4)])
+def test_lopsided_streams_round_trip_and_lookahead(raw, S):
+    """Sub-streams that use the code very unevenly (some all long codes, most all short): round trip
+    through the oracle and the independent decoder, and the placement rule keeps every stream between
+    320 and 448 placed bits ahead of its position (or has placed all of its blocks) after every step."""
+    from tests.helpers import lopsided_bytes
+    data = lopsided_bytes(raw, S, raw + S)
+    payload = oc.encode_chunk(data, S)
+    assert (oc.decode_chunk(payload, raw, S) == data).all()
+    assert pyref.parse_and_decode(payload.tobytes(), raw, S) == data.tobytes()
+    ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
+    assert ln.max() >= 9 and ln[0] <= 2
+    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    groups = (raw + 15) // 16
+    rounds = (groups + S - 1) // S
+    for j in range(min(S, 3)):  # the extreme streams
+        f, used = 0, 0
+        for h in range(2 * rounds):
+            for _ in range(3 if h == 0 else 1):
+                if f < nb[j] and 128 * f - used < 320:
+                    f += 1
+            assert f == nb[j] or 320 <= 128 * f - used < 448, (j, h)
+            g = j + (h // 2) * S
+            if g < groups:
+                lo = 16 * g + 8 * (h % 2)
+                used += int(ln[data[lo:min(lo + 8, raw)]].sum())
+        assert f == nb[j] and (used + 127) // 128 == nb[j]
+
+
 def test_independent_decoder_full_chunk_with_long_codes():
     """A 64 KiB chunk with a wide alphabet: codes up to the 11-bit limit occur."""
     r = np.random.default_rng(9)
