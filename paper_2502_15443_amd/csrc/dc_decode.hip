@@ -717,17 +717,17 @@ __device__ __forceinline__ float lanes_sum(float v)
 }
 
 // Batch-1 product on weights that are already decoded: y_i = scale_i * sum_j q_ij x_j, q int8 row-major.
-// A wave owns kGemvRows consecutive rows and walks the columns 16 bytes a lane (1 KiB a wave and row),
-// so that x is converted once for all its rows; the weights enter as byte ^ 0x80 (one conversion
-// instruction a byte) and the -128 * sum(x) term is taken out at the end.
+// A workgroup owns kGemvRows consecutive rows; its 256 threads walk the columns 16 bytes a thread
+// (4 KiB a workgroup and row), so that x is converted once for all the rows; the weights enter as
+// byte ^ 0x80 (one conversion instruction a byte) and the -128 * sum(x) term is taken out at the end.
 constexpr int kGemvRows = 4;
 __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restrict__ q, const float *__restrict__ row_scale,
                                                          uint32_t rows, uint32_t cols, const uint16_t *__restrict__ x_bf16,
                                                          float *__restrict__ y_f32, uint16_t *__restrict__ y_bf16)
 {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kGemvRows;
-    if (row0 >= rows) return;
+    __shared__ float part[4][kGemvRows + 1];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t row0 = blockIdx.x * kGemvRows;
     const uint8_t *qr[kGemvRows];
 #pragma unroll
     for (int r = 0; r < kGemvRows; r++) {
@@ -736,7 +736,7 @@ __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restri
     }
     float acc[kGemvRows] = {0.0f, 0.0f, 0.0f, 0.0f};
     float xsum = 0.0f;
-    for (uint32_t c = lane * 16; c < cols; c += 1024) {
+    for (uint32_t c = threadIdx.x * 16; c < cols; c += 4096) {
         u32x4 w[kGemvRows];
 #pragma unroll
         for (int r = 0; r < kGemvRows; r++) w[r] = load16_stream(qr[r] + c);
@@ -764,13 +764,20 @@ __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restri
     }
     xsum = lanes_sum(xsum);
 #pragma unroll
-    for (int r = 0; r < kGemvRows; r++) {
-        const float total = lanes_sum(acc[r]);
-        if (lane == 63 && row0 + r < rows) {
-            const float y = row_scale[row0 + r] * (total - 128.0f * xsum);
-            y_f32[row0 + r] = y;
-            if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
-        }
+    for (int r = 0; r < kGemvRows; r++) acc[r] = lanes_sum(acc[r]);
+    if (lane == 63) {
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++) part[wave][r] = acc[r];
+        part[wave][kGemvRows] = xsum;
+    }
+    __syncthreads();
+    if (threadIdx.x < kGemvRows && row0 + threadIdx.x < rows) {
+        const uint32_t r = threadIdx.x;
+        const float total = part[0][r] + part[1][r] + part[2][r] + part[3][r];
+        const float xs4 = part[0][kGemvRows] + part[1][kGemvRows] + part[2][kGemvRows] + part[3][kGemvRows];
+        const float y = row_scale[row0 + r] * (total - 128.0f * xs4);
+        y_f32[row0 + r] = y;
+        if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
 }
 
@@ -954,7 +961,7 @@ extern "C" int dc_gemv_i8(const int8_t *q_dev, const float *row_scale_dev, uint3
 {
     if (!q_dev || !row_scale_dev || !x_bf16_dev || !y_f32_dev || rows == 0 || cols == 0 || cols % 16) return DC_E_ARG;
     if (!aligned16(q_dev) || !aligned16(x_bf16_dev)) return DC_E_ARG;
-    const uint32_t blocks = (rows + 4 * kGemvRows - 1) / (4 * kGemvRows);
+    const uint32_t blocks = (rows + kGemvRows - 1) / kGemvRows;
     hipLaunchKernelGGL(dc_gemv_i8_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        reinterpret_cast<const uint8_t *>(q_dev), row_scale_dev, rows, cols, x_bf16_dev, y_f32_dev,
                        y_bf16_dev);
