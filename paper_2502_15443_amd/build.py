@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libdc_mi355x.so")
 SOURCES = [os.path.join(PKG, "csrc", "dc_host.cpp"), os.path.join(PKG, "csrc", "dc_decode.hip")]
-HEADERS = [os.path.join(ROOT, "include", "dc.h")]
+HEADERS = [os.path.join(ROOT, "include", "dc.h"), os.path.join(PKG, "csrc", "dc_device.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

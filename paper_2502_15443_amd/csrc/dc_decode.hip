@@ -17,6 +17,9 @@
 #include <hip/hip_runtime.h>
 
 #include "dc.h"
+#include "dc_device.h"
+
+using namespace dcdev;
 
 namespace {
 
@@ -26,19 +29,6 @@ constexpr int kRingWords = 16;                 // per lane
 constexpr uint32_t kBlockBytes = DC_BLOCK_BYTES; // bitstream fetch granule
 
 enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// 128-bit streaming accesses for data that is touched once.
-__device__ __forceinline__ void store16_stream(void *p, uint32_t a, uint32_t b, uint32_t c, uint32_t d)
-{
-    u32x4 v = {a, b, c, d};
-    __builtin_nontemporal_store(v, static_cast<u32x4 *>(p));
-}
-__device__ __forceinline__ u32x4 load16_stream(const void *p)
-{
-    return __builtin_nontemporal_load(static_cast<const u32x4 *>(p));
-}
 
 template <int S> struct Geometry {
     static constexpr int kLanesPerChunk = S < 64 ? S : 64;       // lanes of one wave that serve a chunk
@@ -73,51 +63,6 @@ struct DecodeArgs {
     uint32_t n_mats;
     MatrixArgs mats[DC_MAX_MATRICES];
 };
-
-// LDS accessed through 32-bit byte addresses, so that address arithmetic stays in one VALU operation.
-typedef __attribute__((address_space(3))) uint32_t lds_u32;
-typedef __attribute__((address_space(3))) uint16_t lds_u16;
-__device__ __forceinline__ uint32_t lds_address(const void *p)
-{
-    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
-}
-__device__ __forceinline__ uint32_t lds_load32(uint32_t addr) { return *(const lds_u32 *)(uintptr_t)addr; }
-__device__ __forceinline__ uint32_t lds_load16(uint32_t addr) { return *(const lds_u16 *)(uintptr_t)addr; }
-
-// Value of another lane through the data-parallel primitives; lanes without a source (and rows that
-// the row mask leaves out) read 0.  0x110 + n: n lanes to the right inside a row of 16; 0x142 / 0x143:
-// lane 15 of a row to the next row / lane 31 to rows 2 and 3; 0x138: one lane to the right over
-// the whole wave.
-template <int CTRL, int ROW_MASK> __device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v)
-{
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, false);
-}
-
-// Inclusive prefix sum over the 64 lanes (HALVES: over each half of 32 lanes on its own).
-template <bool HALVES> __device__ __forceinline__ uint32_t lanes_prefix_sum(uint32_t v)
-{
-    v += dpp_or_zero<0x111, 0xF>(v);
-    v += dpp_or_zero<0x112, 0xF>(v);
-    v += dpp_or_zero<0x114, 0xF>(v);
-    v += dpp_or_zero<0x118, 0xF>(v);
-    v += dpp_or_zero<0x142, 0xA>(v);
-    if (!HALVES) v += dpp_or_zero<0x143, 0xC>(v);
-    return v;
-}
-
-// For every lane the last non-zero value among the lanes below it (0 if none).
-template <bool HALVES> __device__ __forceinline__ uint32_t lanes_last_nonzero_below(uint32_t v)
-{
-    uint32_t t;
-    v = dpp_or_zero<0x138, 0xF>(v);
-    t = dpp_or_zero<0x111, 0xF>(v); v = v ? v : t;
-    t = dpp_or_zero<0x112, 0xF>(v); v = v ? v : t;
-    t = dpp_or_zero<0x114, 0xF>(v); v = v ? v : t;
-    t = dpp_or_zero<0x118, 0xF>(v); v = v ? v : t;
-    t = dpp_or_zero<0x142, 0xA>(v); v = v ? v : t;
-    if (!HALVES) { t = dpp_or_zero<0x143, 0xC>(v); v = v ? v : t; }
-    return v;
-}
 
 // Sums `val` over runs of consecutive lanes with equal `key` (keys do not decrease with the lane;
 // key 0xFFFFFFFF = lane takes no part) and adds each run's sum to y[key] with one atomic, issued by
@@ -702,20 +647,6 @@ __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
     }
 }
 
-// Sum over the 64 lanes, result in lane 63.
-__device__ __forceinline__ float lanes_sum(float v)
-{
-#define DC_SUM_STEP(CTRL, MASK) v += __uint_as_float(dpp_or_zero<CTRL, MASK>(__float_as_uint(v)));
-    DC_SUM_STEP(0x111, 0xF)
-    DC_SUM_STEP(0x112, 0xF)
-    DC_SUM_STEP(0x114, 0xF)
-    DC_SUM_STEP(0x118, 0xF)
-    DC_SUM_STEP(0x142, 0xA)
-    DC_SUM_STEP(0x143, 0xC)
-#undef DC_SUM_STEP
-    return v;
-}
-
 // Batch-1 product on weights that are already decoded: y_i = scale_i * sum_j q_ij x_j, q int8 row-major.
 // A workgroup owns kGemvRows consecutive rows; its 256 threads walk the columns 16 bytes a thread
 // (4 KiB a workgroup and row), so that x is converted once for all the rows; the weights enter as
@@ -790,12 +721,7 @@ __global__ __launch_bounds__(256) void dc_copy_kernel(const u32x4 *__restrict__ 
 
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
-// Records the launch status of the calling thread; DC_E_HIP callers can ask dc_last_hip_error().
-int launch_status()
-{
-    g_last_hip_error = hipGetLastError();
-    return g_last_hip_error == hipSuccess ? DC_OK : DC_E_HIP;
-}
+int launch_status() { return dc_launch_status(); }
 
 bool decode_params_ok(const dc_params *p)
 {
@@ -827,6 +753,13 @@ template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 } // namespace
+
+int dc_launch_status()
+{
+    g_last_hip_error = hipGetLastError();
+    return g_last_hip_error == hipSuccess ? DC_OK : DC_E_HIP;
+}
+
 
 extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                                     uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
