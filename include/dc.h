@@ -200,6 +200,28 @@ int dc_compress_chunks(const int8_t *src_host, uint64_t raw_bytes, const dc_para
                        uint64_t table_cap, uint64_t *n_chunks);
 
 /*
+ * The same compression on the GPU (Section 3.1; Section 4.2 reports compression speed as well).
+ * Device to device, asynchronous on hip_stream, three launches.  The blob and table are byte for
+ * byte those of dc_compress_chunks for the same input and params.  Policies: DC_POLICY_ALL_HUFF,
+ * DC_POLICY_AUTO, DC_POLICY_BLOCK_LAST (the others need a host-side selection: DC_E_ARG).
+ *   src_dev         raw_bytes int8 values, 16-byte aligned
+ *   blob_dev        out, 16-byte aligned, blob_cap bytes (dc_compress_bound gives a safe size)
+ *   table_dev       out, table_cap >= number of chunks entries
+ *   workspace_dev   scratch of at least dc_compress_chunks_dev_workspace() bytes, 16-byte aligned,
+ *                   owned by the caller; may be reused once the call's work on the stream is done
+ *   result_dev      out, two u64 in device memory: [0] = blob bytes (needed, when [1] != 0),
+ *                   [1] = 0, or DC_E_CAP as a 64-bit value when blob_cap was too small (then the
+ *                   blob is incomplete, the table is still written)
+ * Errors on the host: DC_E_ARG (null or misaligned pointers, unsupported policy or sizes), DC_E_CAP
+ * (workspace or table too small), DC_E_HIP.
+ */
+int dc_compress_chunks_dev_workspace(uint64_t raw_bytes, const dc_params *params, uint64_t *workspace_bytes);
+int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
+                           uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap,
+                           void *workspace_dev, uint64_t workspace_bytes, uint64_t *result_dev,
+                           void *hip_stream);
+
+/*
  * Host-side check of a table and blob against the stored format: offsets, sizes, alignment, code
  * lengths forming a complete code, sub-stream extents, and that every sub-stream holds its symbols.
  * Returns DC_OK or DC_E_FORMAT (first offending chunk index in *bad_chunk when not NULL).

@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     quantize_tensor,
     compress_bound,
     compress_chunks,
+    compress_chunks_dev,
+    compress_chunks_dev_workspace,
     validate,
     decompress_chunks,
     decompress_dequant_bf16,

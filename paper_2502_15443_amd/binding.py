@@ -105,6 +105,10 @@ def _load():
     L.dc_compress_bound.argtypes = [u64, pp, pu64, pu64]
     L.dc_compress_chunks.restype = i32
     L.dc_compress_chunks.argtypes = [vp, u64, pp, vp, u64, pu64, vp, u64, pu64]
+    L.dc_compress_chunks_dev_workspace.restype = i32
+    L.dc_compress_chunks_dev_workspace.argtypes = [u64, pp, pu64]
+    L.dc_compress_chunks_dev.restype = i32
+    L.dc_compress_chunks_dev.argtypes = [vp, u64, pp, vp, u64, vp, u64, vp, u64, vp, vp]
     L.dc_validate.restype = i32
     L.dc_validate.argtypes = [vp, u64, vp, u64, pp, pu64]
     L.dc_decompress_chunks.restype = i32
@@ -211,6 +215,21 @@ def compress_chunks(src: np.ndarray, params: Params) -> Tuple[np.ndarray, np.nda
     _check(_L.dc_compress_chunks(_host(s), s.size, C.byref(cp), _host(blob), cap, C.byref(used), _host(table),
                                  nc, C.byref(n_out)), "dc_compress_chunks")
     return blob[:used.value].copy(), table[:n_out.value]
+
+
+def compress_chunks_dev_workspace(raw_bytes: int, params: Params) -> int:
+    n = C.c_uint64(0)
+    cp = params._c()
+    _check(_L.dc_compress_chunks_dev_workspace(raw_bytes, C.byref(cp), C.byref(n)), "dc_compress_chunks_dev_workspace")
+    return int(n.value)
+
+
+def compress_chunks_dev(src_dev, raw_bytes: int, params: Params, blob_dev, blob_cap: int, table_dev, table_cap: int,
+                        workspace_dev, workspace_bytes: int, result_dev, stream: int = 0) -> None:
+    cp = params._c()
+    _check(_L.dc_compress_chunks_dev(_dev(src_dev), raw_bytes, C.byref(cp), _dev(blob_dev), blob_cap, _dev(table_dev),
+                                     table_cap, _dev(workspace_dev), workspace_bytes, _dev(result_dev), stream),
+           "dc_compress_chunks_dev")
 
 
 def validate(blob: np.ndarray, table: np.ndarray, params: Params) -> None:

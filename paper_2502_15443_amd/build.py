@@ -8,7 +8,8 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libdc_mi355x.so")
-SOURCES = [os.path.join(PKG, "csrc", "dc_host.cpp"), os.path.join(PKG, "csrc", "dc_decode.hip")]
+SOURCES = [os.path.join(PKG, "csrc", "dc_host.cpp"), os.path.join(PKG, "csrc", "dc_decode.hip"),
+           os.path.join(PKG, "csrc", "dc_encode.hip")]
 HEADERS = [os.path.join(ROOT, "include", "dc.h"), os.path.join(PKG, "csrc", "dc_device.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

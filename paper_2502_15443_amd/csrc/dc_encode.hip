@@ -1,0 +1,451 @@
+// Device side of libdc_mi355x: chunk compression on the GPU (the compression stage of Section 3.1 of
+// the paper; Section 4.2 also reports compression speed).  Three launches:
+//   dc_codes_kernel   one workgroup per chunk: byte histogram, length-limited code lengths by
+//                     package-merge (same ordering rules as the host compressor, so the lengths are
+//                     identical), bits of every sub-stream, size of the Huffman payload;
+//   dc_layout_kernel  one workgroup: which chunks stay raw, payload offsets (prefix sum), chunk table;
+//   dc_emit_kernel    one workgroup per chunk: header, canonical codes, and the sub-streams written as
+//                     16-byte blocks in the order of the format's placement rule.
+// The stored format is in include/dc.h.
+#include <hip/hip_runtime.h>
+
+#include "dc.h"
+#include "dc_device.h"
+
+using namespace dcdev;
+
+namespace {
+
+constexpr int kL = DC_MAX_CODE_LEN;
+constexpr uint32_t kBlockBits = 8 * DC_BLOCK_BYTES;
+
+struct EncArgs {
+    const uint8_t *src;
+    uint64_t raw_bytes;
+    uint64_t n_chunks;
+    uint32_t chunk_bytes;
+    uint32_t S;
+    uint32_t policy;
+    uint32_t block_chunks;
+    // workspace
+    uint8_t *lens;  // [n_chunks][256] code lengths
+    uint32_t *bits; // [n_chunks][S] bits of every sub-stream
+    uint32_t *comp; // [n_chunks] bytes of the Huffman payload
+    // results
+    uint8_t *blob;
+    uint64_t blob_cap;
+    dc_chunk *table;
+    uint64_t *result; // [0] blob bytes needed, [1] 0 or DC_E_CAP as an unsigned value
+};
+
+__device__ __forceinline__ uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
+__device__ __forceinline__ uint32_t header_bytes(uint32_t S) { return (128 + 2 * S + 4 * (S / set_width(S)) + 15) / 16 * 16; }
+__device__ __forceinline__ uint32_t chunk_len(const EncArgs &a, uint64_t k)
+{
+    const uint64_t lo = k * a.chunk_bytes;
+    const uint64_t left = a.raw_bytes - lo;
+    return left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
+}
+
+// Number of entries of the ascending array v[0..n) that are < x (strict) or <= x.
+template <bool STRICT> __device__ __forceinline__ uint32_t count_below(const uint32_t *v, uint32_t n, uint32_t x, uint32_t shift)
+{
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const uint32_t y = v[mid] >> shift;
+        if (STRICT ? y < x : y <= x) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t key[256];    // count << 8 | byte value, ascending after the sort; absent values last
+    __shared__ uint32_t level[2][512]; // weights of the items of the previous / current level
+    __shared__ uint32_t pack[256];     // packages made of the previous level
+    __shared__ uint16_t leaves_before[kL][514];
+    __shared__ uint32_t bought_leaves[kL];
+    __shared__ uint8_t len_of[256];
+    __shared__ uint32_t sbits[256];
+    __shared__ uint32_t blocks_total;
+
+    const uint32_t t = threadIdx.x;
+    const uint64_t k = blockIdx.x;
+    const uint32_t raw = chunk_len(a, k);
+    const uint8_t *src = a.src + k * a.chunk_bytes;
+
+    hist[t] = 0;
+    sbits[t] = 0;
+    len_of[t] = 0;
+    if (t == 0) blocks_total = 0;
+    __syncthreads();
+    const uint32_t n16 = raw / 16;
+    for (uint32_t i = t; i < n16; i += 256) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(src + 16 * (size_t)i);
+#pragma unroll
+        for (int w = 0; w < 4; w++)
+#pragma unroll
+            for (int b = 0; b < 4; b++) atomicAdd(&hist[(v[w] >> (8 * b)) & 0xFFu], 1u);
+    }
+    for (uint32_t i = n16 * 16 + t; i < raw; i += 256) atomicAdd(&hist[src[i]], 1u);
+    __syncthreads();
+
+    const uint32_t cnt = hist[t];
+    key[t] = cnt ? (cnt << 8 | t) : 0xFFFFFFFFu;
+    const uint32_t n = (uint32_t)__syncthreads_count(cnt != 0);
+    // bitonic sort, ascending: leaves in order of (count, byte value)
+    for (uint32_t size = 2; size <= 256; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            const uint32_t partner = t ^ stride;
+            if (partner > t) {
+                const bool up = (t & size) == 0;
+                const uint32_t x = key[t], y = key[partner];
+                if ((x > y) == up) {
+                    key[t] = y;
+                    key[partner] = x;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    if (n == 1) {
+        if (t == 0) len_of[key[0] & 0xFFu] = 1;
+    } else if (n >= 2) {
+        // Package-merge: level 0 is the sorted leaves; level j is the leaves merged with the pairs of
+        // level j-1, a leaf before a package of equal weight.  leaves_before[j][m] = leaves among the
+        // first m items of level j.
+        const uint32_t lw = t < n ? key[t] >> 8 : 0;
+        if (t < n) level[0][t] = lw;
+        for (uint32_t m = t; m < 514; m += 256) leaves_before[0][m] = (uint16_t)(m < n ? m : n);
+        uint32_t size_prev = n, cur = 0;
+        for (int j = 1; j < kL; j++) {
+            __syncthreads();
+            const uint32_t npk = size_prev / 2;
+            if (t < npk) pack[t] = level[cur][2 * t] + level[cur][2 * t + 1];
+            __syncthreads();
+            if (t < n) {
+                const uint32_t pos = t + count_below<true>(pack, npk, lw, 0);
+                level[cur ^ 1][pos] = lw;
+                leaves_before[j][pos] = (uint16_t)t;
+            }
+            if (t < npk) {
+                const uint32_t pw = pack[t];
+                const uint32_t c = count_below<false>(key, n, pw, 8);
+                level[cur ^ 1][t + c] = pw;
+                leaves_before[j][t + c] = (uint16_t)c;
+            }
+            if (t == 0) leaves_before[j][n + npk] = (uint16_t)n;
+            size_prev = n + npk;
+            cur ^= 1;
+        }
+        __syncthreads();
+        if (t == 0) {
+            uint32_t bought = 2 * n - 2;
+            for (int j = kL - 1; j >= 0; j--) {
+                uint32_t nl = 0;
+                if (bought > 0) {
+                    nl = leaves_before[j][bought];
+                    bought = 2 * (bought - nl);
+                }
+                bought_leaves[j] = nl;
+            }
+        }
+        __syncthreads();
+        if (t < n) {
+            uint32_t depth = 0;
+#pragma unroll
+            for (int j = 0; j < kL; j++) depth += t < bought_leaves[j];
+            len_of[key[t] & 0xFFu] = (uint8_t)depth;
+        }
+    }
+    __syncthreads();
+    a.lens[k * 256 + t] = len_of[t];
+
+    // bits of every sub-stream: thread t sees the 16-byte groups t, t + 256, ... which all belong to
+    // sub-stream t mod S (S divides 256)
+    const uint32_t groups = (raw + 15) / 16;
+    uint32_t mine = 0;
+    for (uint32_t g = t; g < groups; g += 256) {
+        const uint32_t lo = 16 * g, hi = lo + 16 < raw ? lo + 16 : raw;
+        if (hi - lo == 16) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(src + lo);
+#pragma unroll
+            for (int w = 0; w < 4; w++)
+#pragma unroll
+                for (int b = 0; b < 4; b++) mine += len_of[(v[w] >> (8 * b)) & 0xFFu];
+        } else {
+            for (uint32_t p = lo; p < hi; p++) mine += len_of[src[p]];
+        }
+    }
+    if (mine) atomicAdd(&sbits[t % a.S], mine);
+    __syncthreads();
+    if (t < a.S) {
+        a.bits[k * a.S + t] = sbits[t];
+        atomicAdd(&blocks_total, (sbits[t] + kBlockBits - 1) / kBlockBits);
+    }
+    __syncthreads();
+    if (t == 0) a.comp[k] = header_bytes(a.S) + DC_BLOCK_BYTES * blocks_total;
+}
+
+// Size of chunk k in the blob and whether it stays raw.
+__device__ __forceinline__ uint32_t stored_size(const EncArgs &a, uint64_t k, bool &is_raw)
+{
+    const uint32_t raw = chunk_len(a, k);
+    const uint32_t huff = a.comp[k];
+    is_raw = false;
+    if (a.policy == DC_POLICY_AUTO) is_raw = (int64_t)raw - (int64_t)huff <= 0;
+    else if (a.policy == DC_POLICY_BLOCK_LAST) is_raw = (k % a.block_chunks) != a.block_chunks - 1;
+    return is_raw ? (raw + 15u) & ~15u : huff;
+}
+
+__global__ __launch_bounds__(256) void dc_layout_kernel(EncArgs a)
+{
+    __shared__ uint64_t part[256];
+    const uint32_t t = threadIdx.x;
+    const uint64_t per = (a.n_chunks + 255) / 256;
+    const uint64_t k0 = t * per, k1 = k0 + per < a.n_chunks ? k0 + per : a.n_chunks;
+    uint64_t sum = 0;
+    bool is_raw;
+    for (uint64_t k = k0; k < k1; k++) sum += stored_size(a, k, is_raw);
+    part[t] = sum;
+    __syncthreads();
+    if (t == 0) {
+        uint64_t run = 0;
+        for (int i = 0; i < 256; i++) {
+            const uint64_t s = part[i];
+            part[i] = run;
+            run += s;
+        }
+        a.result[0] = run + DC_BLOB_TAIL_BYTES;
+        a.result[1] = run + DC_BLOB_TAIL_BYTES > a.blob_cap ? (uint64_t)(int64_t)DC_E_CAP : 0;
+        if (run + DC_BLOB_TAIL_BYTES <= a.blob_cap)
+            for (int i = 0; i < DC_BLOB_TAIL_BYTES; i++) a.blob[run + i] = 0;
+    }
+    __syncthreads();
+    uint64_t off = part[t];
+    for (uint64_t k = k0; k < k1; k++) {
+        const uint32_t size = stored_size(a, k, is_raw);
+        dc_chunk e;
+        e.off = off;
+        e.comp_bytes = size;
+        e.raw_bytes_flags = chunk_len(a, k) | (is_raw ? DC_CHUNK_RAW : 0u);
+        a.table[k] = e;
+        off += size;
+    }
+}
+
+// One sub-stream while it is written: the coder runs ahead of the position a decoder would have at
+// the current step, only as far as the next block it must hand over.
+struct Coder {
+    uint64_t acc;       // bits not yet in the ring
+    uint32_t nbits;     // valid bits in acc
+    uint32_t words;     // words put into the ring so far
+    uint32_t next_half; // next half group to code
+};
+
+template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel(EncArgs a)
+{
+    constexpr int WAVES = THREADS / 64;
+    __shared__ __attribute__((aligned(4096))) uint32_t ring[WAVES * 16 * 64]; // 16 words a lane, as in the decoder
+    __shared__ uint32_t book[256];                                            // bit-reversed code | length << 16
+    __shared__ uint8_t len_of[256];
+    __shared__ uint32_t set_blocks[WAVES];
+
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint64_t k = blockIdx.x;
+    const uint32_t S = a.S;
+    const dc_chunk ent = a.table[k];
+    const uint32_t raw = ent.raw_bytes_flags & ~DC_CHUNK_RAW;
+    if (ent.off + ent.comp_bytes + DC_BLOB_TAIL_BYTES > a.blob_cap) return; // the caller's blob is too small
+    const uint8_t *src = a.src + k * a.chunk_bytes;
+    uint8_t *out = a.blob + ent.off;
+
+    if (ent.raw_bytes_flags & DC_CHUNK_RAW) {
+        const uint32_t n16 = raw / 16;
+        for (uint32_t i = t; i < n16; i += THREADS)
+            *reinterpret_cast<u32x4 *>(out + 16 * (size_t)i) = *reinterpret_cast<const u32x4 *>(src + 16 * (size_t)i);
+        if (t < 16 && n16 * 16 < raw) out[n16 * 16 + t] = n16 * 16 + t < raw ? src[n16 * 16 + t] : 0;
+        return;
+    }
+
+    // ---- header: code lengths, blocks of every sub-stream, region offsets
+    for (uint32_t v = t; v < 256; v += THREADS) len_of[v] = a.lens[k * 256 + v];
+    __syncthreads();
+    for (uint32_t i = t; i < 128; i += THREADS) out[i] = (uint8_t)(len_of[2 * i] | (len_of[2 * i + 1] << 4));
+    const bool has_stream = t < S;
+    const uint32_t stream_bits = has_stream ? a.bits[k * S + t] : 0;
+    const uint32_t nb = (stream_bits + kBlockBits - 1) / kBlockBits;
+    if (has_stream) reinterpret_cast<uint16_t *>(out + 128)[t] = (uint16_t)nb;
+    const uint32_t wave_blocks = lanes_prefix_sum<false>(nb);
+    if (lane == 63) set_blocks[wave] = wave_blocks;
+    __syncthreads();
+    const uint32_t hdr = header_bytes(S);
+    const uint32_t n_sets = S / set_width(S);
+    uint32_t region = hdr; // first byte of this wave's region
+    for (uint32_t w = 0; w < wave; w++) region += DC_BLOCK_BYTES * set_blocks[w];
+    if (lane == 0 && wave < n_sets) reinterpret_cast<uint32_t *>(out + 128 + 2 * S)[wave] = region;
+    for (uint32_t i = 128 + 2 * S + 4 * n_sets + t; i < hdr; i += THREADS) out[i] = 0;
+
+    // ---- canonical codes: numbered in order of (length, byte value)
+    for (uint32_t v = t; v < 256; v += THREADS) {
+        const uint32_t l = len_of[v];
+        uint32_t entry = 0;
+        if (l) {
+            uint32_t rank = 0;          // values before v with the same length
+            uint32_t shorter_units = 0; // sum over values u of 2^(l - len_u) for len_u < l, and of 1 for len_u == l, u < v
+            for (uint32_t u = 0; u < 256; u++) {
+                const uint32_t lu = len_of[u];
+                if (lu != 0 && lu < l) shorter_units += 1u << (l - lu);
+                else if (lu == l && u < v) rank++;
+            }
+            const uint32_t code = shorter_units + rank; // all shorter codes come first, each worth 2^(l - len) codes of length l
+            entry = (__brev(code) >> (32 - l)) | (l << 16);
+        }
+        book[v] = entry;
+    }
+    __syncthreads();
+    if (!has_stream) return;
+
+    // ---- the sub-stream of this lane
+    const uint32_t groups = (raw + 15) / 16;
+    const uint32_t rounds = (groups + S - 1) / S;
+    const uint32_t my_groups = t < groups ? (groups - t + S - 1) / S : 0;
+    const uint32_t ring_lane = lds_address(ring + wave * (16 * 64) + lane);
+    Coder c = {0, 0, 0, 0};
+    uint32_t taken = 0, used = 0;
+    uint32_t next_block = region / DC_BLOCK_BYTES;
+    const uint64_t set_lanes = S < 64 ? (1ull << S) - 1 : ~0ull;
+
+    // bytes [lo, lo + n) of the chunk, n <= 8, as a 64-bit word (missing bytes zero)
+    auto half_group = [&](uint32_t h, uint32_t &n) -> uint64_t {
+        const uint32_t g = t + (h >> 1) * S;
+        const uint32_t lo = 16 * g + 8 * (h & 1);
+        n = lo < raw ? (raw - lo < 8 ? raw - lo : 8) : 0;
+        if (n == 8) return *reinterpret_cast<const uint64_t *>(src + lo);
+        uint64_t v = 0;
+        for (uint32_t i = 0; i < n; i++) v |= (uint64_t)src[lo + i] << (8 * i);
+        return v;
+    };
+
+    for (uint32_t h = 0; h < 2 * rounds; h++) {
+        for (int pass = h == 0 ? 3 : 1; pass > 0; pass--) {
+            const bool want = taken < nb && kBlockBits * taken < used + DC_LOOKAHEAD_BITS;
+            if (want) {
+                // code on until block `taken` is complete (or the stream ends, then pad with zeros)
+                while (c.words < 4 * (taken + 1)) {
+                    if (c.next_half < 2 * my_groups) {
+                        uint32_t n;
+                        const uint64_t bytes = half_group(c.next_half, n);
+                        c.next_half++;
+                        for (uint32_t i = 0; i < n; i++) {
+                            const uint32_t e = book[(bytes >> (8 * i)) & 0xFFu];
+                            c.acc |= (uint64_t)(e & 0xFFFFu) << c.nbits;
+                            c.nbits += e >> 16;
+                            if (c.nbits >= 32) {
+                                *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
+                                c.words++;
+                                c.acc >>= 32;
+                                c.nbits -= 32;
+                            }
+                        }
+                    } else {
+                        *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
+                        c.words++;
+                        c.acc = 0;
+                        c.nbits = 0;
+                    }
+                }
+            }
+            const uint64_t m = __ballot(want) & set_lanes;
+            if (want) {
+                const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                u32x4 blk;
+#pragma unroll
+                for (int i = 0; i < 4; i++) blk[i] = lds_load32(ring_lane + (((4 * taken + i) & 15u) << 8));
+                *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
+                taken++;
+            }
+            next_block += (uint32_t)__popcll(m);
+        }
+        // the decoder's position after half group h
+        if ((h >> 1) < my_groups) {
+            uint32_t n;
+            const uint64_t bytes = half_group(h, n);
+            for (uint32_t i = 0; i < n; i++) used += book[(bytes >> (8 * i)) & 0xFFu] >> 16;
+        }
+    }
+}
+
+template <int THREADS> void launch_emit(const EncArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(dc_emit_kernel<THREADS>, dim3((uint32_t)a.n_chunks), dim3(THREADS), 0, stream, a);
+}
+
+bool enc_params_ok(const dc_params *p)
+{
+    if (!p) return false;
+    if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
+    if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128 && p->n_streams != 256) return false;
+    if (p->policy == DC_POLICY_BLOCK_LAST) return p->block_chunks != 0;
+    return p->policy == DC_POLICY_ALL_HUFF || p->policy == DC_POLICY_AUTO;
+}
+
+uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
+
+} // namespace
+
+extern "C" int dc_compress_chunks_dev_workspace(uint64_t raw_bytes, const dc_params *params, uint64_t *workspace_bytes)
+{
+    if (!enc_params_ok(params) || raw_bytes == 0 || !workspace_bytes) return DC_E_ARG;
+    const uint64_t nc = (raw_bytes + params->chunk_bytes - 1) / params->chunk_bytes;
+    *workspace_bytes = align256(nc * 256) + align256(nc * params->n_streams * 4) + align256(nc * 4);
+    return DC_OK;
+}
+
+extern "C" int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
+                                      uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap,
+                                      void *workspace_dev, uint64_t workspace_bytes, uint64_t *result_dev,
+                                      void *hip_stream)
+{
+    uint64_t need = 0;
+    if (dc_compress_chunks_dev_workspace(raw_bytes, params, &need) != DC_OK) return DC_E_ARG;
+    if (!src_dev || !blob_dev || !table_dev || !workspace_dev || !result_dev) return DC_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(src_dev) & 15u) || (reinterpret_cast<uintptr_t>(blob_dev) & 15u) ||
+        (reinterpret_cast<uintptr_t>(table_dev) & 7u) || (reinterpret_cast<uintptr_t>(workspace_dev) & 15u) ||
+        (reinterpret_cast<uintptr_t>(result_dev) & 7u))
+        return DC_E_ARG;
+    const uint64_t nc = (raw_bytes + params->chunk_bytes - 1) / params->chunk_bytes;
+    if (nc > 0x7FFFFFFFull) return DC_E_ARG;
+    if (workspace_bytes < need || table_cap < nc) return DC_E_CAP;
+    EncArgs a = {};
+    a.src = reinterpret_cast<const uint8_t *>(src_dev);
+    a.raw_bytes = raw_bytes;
+    a.n_chunks = nc;
+    a.chunk_bytes = params->chunk_bytes;
+    a.S = params->n_streams;
+    a.policy = params->policy;
+    a.block_chunks = params->block_chunks;
+    uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
+    a.lens = ws;
+    a.bits = reinterpret_cast<uint32_t *>(ws + align256(nc * 256));
+    a.comp = reinterpret_cast<uint32_t *>(ws + align256(nc * 256) + align256(nc * a.S * 4));
+    a.blob = blob_dev;
+    a.blob_cap = blob_cap;
+    a.table = table_dev;
+    a.result = result_dev;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipLaunchKernelGGL(dc_codes_kernel, dim3((uint32_t)nc), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(dc_layout_kernel, dim3(1), dim3(256), 0, stream, a);
+    switch (a.S) {
+    case 32:
+    case 64: launch_emit<64>(a, stream); break;
+    case 128: launch_emit<128>(a, stream); break;
+    default: launch_emit<256>(a, stream); break;
+    }
+    return dc_launch_status();
+}

@@ -1,0 +1,99 @@
+"""GPU compression (dc_compress_chunks_dev) against the CPU oracle: the blob and the chunk table must be
+byte for byte the oracle's, so code lengths, canonical codes, sub-stream bits and block placement all
+have one right answer."""
+import numpy as np
+import pytest
+
+import oracle.codec as oc
+import paper_2502_15443_amd as dc
+import synth
+from tests.helpers import lopsided_bytes, oracle_matrix, weightlike_bytes
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+E_CAP_U64 = (1 << 64) - 2
+
+
+def dev_compress(data: np.ndarray, params, blob_cap=None):
+    n = data.size
+    st = torch.cuda.current_stream().cuda_stream
+    src = torch.from_numpy(np.ascontiguousarray(data).view(np.uint8).reshape(-1)).cuda()
+    cap, nc = dc.compress_bound(n, params)
+    if blob_cap is not None:
+        cap = blob_cap
+    blob_d = torch.full((cap + 64,), 0xEE, dtype=torch.uint8, device="cuda")
+    table_d = torch.zeros(nc * 16, dtype=torch.uint8, device="cuda")
+    ws_bytes = dc.compress_chunks_dev_workspace(n, params)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    res = torch.zeros(2, dtype=torch.int64, device="cuda")
+    dc.compress_chunks_dev(src, n, params, blob_d, cap, table_d, nc, ws, ws_bytes, res, st)
+    torch.cuda.synchronize()
+    r = res.cpu().numpy().view(np.uint64)
+    guard = blob_d[cap:].cpu().numpy()
+    assert (guard == 0xEE).all()  # nothing written beyond the stated capacity
+    return blob_d[:cap].cpu().numpy(), table_d.cpu().numpy().view(dc.CHUNK_DTYPE), int(r[0]), int(r[1])
+
+
+def check_equal_to_oracle(data, C, S, policy=oc.ALL_HUFF, block=0):
+    p = dc.Params(C, S, policy, 0.0, block)
+    blob, table, used, status = dev_compress(data, p)
+    c = oc.compress(data, C, S, policy, block=block, threads=8)
+    assert status == 0 and used == c.blob.size
+    assert np.array_equal(table, c.table)
+    assert np.array_equal(blob[:used], c.blob)
+    return blob[:used], table
+
+
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
+@pytest.mark.parametrize("n,C", [(3 * 65536, 65536), (5 * 16384 + 777, 16384), (7 * 4096 + 4095, 4096), (100, 65536),
+                                 (1, 4096), (2 * 262144 + 12345, 262144)])
+def test_device_blob_equals_oracle_blob(S, n, C):
+    print(f"case dev compress S={S} n={n} C={C}", flush=True)
+    check_equal_to_oracle(weightlike_bytes(n, 300 + n % 911 + S), C, S)
+
+
+@pytest.mark.parametrize("S", [32, 256])
+def test_device_compress_degenerate_and_limit_cases(S):
+    print(f"case dev compress degenerate S={S}", flush=True)
+    C = 4096
+    r = np.random.default_rng(1)
+    skew = np.clip(np.rint(r.standard_cauchy(C) * 2), -127, 127).astype(np.int8).view(np.uint8)  # length limit active
+    fib = np.repeat(np.arange(20, dtype=np.uint8), [1, 1, 2, 3, 5, 8, 13, 21, 34, 55, 89, 144, 233, 377, 610, 987, 400,
+                                                    300, 200, 673])[:C]
+    data = np.concatenate([np.zeros(C, np.uint8), np.full(C, 0x81, np.uint8), r.integers(0, 256, C, dtype=np.uint8),
+                           np.tile(np.array([3, 250], np.uint8), C // 2), np.arange(C, dtype=np.uint32).astype(np.uint8),
+                           skew, np.resize(fib, C), lopsided_bytes(C, S, 5), np.array([7], np.uint8)])
+    for policy in (oc.ALL_HUFF, oc.AUTO):
+        check_equal_to_oracle(data, C, S, policy)
+    check_equal_to_oracle(data, C, S, oc.BLOCK_LAST, block=3)
+
+
+def test_device_compress_config2_matrix_and_round_trip():
+    """gate_proj of the Llama-7B-shaped layer in the benchmark's parameters: same blob as the library's host
+    compressor (itself checked against the oracle), accepted by the validator, decoded back on the GPU."""
+    q, _ = oracle_matrix(11008, 4096, synth.matrix_seed(0, 4), True)
+    C, S = 65536, 256
+    p = dc.Params(C, S)
+    blob, table, used, status = dev_compress(q, p)
+    hb, ht = dc.compress_chunks(q, p)
+    assert status == 0 and used == hb.size and np.array_equal(table, ht) and np.array_equal(blob[:used], hb)
+    dc.validate(blob[:used], table, p)
+    c0 = oc.compress(q.reshape(-1)[:4 * C], C, S)  # first chunks straight from the oracle
+    assert np.array_equal(blob[:int(table["off"][4])], c0.blob[:-64])
+    st = torch.cuda.current_stream().cuda_stream
+    dst = torch.empty(q.size, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(torch.from_numpy(blob[:used]).cuda(), used, torch.from_numpy(table.view(np.uint8)).cuda(),
+                         len(table), p, dst, q.size, st)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), q.view(np.uint8).ravel())
+
+
+def test_device_compress_reports_small_blob():
+    data = weightlike_bytes(6 * 4096, 3)
+    p = dc.Params(4096, 64)
+    _, table, used, status = dev_compress(data, p, blob_cap=8192)
+    c = oc.compress(data, 4096, 64)
+    assert status == E_CAP_U64 and used == c.blob.size and np.array_equal(table, c.table)
+    with pytest.raises(dc.DCError):
+        dev_compress(data, dc.Params(4096, 64, dc.POLICY_RAW_FRACTION, 0.5))
