@@ -220,6 +220,54 @@ def layer_streaming(torch, dc, synth, params, n_layers=8, reps=10):
     return out
 
 
+def full_model(torch, dc, synth, n_layers, sweep):
+    """The 32-layer Llama-7B-shaped weight set (per-layer seeds, quantised without the rescale), every chunk
+    decoded into one buffer by one launch, for each (chunk_bytes, n_streams) of `sweep`.  One JSON line.
+    Not the headline: the weights take minutes to generate."""
+    stream = torch.cuda.current_stream().cuda_stream
+    t0 = time.perf_counter()
+    qs = []
+    for layer in range(n_layers):
+        for m in synth.layer_specs("llama7b"):
+            seed = synth.matrix_seed(layer, m.index)
+            q, _, _ = dc.quantize_rows(synth.gen_weight(m.rows, m.cols, seed), None, 0.5, 1)
+            qs.append(q.reshape(-1))
+    gen_s = time.perf_counter() - t0
+    raw_bytes = int(sum(q.size for q in qs))
+    flat = torch.from_numpy(np.concatenate(qs).view(np.uint8))
+    dst = torch.empty(raw_bytes, dtype=torch.uint8, device="cuda")
+    rows = []
+    for C, S in sweep:
+        p = dc.Params(C, S)
+        blobs, tables, off = [], [], 0
+        t0 = time.perf_counter()
+        for q in qs:
+            b, t = dc.compress_chunks(q, p)
+            t = t.copy()
+            t["off"] += off
+            off += b.size
+            blobs.append(b)
+            tables.append(t)
+        comp_s = time.perf_counter() - t0
+        blob, table = np.concatenate(blobs), np.concatenate(tables)
+        del blobs, tables
+        blob_d = torch.from_numpy(blob).cuda()
+        table_d = torch.from_numpy(table.view(np.uint8)).cuda()
+        ms, _ = time_launches(
+            torch, lambda i: dc.decompress_chunks(blob_d, blob.size, table_d, len(table), p, dst, raw_bytes, stream), 10, 2)
+        exact = bool(torch.equal(dst.cpu(), flat))
+        rows.append({"chunk_bytes": C, "n_streams": S, "n_chunks": len(table),
+                     "compression_ratio": round(raw_bytes / (blob.size + table.nbytes), 5), "ms": round(ms, 4),
+                     "decoded_GBps": round(raw_bytes / ms / 1e6, 1),
+                     "hbm_frac": round((raw_bytes + blob.size + table.nbytes) / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                     "exact": exact, "host_compress_s": round(comp_s, 1)})
+        del blob_d, table_d, blob, table
+    print(json.dumps({"workload": f"{n_layers} Llama-7B-shaped layers, distinct per-layer seeds, per-row INT8 without "
+                                  "rescale, one launch into one buffer", "raw_bytes": raw_bytes,
+                      "generate_and_quantise_s": round(gen_s, 1), "sweep": rows}))
+    return 0 if all(r["exact"] for r in rows) else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,6 +278,9 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=65536)
     ap.add_argument("--tile", type=int, default=1,
                     help="decode this many copies of the layer in one launch (input-size scaling; not the headline)")
+    ap.add_argument("--full-model", type=int, default=0, metavar="LAYERS",
+                    help="instead of the headline: decode LAYERS distinct layers (32 = the whole model) in one launch, "
+                         "sweeping the chunk size")
     ap.add_argument("--no-extras", action="store_true", help="skip fused/raw-fraction/copy side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -247,6 +298,9 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.full_model:
+        return full_model(torch, dc, synth, args.full_model,
+                          [(65536, 64), (65536, 256), (16384, 64), (262144, 64), (262144, 256)])
     stream = torch.cuda.current_stream().cuda_stream
     S, C = args.streams, args.chunk
     params = dc.Params(C, S)
