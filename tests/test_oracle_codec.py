@@ -420,3 +420,33 @@ def test_mask_policy():
     c = oc.compress(data, C, S, oc.RAW_MASK, mask=mask)
     assert (((c.table["raw_bytes_flags"] & oc.RAW_FLAG) != 0) == (mask != 0)).all()
     assert (oc.decompress(c.blob, c.table, C, S, data.size) == data).all()
+
+
+# ------------------------------------------------------------------ values fixed by the paper's text
+
+def golden_rows(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [line.split() for line in open(path) if line.strip() and not line.startswith("#")]
+
+
+def test_block_last_policy_is_the_papers_positional_rule():
+    """tests/golden/speed_adaptive_blocks.txt: which chunks the paper's rule compresses."""
+    for row in golden_rows("speed_adaptive_blocks.txt"):
+        block, n_chunks, compressed = int(row[0]), int(row[1]), sorted(int(x) for x in row[2:])
+        data = gaussian_bytes(n_chunks * 256, 8.0, block + n_chunks)
+        c = oc.compress(data, 256, 4, oc.BLOCK_LAST, block=block)
+        raw = (c.table["raw_bytes_flags"] & oc.RAW_FLAG) != 0
+        assert sorted(np.flatnonzero(~raw).tolist()) == compressed
+        assert (oc.decompress(c.blob, c.table, 256, 4, data.size) == data).all()
+
+
+def test_layer_sizes_of_the_papers_speed_table():
+    """tests/golden/layer_sizes_mib.txt: one byte a weight, 12 hidden^2 weights a decoder layer; the same
+    count for the Llama-shaped layers of the workloads is 4 h^2 + 3 h f."""
+    for hidden, printed in golden_rows("layer_sizes_mib.txt"):
+        weights = 12 * int(hidden) ** 2 / 2 ** 20
+        assert 0 <= float(printed) - weights < 0.002 * weights
+    import synth
+    for kind, hidden, ffn in (("llama7b", 4096, 11008), ("llama13b", 5120, 13824)):
+        assert sum(m.rows * m.cols for m in synth.layer_specs(kind)) == 4 * hidden ** 2 + 3 * hidden * ffn
