@@ -97,3 +97,20 @@ def test_device_compress_reports_small_blob():
     assert status == E_CAP_U64 and used == c.blob.size and np.array_equal(table, c.table)
     with pytest.raises(dc.DCError):
         dev_compress(data, dc.Params(4096, 64, dc.POLICY_RAW_FRACTION, 0.5))
+
+
+@pytest.mark.parametrize("S", [32, 256])
+def test_largest_chunk_size_both_ways(S):
+    """1 MiB chunks (the largest the format allows): device compression equals the oracle's, device decode
+    restores the input."""
+    print(f"case 1 MiB chunks S={S}", flush=True)
+    C = 1 << 20
+    n = 2 * C + 70000
+    data = weightlike_bytes(n, 41 + S)
+    blob, table = check_equal_to_oracle(data, C, S)
+    st = torch.cuda.current_stream().cuda_stream
+    dst = torch.full((n,), 0xAB, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(torch.from_numpy(blob).cuda(), blob.size, torch.from_numpy(table.view(np.uint8)).cuda(),
+                         len(table), dc.Params(C, S), dst, n, st)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), data)
