@@ -246,6 +246,8 @@ struct Coder {
     uint32_t nbits;     // valid bits in acc
     uint32_t words;     // words put into the ring so far
     uint32_t next_half; // next half group to code
+    uint64_t bytes;     // its bytes, loaded ahead of use
+    uint32_t n;         // how many of them exist
 };
 
 template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel(EncArgs a)
@@ -255,6 +257,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     __shared__ uint32_t book[256];                                            // bit-reversed code | length << 16
     __shared__ uint8_t len_of[256];
     __shared__ uint32_t set_blocks[WAVES];
+    __shared__ uint32_t len_count[4][kL + 1]; // [64 byte values][code length]
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint64_t k = blockIdx.x;
@@ -291,19 +294,28 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     if (lane == 0 && wave < n_sets) reinterpret_cast<uint32_t *>(out + 128 + 2 * S)[wave] = region;
     for (uint32_t i = 128 + 2 * S + 4 * n_sets + t; i < hdr; i += THREADS) out[i] = 0;
 
-    // ---- canonical codes: numbered in order of (length, byte value)
+    // ---- canonical codes: numbered in order of (length, byte value).  A wave looks at 64 consecutive
+    // byte values at a time: rank = values of the same length before this one within the 64.
+    for (uint32_t v = t; v < 256; v += THREADS) {
+        const uint32_t l = len_of[v];
+        uint32_t rank = 0;
+        for (uint32_t l2 = 1; l2 <= (uint32_t)kL; l2++) {
+            const uint64_t m = __ballot(l == l2);
+            if (l == l2) rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (lane == 0) len_count[v >> 6][l2] = (uint32_t)__popcll(m);
+        }
+        book[v] = rank;
+    }
+    __syncthreads();
     for (uint32_t v = t; v < 256; v += THREADS) {
         const uint32_t l = len_of[v];
         uint32_t entry = 0;
         if (l) {
-            uint32_t rank = 0;          // values before v with the same length
-            uint32_t shorter_units = 0; // sum over values u of 2^(l - len_u) for len_u < l, and of 1 for len_u == l, u < v
-            for (uint32_t u = 0; u < 256; u++) {
-                const uint32_t lu = len_of[u];
-                if (lu != 0 && lu < l) shorter_units += 1u << (l - lu);
-                else if (lu == l && u < v) rank++;
-            }
-            const uint32_t code = shorter_units + rank; // all shorter codes come first, each worth 2^(l - len) codes of length l
+            // every shorter code of length m stands for 2^(l - m) codes of length l that come first
+            uint32_t code = book[v];
+            for (uint32_t m = 1; m < l; m++)
+                code += (len_count[0][m] + len_count[1][m] + len_count[2][m] + len_count[3][m]) << (l - m);
+            for (uint32_t b = 0; b < (v >> 6); b++) code += len_count[b][l];
             entry = (__brev(code) >> (32 - l)) | (l << 16);
         }
         book[v] = entry;
@@ -316,7 +328,6 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     const uint32_t rounds = (groups + S - 1) / S;
     const uint32_t my_groups = t < groups ? (groups - t + S - 1) / S : 0;
     const uint32_t ring_lane = lds_address(ring + wave * (16 * 64) + lane);
-    Coder c = {0, 0, 0, 0};
     uint32_t taken = 0, used = 0;
     uint32_t next_block = region / DC_BLOCK_BYTES;
     const uint64_t set_lanes = S < 64 ? (1ull << S) - 1 : ~0ull;
@@ -332,27 +343,51 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
         return v;
     };
 
+    Coder c = {0, 0, 0, 0, 0, 0};
+    if (my_groups) c.bytes = half_group(0, c.n);
+    // codes the next half group into the ring: at most 88 bits on top of fewer than 32, so at most
+    // three words
+    auto code_half = [&]() {
+        const uint64_t bytes = c.bytes;
+        const uint32_t n = c.n;
+        c.next_half++;
+        if (c.next_half < 2 * my_groups) c.bytes = half_group(c.next_half, c.n);
+        // the table reads do not depend on each other; the bit buffer takes two codes (at most 22
+        // bits on top of fewer than 32) between checks
+        uint32_t e[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) e[i] = (uint32_t)i < n ? book[(bytes >> (8 * i)) & 0xFFu] : 0;
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+            c.acc |= (uint64_t)(e[i] & 0xFFFFu) << c.nbits;
+            c.nbits += e[i] >> 16;
+            c.acc |= (uint64_t)(e[i + 1] & 0xFFFFu) << c.nbits;
+            c.nbits += e[i + 1] >> 16;
+            if (c.nbits >= 32) {
+                *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
+                c.words++;
+                c.acc >>= 32;
+                c.nbits -= 32;
+            }
+        }
+    };
+
     for (uint32_t h = 0; h < 2 * rounds; h++) {
+        // the half group a decoder consumes at this step (needed after the blocks of the step)
+        uint32_t step_n = 0;
+        uint64_t step_bytes = 0;
+        if ((h >> 1) < my_groups) step_bytes = half_group(h, step_n);
+        // All lanes code one half group ahead together while the ring has room for it (the words of
+        // block `taken` onwards are still in the ring, 16 words in all), so that the loop below, where
+        // lanes diverge, rarely has anything left to do.
+        if (c.next_half < 2 * my_groups && c.words + 3 <= 4 * taken + 16) code_half();
         for (int pass = h == 0 ? 3 : 1; pass > 0; pass--) {
             const bool want = taken < nb && kBlockBits * taken < used + DC_LOOKAHEAD_BITS;
             if (want) {
                 // code on until block `taken` is complete (or the stream ends, then pad with zeros)
                 while (c.words < 4 * (taken + 1)) {
                     if (c.next_half < 2 * my_groups) {
-                        uint32_t n;
-                        const uint64_t bytes = half_group(c.next_half, n);
-                        c.next_half++;
-                        for (uint32_t i = 0; i < n; i++) {
-                            const uint32_t e = book[(bytes >> (8 * i)) & 0xFFu];
-                            c.acc |= (uint64_t)(e & 0xFFFFu) << c.nbits;
-                            c.nbits += e >> 16;
-                            if (c.nbits >= 32) {
-                                *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
-                                c.words++;
-                                c.acc >>= 32;
-                                c.nbits -= 32;
-                            }
-                        }
+                        code_half();
                     } else {
                         *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
                         c.words++;
@@ -373,11 +408,8 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
             next_block += (uint32_t)__popcll(m);
         }
         // the decoder's position after half group h
-        if ((h >> 1) < my_groups) {
-            uint32_t n;
-            const uint64_t bytes = half_group(h, n);
-            for (uint32_t i = 0; i < n; i++) used += book[(bytes >> (8 * i)) & 0xFFu] >> 16;
-        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) used += (uint32_t)i < step_n ? book[(step_bytes >> (8 * i)) & 0xFFu] >> 16 : 0;
     }
 }
 
