@@ -47,50 +47,51 @@ __device__ __forceinline__ uint32_t chunk_len(const EncArgs &a, uint64_t k)
     return left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
 }
 
-// Number of entries of the ascending array v[0..n) that are < x (strict) or <= x.
-template <bool STRICT> __device__ __forceinline__ uint32_t count_below(const uint32_t *v, uint32_t n, uint32_t x, uint32_t shift)
-{
-    uint32_t lo = 0, hi = n;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        const uint32_t y = v[mid] >> shift;
-        if (STRICT ? y < x : y <= x) lo = mid + 1;
-        else hi = mid;
-    }
-    return lo;
-}
-
 __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
 {
+    // 16 KiB used twice: first the histogram in 32 columns, one per LDS bank, so that the lanes of one
+    // update never meet in a bank; then the tables of the package-merge.
+    __shared__ uint32_t arena[4112];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t key[256];    // count << 8 | byte value, ascending after the sort; absent values last
-    __shared__ uint32_t level[2][512]; // weights of the items of the previous / current level
-    __shared__ uint32_t pack[256];     // packages made of the previous level
-    __shared__ uint16_t leaves_before[kL][514];
     __shared__ uint32_t bought_leaves[kL];
     __shared__ uint8_t len_of[256];
     __shared__ uint32_t sbits[256];
     __shared__ uint32_t blocks_total;
+    uint32_t(*level)[512] = reinterpret_cast<uint32_t(*)[512]>(arena);              // weights of the items of the previous / current level
+    uint32_t *pack = arena + 1024;                                                    // [256] packages made of the previous level
+    uint16_t(*leaves_before)[514] = reinterpret_cast<uint16_t(*)[514]>(arena + 1280); // [kL][514]
 
     const uint32_t t = threadIdx.x;
     const uint64_t k = blockIdx.x;
     const uint32_t raw = chunk_len(a, k);
     const uint8_t *src = a.src + k * a.chunk_bytes;
 
-    hist[t] = 0;
+    // Column c = t mod 32 holds, for every pair of byte values (2p, 2p+1), two 16-bit counts in the word
+    // arena[32 p + c]; a column sees at most raw / 32 <= 32768 bytes, so the low count never carries.
+    for (uint32_t i = t; i < 4096; i += 256) arena[i] = 0;
     sbits[t] = 0;
     len_of[t] = 0;
     if (t == 0) blocks_total = 0;
     __syncthreads();
+    uint32_t *column = arena + (t & 31u);
+    auto count = [&](uint32_t b) { atomicAdd(column + ((b >> 1) << 5), 1u << ((b & 1u) << 4)); };
     const uint32_t n16 = raw / 16;
     for (uint32_t i = t; i < n16; i += 256) {
         const u32x4 v = *reinterpret_cast<const u32x4 *>(src + 16 * (size_t)i);
 #pragma unroll
         for (int w = 0; w < 4; w++)
 #pragma unroll
-            for (int b = 0; b < 4; b++) atomicAdd(&hist[(v[w] >> (8 * b)) & 0xFFu], 1u);
+            for (int b = 0; b < 4; b++) count((v[w] >> (8 * b)) & 0xFFu);
     }
-    for (uint32_t i = n16 * 16 + t; i < raw; i += 256) atomicAdd(&hist[src[i]], 1u);
+    for (uint32_t i = n16 * 16 + t; i < raw; i += 256) count(src[i]);
+    __syncthreads();
+    {
+        // byte value t: its row is 32 words; start at column t so that the threads of a wave spread over the banks
+        uint32_t sum = 0;
+        for (uint32_t i = 0; i < 32; i++) sum += (arena[((t >> 1) << 5) + ((t + i) & 31u)] >> ((t & 1u) << 4)) & 0xFFFFu;
+        hist[t] = sum;
+    }
     __syncthreads();
 
     const uint32_t cnt = hist[t];
@@ -128,16 +129,25 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
             const uint32_t npk = size_prev / 2;
             if (t < npk) pack[t] = level[cur][2 * t] + level[cur][2 * t + 1];
             __syncthreads();
+            // A leaf goes after the packages lighter than it, a package after the leaves not heavier
+            // than it.  Both counts come from one 9-step search over an ascending array of at most 256
+            // entries, the two searches side by side so that their LDS reads overlap.
+            const uint32_t pw = t < npk ? pack[t] : 0;
+            uint32_t packs_below = 0, leaves_upto = 0;
+#pragma unroll
+            for (uint32_t step = 256; step > 0; step >>= 1) {
+                const uint32_t ip = packs_below + step - 1, il = leaves_upto + step - 1;
+                const uint32_t yp = pack[ip < npk ? ip : 0], yl = key[il < n ? il : 0] >> 8;
+                if (ip < npk && yp < lw) packs_below += step;
+                if (il < n && yl <= pw) leaves_upto += step;
+            }
             if (t < n) {
-                const uint32_t pos = t + count_below<true>(pack, npk, lw, 0);
-                level[cur ^ 1][pos] = lw;
-                leaves_before[j][pos] = (uint16_t)t;
+                level[cur ^ 1][t + packs_below] = lw;
+                leaves_before[j][t + packs_below] = (uint16_t)t;
             }
             if (t < npk) {
-                const uint32_t pw = pack[t];
-                const uint32_t c = count_below<false>(key, n, pw, 8);
-                level[cur ^ 1][t + c] = pw;
-                leaves_before[j][t + c] = (uint16_t)c;
+                level[cur ^ 1][t + leaves_upto] = pw;
+                leaves_before[j][t + leaves_upto] = (uint16_t)leaves_upto;
             }
             if (t == 0) leaves_before[j][n + npk] = (uint16_t)n;
             size_prev = n + npk;
