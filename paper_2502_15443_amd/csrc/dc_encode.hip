@@ -362,24 +362,47 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
         const uint32_t n = c.n;
         c.next_half++;
         if (c.next_half < 2 * my_groups) c.bytes = half_group(c.next_half, c.n);
-        // the table reads do not depend on each other; the bit buffer takes two codes (at most 22
-        // bits on top of fewer than 32) between checks
-        uint32_t e[8];
-#pragma unroll
-        for (int i = 0; i < 8; i++) e[i] = (uint32_t)i < n ? book[(bytes >> (8 * i)) & 0xFFu] : 0;
-#pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-            c.acc |= (uint64_t)(e[i] & 0xFFFFu) << c.nbits;
-            c.nbits += e[i] >> 16;
-            c.acc |= (uint64_t)(e[i + 1] & 0xFFFFu) << c.nbits;
-            c.nbits += e[i + 1] >> 16;
+        auto flush = [&]() {
             if (c.nbits >= 32) {
                 *(lds_u32 *)(uintptr_t)(ring_lane + ((c.words & 15u) << 8)) = (uint32_t)c.acc;
                 c.words++;
                 c.acc >>= 32;
                 c.nbits -= 32;
             }
+        };
+        if (n == 8) {
+            // the table reads do not depend on each other; the bit buffer takes two codes (at most 22
+            // bits on top of fewer than 32) between checks
+            uint32_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) e[i] = book[(bytes >> (8 * i)) & 0xFFu];
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) {
+                const uint32_t l0 = e[i] >> 16;
+                const uint32_t two = (e[i] & 0xFFFFu) | (e[i + 1] & 0xFFFFu) << l0;
+                c.acc |= (uint64_t)two << c.nbits;
+                c.nbits += l0 + (e[i + 1] >> 16);
+                flush();
+            }
+        } else {
+            for (uint32_t i = 0; i < n; i++) { // the ragged end of the chunk
+                const uint32_t e = book[(bytes >> (8 * i)) & 0xFFu];
+                c.acc |= (uint64_t)(e & 0xFFFFu) << c.nbits;
+                c.nbits += e >> 16;
+                flush();
+            }
         }
+    };
+    // bits that the codes of a half group take
+    auto bits_of = [&](uint64_t bytes, uint32_t n) -> uint32_t {
+        uint32_t sum = 0;
+        if (n == 8) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) sum += book[(bytes >> (8 * i)) & 0xFFu] >> 16;
+        } else {
+            for (uint32_t i = 0; i < n; i++) sum += book[(bytes >> (8 * i)) & 0xFFu] >> 16;
+        }
+        return sum;
     };
 
     for (uint32_t h = 0; h < 2 * rounds; h++) {
@@ -418,8 +441,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
             next_block += (uint32_t)__popcll(m);
         }
         // the decoder's position after half group h
-#pragma unroll
-        for (int i = 0; i < 8; i++) used += (uint32_t)i < step_n ? book[(step_bytes >> (8 * i)) & 0xFFu] >> 16 : 0;
+        used += bits_of(step_bytes, step_n);
     }
 }
 
