@@ -530,11 +530,24 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     uint32_t col = (uint32_t)(pos - (uint64_t)row * cols);
 
     if (MODE == kModeBf16) {
+        // A lane's 16 values become 32 bytes, so two 16-byte stores of its own values would each
+        // write half of every 128-byte line.  Lanes l and l + 16 (the same chunk) trade eight bytes
+        // first: afterwards the first store of the wave covers the groups of lanes 0-15 and 32-47
+        // completely and the second store those of lanes 16-31 and 48-63, whole lines both.
+        //   lane l     (bit 4 clear): w0 w1 = its bytes 0-7,          w2 w3 = bytes 0-7 of lane l + 16
+        //   lane l + 16             : w0 w1 = bytes 8-15 of lane l,   w2 w3 = its bytes 8-15
         uint16_t *out = static_cast<uint16_t *>(mat.dst);
+        const uint32_t upper = (ct >> 4) & 1u;
+        const uint32_t ct_a = ct & ~16u, ct_b = ct_a + 16; // the groups the first and the second store belong to
+        const uint64_t pos_a = dst_pos + ct_a * 16, pos_b = dst_pos + ct_b * 16;
+        uint32_t row_a = (uint32_t)(pos_a / cols), row_b = (uint32_t)(pos_b / cols);
+        uint32_t col_a = (uint32_t)(pos_a - (uint64_t)row_a * cols), col_b = (uint32_t)(pos_b - (uint64_t)row_b * cols);
         for (uint32_t r = 0; r < rounds; r++) {
             const uint32_t start = r * round_bytes + ct * 16;
             // the matrix size is a multiple of 16, so a group is whole or absent
             const bool whole = raw >= start + 16;
+            // asked for before the decode, so that they arrive meanwhile
+            const float s_a = mat.row_scale[row_a < mat.rows ? row_a : 0], s_b = mat.row_scale[row_b < mat.rows ? row_b : 0];
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
                 decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
@@ -542,23 +555,33 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
-            if (whole) {
-                const float s = mat.row_scale[row];
+            // rows of 16 lanes: the odd rows of the first operand change places with the even rows of the second
+            const auto x02 = __builtin_amdgcn_permlane16_swap(w[0], w[2], false, false);
+            const auto x13 = __builtin_amdgcn_permlane16_swap(w[1], w[3], false, false);
+            const uint32_t wa[2] = {x02[0], x13[0]}, wb[2] = {x02[1], x13[1]};
+            const uint32_t base = r * round_bytes;
+            if (raw >= base + ct_a * 16 + 16) {
+                const float s = s_a;
                 const float bias = -128.0f * s;
-                uint32_t o[8];
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    float f[4];
-                    word_to_scaled_f32(w[i], s, bias, f);
-                    o[2 * i] = bf16x2(f[0], f[1]);
-                    o[2 * i + 1] = bf16x2(f[2], f[3]);
-                }
-                uint16_t *d = out + (pos + (uint64_t)r * round_bytes);
-                store16_stream(d, o[0], o[1], o[2], o[3]);
-                store16_stream(d + 8, o[4], o[5], o[6], o[7]);
+                float f[8];
+                word_to_scaled_f32(wa[0], s, bias, f);
+                word_to_scaled_f32(wa[1], s, bias, f + 4);
+                store16_stream(out + (pos_a + base + 8 * upper), bf16x2(f[0], f[1]), bf16x2(f[2], f[3]), bf16x2(f[4], f[5]),
+                               bf16x2(f[6], f[7]));
             }
-            col += round_bytes;
-            while (col >= cols) { col -= cols; row++; }
+            if (raw >= base + ct_b * 16 + 16) {
+                const float s = s_b;
+                const float bias = -128.0f * s;
+                float f[8];
+                word_to_scaled_f32(wb[0], s, bias, f);
+                word_to_scaled_f32(wb[1], s, bias, f + 4);
+                store16_stream(out + (pos_b + base + 8 * upper), bf16x2(f[0], f[1]), bf16x2(f[2], f[3]), bf16x2(f[4], f[5]),
+                               bf16x2(f[6], f[7]));
+            }
+            col_a += round_bytes;
+            while (col_a >= cols) { col_a -= cols; row_a++; }
+            col_b += round_bytes;
+            while (col_b >= cols) { col_b -= cols; row_b++; }
         }
         return;
     }

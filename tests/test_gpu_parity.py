@@ -143,6 +143,26 @@ def test_dequant_bf16_bit_exact(S, rows, cols, rescale):
     assert np.array_equal(got, oq.dequant_bf16(q, scale))
 
 
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
+@pytest.mark.parametrize("rows,cols,C,f", [(1, 16784, 16384, 0.0), (3, 5488, 4096, 0.5), (67, 1040, 65536, 0.0),
+                                           (40, 2752, 16384, 1.0)])
+def test_dequant_bf16_ragged_ends_and_raw_chunks(S, rows, cols, C, f):
+    """Last chunks that end inside a 16-lane row of sub-streams (the lanes of a row and of the next trade
+    halves before they store), raw chunks among the coded ones, and nothing written past the matrix."""
+    print(f"case bf16 ragged S={S} {rows}x{cols} C={C} f={f}", flush=True)
+    q, scale = oracle_matrix(rows, cols, synth.matrix_seed(4, 2), False)
+    c = oc.compress(q, C, S, oc.RAW_FRACTION, f)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    n = rows * cols
+    out = torch.full((n + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, out, n,
+                               stream())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[:n].reshape(rows, cols), oq.dequant_bf16(q, scale))
+    assert (got[n:] == 0x5A5A).all()
+
+
 def gemv_check(y, y_ref):
     rms = float(np.sqrt(np.mean(y_ref ** 2)))
     err = np.abs(y.astype(np.float64) - y_ref)
