@@ -40,21 +40,30 @@
  *   Huffman payload
  *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
  *                        byte v >> 1; 0 = value absent, otherwise 1..11
- *       [128,128+2S)     u16 nb[j], j < S: number of 16-byte blocks of sub-stream j
- *       [128+2S, +4*S/W) u32 set_off[w]: first byte of the block region of stream set w, counted
+ *       [128,128+2S)     u16 per sub-stream j < S: bits 0..13 nb[j], the number of 16-byte blocks
+ *                        of the stream; bits 14..15 tw[j] - 1, where tw[j] = 1..4 is the number
+ *                        of 32-bit words of the stream's last block that hold stream bits (both
+ *                        fields 0 for a stream without symbols)
+ *       [128+2S, +4*S/W) u32 set_off[w]: first byte of the area of stream set w, counted
  *                        from the payload start, multiple of 16; then zero padding to a multiple
  *                        of 16.  A stream set is W = min(S, 64) consecutive sub-streams (the
  *                        streams one wavefront decodes): set w = streams [W*w, W*w + W).
  *       sub-streams      the chunk is cut in 16-byte groups; group g belongs to
  *                        sub-stream g mod S; a sub-stream is the concatenated
- *                        codes of its bytes in increasing position, zero padded
- *                        to a whole number of 16-byte blocks.  No end marker:
- *                        symbol counts follow from raw_bytes.
+ *                        codes of its bytes in increasing position; seen as a
+ *                        sequence of 16-byte blocks it is zero padded to a whole
+ *                        block.  No end marker: symbol counts follow from raw_bytes.
  *       bit order        stream bit i is bit (i mod 32) of little-endian u32
  *                        word i / 32; a code is written most significant code
  *                        bit first.
- *       block regions    one per stream set, back to back after the header.  A region holds
- *                        the blocks of its streams interleaved in the order in which a decoder
+ *       set areas        one per stream set, back to back after the header, each a multiple of
+ *                        16 bytes.  An area is a block region, then the tails, then zero
+ *                        padding.  The tails are the last blocks of the set's streams, in
+ *                        ascending stream order, each cut down to its first tw[j] words (so a
+ *                        stream costs its bits rounded up to 4 bytes, not to 16; a reader may
+ *                        load 16 bytes at a tail and ignore the rest: DC_BLOB_TAIL_BYTES keep
+ *                        that inside the blob).  The region holds every other block
+ *                        of the streams, interleaved in the order in which a decoder
  *                        that works through all streams in step asks for them, so that it
  *                        reads the region front to back.  The order is fixed by this rule.
  *                        Decoding goes in steps h = 0, 1, ...; step h comes before symbols
@@ -62,8 +71,10 @@
  *                        Let c[j] be the stream bits used by the symbols of stream j that come
  *                        before step h, and f[j] the blocks of stream j placed so far.  At a
  *                        step, for j ascending over the set: if f[j] < nb[j] and
- *                        128*f[j] - c[j] < DC_LOOKAHEAD_BITS, block f[j] of stream j is placed
- *                        next in the region and f[j] grows by one.  Step 0 is carried out three
+ *                        128*f[j] - c[j] < DC_LOOKAHEAD_BITS, the stream takes block f[j] and
+ *                        f[j] grows by one; a block that is not the stream's last is placed
+ *                        next in the region, the last one is the stream's tail and takes no
+ *                        place in the region.  Step 0 is carried out three
  *                        times in a row, every later step once.  (Half a group uses at most 88
  *                        bits, so after every step a stream has at least DC_LOOKAHEAD_BITS bits
  *                        placed beyond its position, or all of its blocks; every block is

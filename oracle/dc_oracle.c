@@ -25,18 +25,24 @@
  *   Huffman payload
  *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
  *                      (0 = value absent, else 1..11)
- *     [128,128+2S)     u16 nb[j]: number of 16-byte blocks of sub-stream j
+ *     [128,128+2S)     u16 per sub-stream j: bits 0-13 nb[j], the number of
+ *                      16-byte blocks of the stream; bits 14-15 tw[j]-1, where
+ *                      tw[j] = 1..4 is the number of 32-bit words of its last
+ *                      block that hold stream bits (0 if nb[j] = 0)
  *     then             u32 set_off[w], one per stream set: start of the set's
- *                      block region from payload start; then zeros to a
- *                      multiple of 16.  A stream set is W = min(S,64)
- *                      consecutive sub-streams.
+ *                      area from payload start; then zeros to a multiple of
+ *                      16.  A stream set is W = min(S,64) consecutive
+ *                      sub-streams.
  *     sub-streams      stream j = codes of the bytes of the 16-byte groups
  *                      g = j, j+S, j+2S, ... of the chunk, in increasing
- *                      position; a stream is padded with zero bits to a whole
- *                      number of 16-byte blocks
- *     block regions    one per stream set, back to back after the header; the
- *                      blocks of the set's streams in the order of the
- *                      placement rule below (orc_step)
+ *                      position; as a sequence of blocks it is padded with
+ *                      zero bits to a whole number of 16-byte blocks
+ *     set areas        one per stream set, back to back after the header:
+ *                      first every block but the last of each of the set's
+ *                      streams, in the order of the placement rule below; then
+ *                      the tails: for the streams of the set in ascending
+ *                      order, the first tw[j] words of the stream's last
+ *                      block; then zeros to a multiple of 16
  *   bit order          stream bit i is bit (i mod 8) of stream byte i/8; a code
  *                      is written most significant code bit first
  *   codes              canonical: lengths by package-merge (below), codes
@@ -46,9 +52,10 @@
  * symbols 8*(h%2) .. 8*(h%2)+7 of group number h/2 of every stream.  With c[j]
  * the stream bits used by the symbols of stream j before step h and f[j] the
  * blocks of stream j placed so far: at a step, for j ascending over the set, if
- * f[j] < nb[j] and 128*f[j] - c[j] < 320 then block f[j] of stream j is placed
- * next in the region and f[j] grows by one.  Step 0 is carried out three times,
- * every later step once.
+ * f[j] < nb[j] and 128*f[j] - c[j] < 320 then the stream takes block f[j] and
+ * f[j] grows by one: a block that is not the stream's last is the next one in
+ * the area, the last block is the stream's tail.  Step 0 is carried out three
+ * times, every later step once.
  *
  * Every function is written for a reader to check by eye, not for speed:
  * one bit at a time, explicit item lists, no tables.
@@ -239,7 +246,8 @@ static uint32_t header_bytes(uint32_t S)
     return (uint32_t)round_up(128 + 2 * (uint64_t)S + 4 * (uint64_t)(S / set_width(S)), 16);
 }
 
-/* Upper bound of a Huffman payload: header + 11 bits a symbol + one partial block a stream. */
+/* Upper bound of a Huffman payload: header + 11 bits a symbol + one partial block a stream
+ * (more than the tails and the padding of the sets can take). */
 uint64_t orc_huff_bound(uint32_t raw_bytes, uint32_t S)
 {
     return round_up(header_bytes(S) + ((uint64_t)raw_bytes * 11 + 7) / 8 + ORC_BLOCK * (uint64_t)S, 16);
@@ -290,34 +298,44 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         return 0;
     orc_canonical_codes(len, code);
 
-    /* size: header, then each stream rounded up to whole blocks */
+    /* size: header, then set by set the whole blocks of the streams (all but the last block of
+     * each) and the last blocks cut down to the 32-bit words that hold bits, the set padded to 16 */
     uint32_t groups = (raw_bytes + 15) / 16;
     uint32_t W = set_width(S), n_sets = S / W, hdr = header_bytes(S);
     uint64_t *nb = calloc(S, sizeof(uint64_t));
-    if (!nb)
+    uint64_t *tw = calloc(S, sizeof(uint64_t));
+    if (!nb || !tw) {
+        free(nb); free(tw);
         return 0;
+    }
     uint64_t total = hdr;
-    for (uint32_t j = 0; j < S; j++) {
-        uint64_t bits = 0;
-        for (uint32_t g = j; g < groups; g += S)
-            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
-                bits += len[src[p]];
-        nb[j] = (bits + 8 * ORC_BLOCK - 1) / (8 * ORC_BLOCK);
-        total += nb[j] * ORC_BLOCK;
+    for (uint32_t w = 0; w < n_sets; w++) {
+        uint64_t area = 0;
+        for (uint32_t j = w * W; j < (w + 1) * W; j++) {
+            uint64_t bits = 0;
+            for (uint32_t g = j; g < groups; g += S)
+                for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
+                    bits += len[src[p]];
+            uint64_t words = (bits + 31) / 32;
+            nb[j] = (words + 3) / 4;
+            tw[j] = nb[j] ? words - 4 * (nb[j] - 1) : 0;
+            area += nb[j] ? (nb[j] - 1) * ORC_BLOCK + 4 * tw[j] : 0;
+        }
+        total += round_up(area, 16);
     }
     if (!out) {
-        free(nb);
+        free(nb); free(tw);
         return total;
     }
     if (cap < total) {
-        free(nb);
+        free(nb); free(tw);
         return 0;
     }
     memset(out, 0, total);
     for (int v = 0; v < 256; v++)
         out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
     for (uint32_t j = 0; j < S; j++) {
-        uint16_t n16 = (uint16_t)nb[j];
+        uint16_t n16 = (uint16_t)(nb[j] | (tw[j] ? (tw[j] - 1) << 14 : 0));
         memcpy(out + 128 + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
     }
 
@@ -345,7 +363,7 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         }
     }
 
-    /* block regions: the placement rule, set by set */
+    /* set areas: the placement rule for the whole blocks, then the tails in stream order */
     uint64_t pos = hdr;
     uint32_t steps = step_count(raw_bytes, S);
     for (uint32_t w = 0; w < n_sets; w++) {
@@ -359,8 +377,10 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
                     uint32_t j = w * W + i;
                     uint64_t c = used[j][symbols_before_step(raw_bytes, S, j, h)];
                     if (f[i] < nb[j] && 128 * f[i] < c + ORC_LOOKAHEAD) {
-                        memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
-                        pos += ORC_BLOCK;
+                        if (f[i] + 1 < nb[j]) { /* the last block is not stored here */
+                            memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
+                            pos += ORC_BLOCK;
+                        }
                         f[i]++;
                     }
                 }
@@ -370,6 +390,13 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
             if (f[i] != nb[w * W + i])
                 total = 0; /* cannot happen: every block is placed by the last step */
         free(f);
+        for (uint32_t j = w * W; j < (w + 1) * W; j++) {
+            if (nb[j] == 0)
+                continue;
+            memcpy(out + pos, st[j] + (nb[j] - 1) * ORC_BLOCK, 4 * tw[j]);
+            pos += 4 * tw[j];
+        }
+        pos = round_up(pos, 16);
     }
     if (pos != total)
         total = 0;
@@ -377,7 +404,7 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         free(st[j]);
         free(used[j]);
     }
-    free(st); free(used); free(nb);
+    free(st); free(used); free(nb); free(tw);
     return total;
 }
 
@@ -428,28 +455,44 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         uint32_t off32;
         memcpy(&off32, payload + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, 4);
         uint64_t pos = off32;
-        /* per stream of the set: its blocks collected so far, bits used, symbols decoded */
+        /* per stream of the set: blocks in all, words of the last one, where that one lies; its
+         * blocks collected so far, bits used */
         uint8_t **st = calloc(W, sizeof(uint8_t *));
         uint64_t *f = calloc(W, sizeof(uint64_t));
         uint64_t *bit = calloc(W, sizeof(uint64_t));
+        uint64_t *nb = calloc(W, sizeof(uint64_t));
+        uint64_t *tw = calloc(W, sizeof(uint64_t));
+        uint64_t *tail = calloc(W, sizeof(uint64_t));
+        uint64_t tail_pos = off32;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
             memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
-            st[i] = calloc((size_t)n16 * ORC_BLOCK + 1, 1);
+            nb[i] = n16 & 0x3FFFu;
+            tw[i] = nb[i] ? (n16 >> 14) + 1u : 0;
+            st[i] = calloc((size_t)nb[i] * ORC_BLOCK + 1, 1);
+            tail_pos += nb[i] ? (nb[i] - 1) * ORC_BLOCK : 0;
         }
+        for (uint32_t i = 0; i < W; i++) { /* the tails follow the whole blocks of the set */
+            tail[i] = tail_pos;
+            tail_pos += 4 * tw[i];
+        }
+        if (tail_pos > comp_bytes)
+            rc = ORC_E_FORMAT;
         for (uint32_t h = 0; h < steps && rc == ORC_OK; h++) {
             int times = h == 0 ? 3 : 1;
             for (int t = 0; t < times && rc == ORC_OK; t++) {
                 for (uint32_t i = 0; i < W; i++) {
-                    uint16_t n16;
-                    memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
-                    if (f[i] < n16 && 128 * f[i] < bit[i] + ORC_LOOKAHEAD) {
-                        if (pos + ORC_BLOCK > comp_bytes) {
-                            rc = ORC_E_FORMAT;
-                            break;
+                    if (f[i] < nb[i] && 128 * f[i] < bit[i] + ORC_LOOKAHEAD) {
+                        if (f[i] + 1 < nb[i]) {
+                            if (pos + ORC_BLOCK > tail[0]) { /* more whole blocks asked for than the area has */
+                                rc = ORC_E_FORMAT;
+                                break;
+                            }
+                            memcpy(st[i] + f[i] * ORC_BLOCK, payload + pos, ORC_BLOCK);
+                            pos += ORC_BLOCK;
+                        } else {
+                            memcpy(st[i] + f[i] * ORC_BLOCK, payload + tail[i], 4 * tw[i]);
                         }
-                        memcpy(st[i] + f[i] * ORC_BLOCK, payload + pos, ORC_BLOCK);
-                        pos += ORC_BLOCK;
                         f[i]++;
                     }
                 }
@@ -488,7 +531,7 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         }
         for (uint32_t i = 0; i < W; i++)
             free(st[i]);
-        free(st); free(f); free(bit);
+        free(st); free(f); free(bit); free(nb); free(tw); free(tail);
     }
     return rc;
 }

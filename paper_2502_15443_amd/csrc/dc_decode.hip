@@ -98,17 +98,21 @@ struct Stream {
     uint32_t next;  // the word that follows buf
     uint32_t tk10;  // 1024 * (blocks asked for so far, f of the placement rule)
     uint32_t nb10;  // 1024 * (blocks of the stream)
+    uint32_t tail_off; // payload offset of the stream's last block, which is stored cut to its used words
     uint32_t pend;  // != 0: blk holds the block asked for at the last step, not yet in the ring
     u32x4 blk;
 };
 
-// What the lanes of one stream set share: where the set's region stands.
+// What the lanes of one stream set share: where the block region of the set's area stands.
 struct Region {
     const uint8_t *payload8;
     uint32_t next_block; // in 16-byte units from the payload start
-    uint32_t max_off;    // last payload offset a block may be loaded from
+    uint32_t max_off;    // last payload offset 16 bytes may be loaded from without leaving the blob
     uint64_t lanes;      // the lanes of the wave that belong to the set
 };
+
+// 16 bytes at an address that is a multiple of 4 only (the cut-down last blocks)
+typedef uint32_t u32x4_align4 __attribute__((ext_vector_type(4), aligned(4)));
 
 // Block number b of a stream goes to ring words 4b .. 4b+3.
 __device__ __forceinline__ void push_block(uint32_t block10, const u32x4 &blk, uint32_t ring_lane)
@@ -125,16 +129,18 @@ __device__ __forceinline__ uint32_t ring_word(uint32_t state, uint32_t ring_lane
     return lds_load32((state & 0xF00u) | ring_lane);
 }
 
-// The lanes with `want` each take the next block of the region, in lane order.
+// The lanes with `want` each take their next block: the next of the region, in lane order, or, for
+// the last block of a stream (`last`), the stream's tail.
 template <bool UNIFORM>
-__device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u32x4 &dst)
+__device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, bool last, u32x4 &dst)
 {
-    const uint64_t m = __ballot(want) & rg.lanes;
+    const uint64_t m = __ballot(want && !last) & rg.lanes;
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     if (want) {
-        uint32_t off = (rg.next_block + rank) * kBlockBytes;
+        uint32_t off = last ? s.tail_off : (rg.next_block + rank) * kBlockBytes;
         off = off < rg.max_off ? off : rg.max_off;
-        dst = *reinterpret_cast<const u32x4 *>(rg.payload8 + off);
+        const u32x4_align4 v = *reinterpret_cast<const u32x4_align4 *>(rg.payload8 + off);
+        dst = u32x4{v[0], v[1], v[2], v[3]};
         s.tk10 += 1024;
     }
     rg.next_block += (uint32_t)__popcll(m);
@@ -153,15 +159,27 @@ __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring
     const int32_t short_of = (int32_t)(s.tk10 + 9u * avail) - (int32_t)(s.state + 8u * (DC_LOOKAHEAD_BITS - 32));
     const int32_t left = (int32_t)s.tk10 - (int32_t)s.nb10;
     const bool want = (short_of > left ? short_of : left) < 0; // both negative
-    take_blocks<UNIFORM>(s, rg, want, s.blk);
+    take_blocks<UNIFORM>(s, rg, want, left == -1024, s.blk);
     s.pend = want;
 }
 
 // Start of a sub-stream: step 0 of the rule runs three times (nothing is used yet, so every stream
 // with blocks left takes one each time), then buf and next are loaded.
 template <bool UNIFORM>
-__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t nb, uint32_t ring_lane)
+__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t field, uint32_t ring_lane)
 {
+    // header field of the stream: blocks in all, and the words of the last block less one
+    const uint32_t nb = field & 0x3FFFu;
+    const uint32_t tw = nb ? ((field >> 14) & 3u) + 1 : 0;
+    // the tails of the set follow its whole blocks, in lane order
+    const uint32_t whole_incl = lanes_prefix_sum<!UNIFORM>(nb ? nb - 1 : 0);
+    const uint32_t tails_incl = lanes_prefix_sum<!UNIFORM>(tw);
+    uint32_t whole_total = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 63);
+    if (!UNIFORM) {
+        const uint32_t lower = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 31);
+        whole_total = (threadIdx.x & 32u) ? whole_total : lower;
+    }
+    s.tail_off = (rg.next_block + whole_total) * kBlockBytes + 4 * (tails_incl - tw);
     s.nb10 = nb << 10;
     s.tk10 = 0;
     s.pend = 0;
@@ -170,7 +188,7 @@ __device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t nb, 
 #pragma unroll
     for (int t = 0; t < 3; t++) {
         got[t] = s.tk10 < s.nb10;
-        take_blocks<UNIFORM>(s, rg, got[t], b[t]);
+        take_blocks<UNIFORM>(s, rg, got[t], s.tk10 + 1024 == s.nb10, b[t]);
     }
 #pragma unroll
     for (int t = 0; t < 3; t++)
@@ -491,7 +509,9 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     Stream st;
     if (huff) {
         rg.payload8 = payload8;
-        rg.max_off = ent.comp_bytes - kBlockBytes;
+        // a tail may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
+        const uint64_t room = a.blob_bytes - ent.off - kBlockBytes;
+        rg.max_off = room < 0xFFFFFFF0ull ? (uint32_t)room : 0xFFFFFFF0u;
         rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
         rg.next_block = payload[(128 + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
         if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);

@@ -40,6 +40,10 @@ struct EncArgs {
 
 __device__ __forceinline__ uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
 __device__ __forceinline__ uint32_t header_bytes(uint32_t S) { return (128 + 2 * S + 4 * (S / set_width(S)) + 15) / 16 * 16; }
+// A sub-stream of `bits` bits: 32-bit words, 16-byte blocks, and words of the last block that hold bits.
+__device__ __forceinline__ uint32_t words_of(uint32_t bits) { return (bits + 31) / 32; }
+__device__ __forceinline__ uint32_t blocks_of(uint32_t bits) { return (words_of(bits) + 3) / 4; }
+__device__ __forceinline__ uint32_t tail_words_of(uint32_t bits) { return bits ? words_of(bits) - 4 * (blocks_of(bits) - 1) : 0; }
 __device__ __forceinline__ uint32_t chunk_len(const EncArgs &a, uint64_t k)
 {
     const uint64_t lo = k * a.chunk_bytes;
@@ -57,7 +61,7 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     __shared__ uint32_t bought_leaves[kL];
     __shared__ uint8_t len_of[256];
     __shared__ uint32_t sbits[256];
-    __shared__ uint32_t blocks_total;
+    __shared__ uint32_t area_bytes[4]; // per stream set: whole blocks and cut-down last blocks
     uint32_t(*level)[512] = reinterpret_cast<uint32_t(*)[512]>(arena);              // weights of the items of the previous / current level
     uint32_t *pack = arena + 1024;                                                    // [256] packages made of the previous level
     uint16_t(*leaves_before)[514] = reinterpret_cast<uint16_t(*)[514]>(arena + 1280); // [kL][514]
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     for (uint32_t i = t; i < 4096; i += 256) arena[i] = 0;
     sbits[t] = 0;
     len_of[t] = 0;
-    if (t == 0) blocks_total = 0;
+    if (t < 4) area_bytes[t] = 0;
     __syncthreads();
     uint32_t *column = arena + (t & 31u);
     auto count = [&](uint32_t b) { atomicAdd(column + ((b >> 1) << 5), 1u << ((b & 1u) << 4)); };
@@ -196,10 +200,14 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     __syncthreads();
     if (t < a.S) {
         a.bits[k * a.S + t] = sbits[t];
-        atomicAdd(&blocks_total, (sbits[t] + kBlockBits - 1) / kBlockBits);
+        if (sbits[t]) atomicAdd(&area_bytes[t / set_width(a.S)], DC_BLOCK_BYTES * (blocks_of(sbits[t]) - 1) + 4 * tail_words_of(sbits[t]));
     }
     __syncthreads();
-    if (t == 0) a.comp[k] = header_bytes(a.S) + DC_BLOCK_BYTES * blocks_total;
+    if (t == 0) {
+        uint32_t size = header_bytes(a.S);
+        for (uint32_t w = 0; w < a.S / set_width(a.S); w++) size += (area_bytes[w] + 15u) & ~15u;
+        a.comp[k] = size;
+    }
 }
 
 // Size of chunk k in the blob and whether it stays raw.
@@ -266,7 +274,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     __shared__ __attribute__((aligned(4096))) uint32_t ring[WAVES * 16 * 64]; // 16 words a lane, as in the decoder
     __shared__ uint32_t book[256];                                            // bit-reversed code | length << 16
     __shared__ uint8_t len_of[256];
-    __shared__ uint32_t set_blocks[WAVES];
+    __shared__ uint32_t set_bytes[WAVES];
     __shared__ uint32_t len_count[4][kL + 1]; // [64 byte values][code length]
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
@@ -292,16 +300,24 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     for (uint32_t i = t; i < 128; i += THREADS) out[i] = (uint8_t)(len_of[2 * i] | (len_of[2 * i + 1] << 4));
     const bool has_stream = t < S;
     const uint32_t stream_bits = has_stream ? a.bits[k * S + t] : 0;
-    const uint32_t nb = (stream_bits + kBlockBits - 1) / kBlockBits;
-    if (has_stream) reinterpret_cast<uint16_t *>(out + 128)[t] = (uint16_t)nb;
-    const uint32_t wave_blocks = lanes_prefix_sum<false>(nb);
-    if (lane == 63) set_blocks[wave] = wave_blocks;
+    const uint32_t nb = blocks_of(stream_bits), tw = tail_words_of(stream_bits);
+    if (has_stream) reinterpret_cast<uint16_t *>(out + 128)[t] = (uint16_t)(nb | (tw ? (tw - 1) << 14 : 0));
+    // the area of a stream set: its whole blocks, then the last blocks cut to their words, lane after lane
+    const uint32_t whole_incl = lanes_prefix_sum<false>(nb ? nb - 1 : 0);
+    const uint32_t tails_incl = lanes_prefix_sum<false>(tw);
+    const uint32_t whole_total = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 63);
+    const uint32_t tails_total = (uint32_t)__builtin_amdgcn_readlane((int)tails_incl, 63);
+    if (lane == 63) set_bytes[wave] = (DC_BLOCK_BYTES * whole_total + 4 * tails_total + 15u) & ~15u;
     __syncthreads();
     const uint32_t hdr = header_bytes(S);
     const uint32_t n_sets = S / set_width(S);
-    uint32_t region = hdr; // first byte of this wave's region
-    for (uint32_t w = 0; w < wave; w++) region += DC_BLOCK_BYTES * set_blocks[w];
+    uint32_t region = hdr; // first byte of this wave's area
+    for (uint32_t w = 0; w < wave; w++) region += set_bytes[w];
     if (lane == 0 && wave < n_sets) reinterpret_cast<uint32_t *>(out + 128 + 2 * S)[wave] = region;
+    const uint32_t tail_at = region + DC_BLOCK_BYTES * whole_total + 4 * (tails_incl - tw);
+    if (lane == 63 && wave < n_sets) // padding of the area
+        for (uint32_t p = region + DC_BLOCK_BYTES * whole_total + 4 * tails_total; p < region + set_bytes[wave]; p += 4)
+            *reinterpret_cast<uint32_t *>(out + p) = 0;
     for (uint32_t i = 128 + 2 * S + 4 * n_sets + t; i < hdr; i += THREADS) out[i] = 0;
 
     // ---- canonical codes: numbered in order of (length, byte value).  A wave looks at 64 consecutive
@@ -429,13 +445,21 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
                     }
                 }
             }
-            const uint64_t m = __ballot(want) & set_lanes;
+            const bool last = taken + 1 == nb; // the last block goes to the tails, cut to its words
+            const uint64_t m = __ballot(want && !last) & set_lanes;
             if (want) {
                 const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
                 u32x4 blk;
 #pragma unroll
                 for (int i = 0; i < 4; i++) blk[i] = lds_load32(ring_lane + (((4 * taken + i) & 15u) << 8));
-                *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
+                if (!last) {
+                    *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
+                } else {
+                    uint32_t *tail = reinterpret_cast<uint32_t *>(out + tail_at);
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+                        if ((uint32_t)i < tw) tail[i] = blk[i];
+                }
                 taken++;
             }
             next_block += (uint32_t)__popcll(m);

@@ -185,18 +185,29 @@ void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &c
     }
 }
 
-inline uint32_t blocks_of(uint64_t bits) { return (uint32_t)((bits + kBlockBits - 1) / kBlockBits); }
+// A sub-stream of `bits` bits: blocks in all, and 32-bit words of the last block that hold bits.
+inline uint32_t words_of(uint64_t bits) { return (uint32_t)((bits + 31) / 32); }
+inline uint32_t blocks_of(uint64_t bits) { return (words_of(bits) + 3) / 4; }
+inline uint32_t tail_words_of(uint64_t bits) { return bits ? words_of(bits) - 4 * (blocks_of(bits) - 1) : 0; }
 
+// Header, then per stream set the whole blocks, the cut-down last blocks and padding to 16.
 uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
 {
+    const uint32_t W = set_width(S);
     uint64_t pos = header_bytes(S);
-    for (uint32_t j = 0; j < S; j++) pos += (uint64_t)blocks_of(bits[j]) * kBlock;
+    for (uint32_t s0 = 0; s0 < S; s0 += W) {
+        uint64_t area = 0;
+        for (uint32_t j = s0; j < s0 + W; j++)
+            if (bits[j]) area += (uint64_t)(blocks_of(bits[j]) - 1) * kBlock + 4ull * tail_words_of(bits[j]);
+        pos += align_up(area, 16);
+    }
     return (uint32_t)pos;
 }
 
 // Writes one Huffman payload; `out` has comp_bytes bytes.  Every sub-stream is first coded on its
-// own (whole blocks, zero padded) while the bits it has used before each step are noted; then the
-// blocks are placed, stream set by stream set, in the order of the placement rule of the format.
+// own (whole blocks, zero padded) while the bits it has used before each step are noted; then, stream
+// set by stream set, the blocks but the last of each stream are placed in the order of the placement
+// rule of the format and the last blocks follow, cut to the words that hold bits.
 void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb,
                         const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
 {
@@ -211,7 +222,8 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
     for (uint32_t j = 0; j < S; j++) {
         nb[j] = blocks_of(bits[j]);
         first_block[j + 1] = first_block[j] + nb[j];
-        const uint16_t n16 = (uint16_t)nb[j];
+        const uint32_t tw = tail_words_of(bits[j]);
+        const uint16_t n16 = (uint16_t)(nb[j] | (tw ? (tw - 1) << 14 : 0));
         std::memcpy(out + 128 + 2 * j, &n16, 2);
     }
     std::vector<uint8_t> coded((size_t)first_block[S] * kBlock + 8, 0);
@@ -254,13 +266,22 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
                 for (uint32_t i = 0; i < W; i++) {
                     const uint32_t j = s0 + i;
                     if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < (uint64_t)used[(size_t)j * (steps + 1) + h] + DC_LOOKAHEAD_BITS) {
-                        std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
-                        pos += kBlock;
+                        if (f[i] + 1 < nb[j]) { // the last block goes to the tails
+                            std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
+                            pos += kBlock;
+                        }
                         f[i]++;
                     }
                 }
             }
         }
+        for (uint32_t j = s0; j < s0 + W; j++) {
+            if (nb[j] == 0) continue;
+            const uint32_t n = 4 * tail_words_of(bits[j]);
+            std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + nb[j] - 1) * kBlock, n);
+            pos += n;
+        }
+        pos = (uint32_t)align_up(pos, 16);
     }
 }
 
@@ -270,7 +291,7 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.1 (gfx950; canonical Huffman L11, block-interleaved sub-streams)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.2 (gfx950; canonical Huffman L11, block-interleaved sub-streams, last blocks cut to words)"; }
 
 extern "C" const char *dc_strerror(int code)
 {
@@ -547,25 +568,46 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
         uint32_t off;
         std::memcpy(&off, p + 128 + 2 * S + 4 * w, 4);
         if (off != region) return false;
-        std::vector<uint32_t> nb(W), f(W, 0);
-        std::vector<uint64_t> bit(W, 0);
-        std::vector<std::vector<uint32_t>> where(W); // payload offset of each placed block
-        uint64_t blocks = 0;
+        std::vector<uint32_t> nb(W), tw(W), tail_at(W), f(W, 0);
+        std::vector<uint64_t> bit(W, 0), have(W, 0);
+        std::vector<std::vector<uint32_t>> where(W); // payload offset of each block taken
+        uint64_t whole = 0, tail_words = 0;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
             std::memcpy(&n16, p + 128 + 2 * (w * W + i), 2);
-            nb[i] = n16;
-            blocks += n16;
+            nb[i] = n16 & 0x3FFFu;
+            tw[i] = nb[i] ? (n16 >> 14) + 1u : 0;
+            if (nb[i] == 0 && n16 != 0) return false;
+            whole += nb[i] ? nb[i] - 1 : 0;
+            tail_words += tw[i];
         }
-        if (blocks * kBlock > comp - region) return false;
+        const uint64_t area = align_up(whole * kBlock + 4 * tail_words, 16);
+        if (area > comp - region) return false;
         uint32_t pos = region;
-        region += (uint32_t)(blocks * kBlock);
+        {
+            uint32_t at = region + (uint32_t)(whole * kBlock);
+            for (uint32_t i = 0; i < W; i++) {
+                tail_at[i] = at;
+                at += 4 * tw[i];
+            }
+            for (; at < region + area; at++)
+                if (p[at]) return false; // padding of the area
+        }
+        const uint32_t tails_begin = region + (uint32_t)(whole * kBlock);
+        region += (uint32_t)area;
         for (uint32_t h = 0; h < steps; h++) {
             for (int t = (h == 0 ? 3 : 1); t > 0; t--)
                 for (uint32_t i = 0; i < W; i++)
                     if (f[i] < nb[i] && (uint64_t)kBlockBits * f[i] < bit[i] + DC_LOOKAHEAD_BITS) {
-                        where[i].push_back(pos);
-                        pos += kBlock;
+                        if (f[i] + 1 < nb[i]) {
+                            if (pos + kBlock > tails_begin) return false;
+                            where[i].push_back(pos);
+                            pos += kBlock;
+                            have[i] += kBlockBits;
+                        } else {
+                            where[i].push_back(tail_at[i]);
+                            have[i] += 32 * tw[i];
+                        }
                         f[i]++;
                     }
             for (uint32_t i = 0; i < W; i++) {
@@ -573,24 +615,24 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
                 if (g >= groups) continue;
                 const uint32_t lo = 16 * g + 8 * (h & 1);
                 const uint32_t hi = std::min(raw, lo + 8);
-                const uint64_t have = (uint64_t)kBlockBits * f[i];
                 for (uint32_t q = lo; q < hi; q++) {
                     uint32_t window = 0;
                     for (int b = 0; b < DC_MAX_CODE_LEN; b++) {
                         const uint64_t x = bit[i] + b;
-                        if (x < have) {
+                        if (x < have[i]) {
                             const uint32_t byte = where[i][x / kBlockBits] + (uint32_t)(x % kBlockBits) / 8;
                             window |= (uint32_t)((p[byte] >> (x & 7)) & 1u) << b;
                         }
                     }
                     const int l = peek_len[window];
-                    if (l == 0 || bit[i] + l > have) return false;
+                    if (l == 0 || bit[i] + l > have[i]) return false;
                     bit[i] += l;
                 }
             }
         }
         for (uint32_t i = 0; i < W; i++)
-            if (f[i] != nb[i] || blocks_of(bit[i]) != nb[i]) return false;
+            if (f[i] != nb[i] || blocks_of(bit[i]) != nb[i] || tail_words_of(bit[i]) != tw[i]) return false;
+        if (pos != tails_begin) return false;
     }
     return region == comp;
 }

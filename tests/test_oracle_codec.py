@@ -198,7 +198,7 @@ def test_lopsided_streams_round_trip_and_lookahead(raw, S):
     assert pyref.parse_and_decode(payload.tobytes(), raw, S) == data.tobytes()
     ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
     assert ln.max() >= 9 and ln[0] <= 2
-    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int) & 0x3FFF
     groups = (raw + 15) // 16
     rounds = (groups + S - 1) // S
     for j in range(min(S, 3)):  # the extreme streams
@@ -247,17 +247,48 @@ def test_header_layout_and_payload_size_closed_form(raw, S):
     ln = oc.code_lengths(cnt.astype(np.uint64)).astype(int)
     for v in range(256):
         assert (payload[v >> 1] >> (4 * (v & 1))) & 15 == ln[v]
-    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    field = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    nb, last_words = field & 0x3FFF, (field >> 14) + 1
     W = min(S, 64)
     set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
-    for j in range(S):  # each stream is its bits rounded up to 16-byte blocks
-        assert nb[j] == (stream_bits(data, ln, S, j) + 127) // 128
+    for j in range(S):  # a stream is its bits rounded up to 32-bit words: whole blocks, then 1..4 words
+        words = (stream_bits(data, ln, S, j) + 31) // 32
+        assert words > 0 and nb[j] == (words + 3) // 4 and last_words[j] == words - 4 * (nb[j] - 1)
     pos = header_bytes(S)
     assert not payload[128 + 2 * S + 4 * (S // W):pos].any()
-    for w in range(S // W):  # regions back to back after the header
+    for w in range(S // W):  # areas back to back after the header, each padded to 16 bytes
         assert set_off[w] == pos
-        pos += 16 * int(nb[w * W:(w + 1) * W].sum())
+        end = pos + 16 * int((nb[w * W:(w + 1) * W] - 1).sum()) + 4 * int(last_words[w * W:(w + 1) * W].sum())
+        assert not payload[end:(end + 15) // 16 * 16].any()
+        pos = (end + 15) // 16 * 16
     assert payload.size == pos
+
+
+@pytest.mark.parametrize("raw,S", [(65536, 256), (16384, 32)])
+def test_last_blocks_are_stored_as_their_used_words_in_stream_order(raw, S):
+    """After the whole blocks of a set come the last blocks of its streams, cut to the words that
+    hold bits: compare with every stream written out independently."""
+    data = gaussian_bytes(raw, 25.0, 11)
+    payload = oc.encode_chunk(data, S)
+    ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
+    code = oc.canonical_codes(ln.astype(np.uint8)).astype(int)
+    W = min(S, 64)
+    set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
+    for w in range(S // W):
+        streams = []
+        for j in range(w * W, (w + 1) * W):
+            bits = []
+            for g in range(j, raw // 16, S):
+                for p in range(16 * g, 16 * g + 16):
+                    v = int(data[p])
+                    bits += [(code[v] >> k) & 1 for k in range(ln[v] - 1, -1, -1)]
+            bits += [0] * (-len(bits) % 32)
+            streams.append(np.packbits(np.array(bits, dtype=np.uint8), bitorder="little").tobytes())
+        pos = set_off[w] + sum((len(b) - 1) // 16 * 16 for b in streams)
+        for b in streams:
+            cut = (len(b) - 1) // 16 * 16  # bytes of the stream in whole blocks before its last block
+            assert payload[pos:pos + len(b) - cut].tobytes() == b[cut:]
+            pos += len(b) - cut
 
 
 def test_first_blocks_of_a_region_are_the_streams_in_turn():
@@ -289,7 +320,7 @@ def test_single_value_chunk_closed_form():
     data = np.full(raw, 0xE7, dtype=np.uint8)
     payload = oc.encode_chunk(data, S)
     per_stream = raw // S  # one bit a symbol
-    want = header_bytes(S) + S * ((per_stream + 127) // 128 * 16)
+    want = header_bytes(S) + (S * ((per_stream + 31) // 32 * 4) + 15) // 16 * 16
     assert payload.size == want
     assert not payload[128 + 2 * S + 4:].any()  # code 0 everywhere
     assert (oc.decode_chunk(payload, raw, S) == data).all()
