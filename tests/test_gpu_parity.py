@@ -103,6 +103,69 @@ def test_destination_untouched_beyond_decoded_bytes():
     assert np.array_equal(out[:n], data) and (out[n:] == 0x5A).all()
 
 
+@pytest.mark.parametrize("S", [32, 256])
+def test_corrupt_payloads_and_table_entries_stay_inside_the_buffers(S):
+    """Whatever the payloads and the table hold, the kernels read inside the blob and write inside the
+    destination (the header of the library promises it; dc_validate is what reports the damage): chunks
+    with damaged headers or random payloads give unspecified bytes for those chunks only, chunks with
+    impossible table entries are skipped, the others decode, and the guard bytes stay."""
+    print(f"case corrupt S={S}", flush=True)
+    C = 16384
+    n = 12 * C
+    rows, cols = 12 * 16, 1024
+    q, scale = oracle_matrix(rows, cols, synth.matrix_seed(5, 1), False)
+    data = q.view(np.uint8).ravel()
+    c = oc.compress(data, C, S)
+    blob, table = c.blob.copy(), c.table.copy()
+    r = np.random.default_rng(99 + S)
+    off = [int(o) for o in table["off"]]
+    size = [int(x) for x in table["comp_bytes"]]
+    blob[off[1]:off[1] + 128] = r.integers(0, 256, 128, dtype=np.uint8)                  # code lengths
+    blob[off[2] + 128:off[2] + 128 + 2 * S] = r.integers(0, 256, 2 * S, dtype=np.uint8)  # blocks and words per stream
+    blob[off[3] + 128 + 2 * S:off[3] + 132 + 2 * S] = 0xFF                               # area offset far outside
+    blob[off[4]:off[4] + size[4]] = r.integers(0, 256, size[4], dtype=np.uint8)           # everything
+    blob[off[5]:off[5] + 128] = 0x11                                                      # 256 codes of one bit
+    blob[off[6]:off[6] + 128] = 0                                                         # no code at all
+    table["off"][7] += 4                                 # misaligned
+    table["comp_bytes"][8] = 1 << 30                     # beyond the blob
+    table["raw_bytes_flags"][9] = C + 16                 # longer than a chunk
+    table["off"][10] = 1 << 40                           # beyond the blob
+    good = [0, 11]
+    blob_d, table_d, scale_d = dev(blob), dev(table), torch.from_numpy(scale).cuda()
+    p = dc.Params(C, S)
+
+    dst = torch.full((n + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, blob.size, table_d, 12, p, dst, n, stream())
+    torch.cuda.synchronize()
+    out = dst.cpu().numpy()
+    assert (out[n:] == 0x5A).all()
+    for k in good:
+        assert np.array_equal(out[k * C:(k + 1) * C], data[k * C:(k + 1) * C])
+    for k in (7, 8, 9, 10):
+        assert (out[k * C:(k + 1) * C] == 0x5A).all()  # skipped
+
+    out16 = torch.full((n + 4096,), 0x5A5A, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, blob.size, table_d, 12, p, scale_d, rows, cols, out16, n, stream())
+    torch.cuda.synchronize()
+    got = out16.cpu().numpy().view(np.uint16)
+    assert (got[n:] == 0x5A5A).all()
+    want = oq.dequant_bf16(q, scale).ravel()
+    for k in good:
+        assert np.array_equal(got[k * C:(k + 1) * C], want[k * C:(k + 1) * C])
+
+    x = synth.gen_activation_bf16(cols, 3)
+    x_d = torch.from_numpy(x.view(np.int16)).cuda()
+    y32 = torch.full((rows + 64,), 7.0, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv(blob_d, blob.size, table_d, 12, p, scale_d, rows, cols, x_d, y32, None, stream())
+    torch.cuda.synchronize()
+    y = y32.cpu().numpy()
+    assert (y[rows:] == 7.0).all()
+    y_ref = oq.gemv_ref(q, scale, x)
+    rows_of = lambda k: slice(k * C // cols, (k + 1) * C // cols)
+    for k in good:
+        gemv_check(y[rows_of(k)], y_ref[rows_of(k)])
+
+
 def test_host_argument_checks_on_device_entry_points():
     C, S, n = 4096, 32, 2 * 4096
     data = weightlike_bytes(n, 29)
