@@ -40,45 +40,51 @@
  *   Huffman payload
  *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
  *                        byte v >> 1; 0 = value absent, otherwise 1..11
- *       [128,128+2S)     u16 per sub-stream j < S: bits 0..13 nb[j], the number of 16-byte blocks
- *                        of the stream; bits 14..15 tw[j] - 1, where tw[j] = 1..4 is the number
- *                        of 32-bit words of the stream's last block that hold stream bits (both
- *                        fields 0 for a stream without symbols)
+ *       [128,128+2S)     u16 per sub-stream j < S: bits 0..11 nb[j], the number of 16-byte blocks
+ *                        of the stream; bits 12..15 hb[j] - 1, where hb[j] = 1..16 is the number
+ *                        of bytes of the stream's first block that exist (both fields 0 for a
+ *                        stream without symbols)
  *       [128+2S, +4*S/W) u32 set_off[w]: first byte of the area of stream set w, counted
  *                        from the payload start, multiple of 16; then zero padding to a multiple
  *                        of 16.  A stream set is W = min(S, 64) consecutive sub-streams (the
  *                        streams one wavefront decodes): set w = streams [W*w, W*w + W).
  *       sub-streams      the chunk is cut in 16-byte groups; group g belongs to
  *                        sub-stream g mod S; a sub-stream is the concatenated
- *                        codes of its bytes in increasing position; seen as a
- *                        sequence of 16-byte blocks it is zero padded to a whole
- *                        block.  No end marker: symbol counts follow from raw_bytes.
+ *                        codes of its bytes in increasing position, zero padded
+ *                        to a whole byte.  It is cut into 16-byte blocks from its
+ *                        end: every block is whole except block 0, whose first
+ *                        pad[j] = 16 - hb[j] bytes do not exist.  Positions in a
+ *                        stream count from where block 0 would start: the first
+ *                        code begins at bit 8*pad[j].  No end marker: symbol
+ *                        counts follow from raw_bytes.
  *       bit order        stream bit i is bit (i mod 32) of little-endian u32
  *                        word i / 32; a code is written most significant code
  *                        bit first.
  *       set areas        one per stream set, back to back after the header, each a multiple of
- *                        16 bytes.  An area is a block region, then the tails, then zero
- *                        padding.  The tails are the last blocks of the set's streams, in
- *                        ascending stream order, each cut down to its first tw[j] words (so a
- *                        stream costs its bits rounded up to 4 bytes, not to 16; a reader may
- *                        load 16 bytes at a tail and ignore the rest: DC_BLOB_TAIL_BYTES keep
- *                        that inside the blob).  The region holds every other block
+ *                        16 bytes.  An area is a block region, then the heads, then zero
+ *                        padding.  The heads are the short blocks 0 of the set's streams, in
+ *                        ascending stream order, hb[j] bytes each (so a stream costs its bits
+ *                        rounded up to a byte, not to 16 bytes; a reader may load the 20 bytes
+ *                        from the 4-byte boundary at or before the place where block 0 would
+ *                        start and ignore what is not the head: that place lies inside the
+ *                        payload, and DC_BLOB_TAIL_BYTES keep the end of the load inside the
+ *                        blob).  The region holds every other block
  *                        of the streams, interleaved in the order in which a decoder
  *                        that works through all streams in step asks for them, so that it
  *                        reads the region front to back.  The order is fixed by this rule.
  *                        Decoding goes in steps h = 0, 1, ...; step h comes before symbols
  *                        8*(h mod 2) .. 8*(h mod 2)+7 of group number (h div 2) of every stream.
- *                        Let c[j] be the stream bits used by the symbols of stream j that come
- *                        before step h, and f[j] the blocks of stream j placed so far.  At a
+ *                        Let c[j] be the position of stream j before step h (8*pad[j] plus the
+ *                        bits of its symbols so far), and f[j] the blocks of stream j placed so far.  At a
  *                        step, for j ascending over the set: if f[j] < nb[j] and
  *                        128*f[j] - c[j] < DC_LOOKAHEAD_BITS, the stream takes block f[j] and
- *                        f[j] grows by one; a block that is not the stream's last is placed
- *                        next in the region, the last one is the stream's tail and takes no
- *                        place in the region.  Step 0 is carried out three
- *                        times in a row, every later step once.  (Half a group uses at most 88
- *                        bits, so after every step a stream has at least DC_LOOKAHEAD_BITS bits
- *                        placed beyond its position, or all of its blocks; every block is
- *                        placed by the last step.)
+ *                        f[j] grows by one; block 0 is the stream's head and takes no place in
+ *                        the region, any other block is placed next in the region.  Step 0 is
+ *                        carried out four times in a row, every later step once.  (Three blocks
+ *                        are 384 - 8*pad[j] bits beyond the first position, hence the fourth
+ *                        time.  Half a group uses at most 88 bits, so after every step a stream
+ *                        has at least DC_LOOKAHEAD_BITS bits placed beyond its position, or all
+ *                        of its blocks; every block is placed by the last step.)
  *       codes            canonical: lengths from package-merge with limit 11
  *                        (leaves ordered by count then byte value, a leaf before
  *                        a package of equal weight); codes numbered in order of

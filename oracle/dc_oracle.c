@@ -25,24 +25,28 @@
  *   Huffman payload
  *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
  *                      (0 = value absent, else 1..11)
- *     [128,128+2S)     u16 per sub-stream j: bits 0-13 nb[j], the number of
- *                      16-byte blocks of the stream; bits 14-15 tw[j]-1, where
- *                      tw[j] = 1..4 is the number of 32-bit words of its last
- *                      block that hold stream bits (0 if nb[j] = 0)
+ *     [128,128+2S)     u16 per sub-stream j: bits 0-11 nb[j], the number of
+ *                      16-byte blocks of the stream; bits 12-15 hb[j]-1, where
+ *                      hb[j] = 1..16 is the number of bytes of its first block
+ *                      that hold stream bits (both 0 for an empty stream)
  *     then             u32 set_off[w], one per stream set: start of the set's
  *                      area from payload start; then zeros to a multiple of
  *                      16.  A stream set is W = min(S,64) consecutive
  *                      sub-streams.
  *     sub-streams      stream j = codes of the bytes of the 16-byte groups
  *                      g = j, j+S, j+2S, ... of the chunk, in increasing
- *                      position; as a sequence of blocks it is padded with
- *                      zero bits to a whole number of 16-byte blocks
+ *                      position, rounded up to whole bytes.  It is cut into
+ *                      16-byte blocks from its END: block 0 is short (its
+ *                      first pad[j] = 16 - hb[j] bytes do not exist), every
+ *                      later block is whole.  Positions in a stream count from
+ *                      the start of block 0, so the first code starts at bit
+ *                      8*pad[j].
  *     set areas        one per stream set, back to back after the header:
- *                      first every block but the last of each of the set's
- *                      streams, in the order of the placement rule below; then
- *                      the tails: for the streams of the set in ascending
- *                      order, the first tw[j] words of the stream's last
- *                      block; then zeros to a multiple of 16
+ *                      first the whole blocks (blocks 1, 2, ... of each of the
+ *                      set's streams) in the order of the placement rule
+ *                      below; then the heads: for the streams of the set in
+ *                      ascending order, the hb[j] bytes of block 0; then zeros
+ *                      to a multiple of 16
  *   bit order          stream bit i is bit (i mod 8) of stream byte i/8; a code
  *                      is written most significant code bit first
  *   codes              canonical: lengths by package-merge (below), codes
@@ -53,9 +57,10 @@
  * the stream bits used by the symbols of stream j before step h and f[j] the
  * blocks of stream j placed so far: at a step, for j ascending over the set, if
  * f[j] < nb[j] and 128*f[j] - c[j] < 320 then the stream takes block f[j] and
- * f[j] grows by one: a block that is not the stream's last is the next one in
- * the area, the last block is the stream's tail.  Step 0 is carried out three
- * times, every later step once.
+ * f[j] grows by one: block 0 is the stream's head, any other block is the next
+ * one in the area.  Step 0 is carried out four times, every later step once.
+ * (c[j] counts from the start of block 0: it is 8*pad[j] before the first
+ * symbol, which is why a stream may need a fourth block before it starts.)
  *
  * Every function is written for a reader to check by eye, not for speed:
  * one bit at a time, explicit item lists, no tables.
@@ -298,14 +303,14 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         return 0;
     orc_canonical_codes(len, code);
 
-    /* size: header, then set by set the whole blocks of the streams (all but the last block of
-     * each) and the last blocks cut down to the 32-bit words that hold bits, the set padded to 16 */
+    /* size: header, then set by set the whole blocks of the streams (all but the first block of
+     * each) and the first blocks cut down to the bytes that hold bits, the set padded to 16 */
     uint32_t groups = (raw_bytes + 15) / 16;
     uint32_t W = set_width(S), n_sets = S / W, hdr = header_bytes(S);
     uint64_t *nb = calloc(S, sizeof(uint64_t));
-    uint64_t *tw = calloc(S, sizeof(uint64_t));
-    if (!nb || !tw) {
-        free(nb); free(tw);
+    uint64_t *hb = calloc(S, sizeof(uint64_t));
+    if (!nb || !hb) {
+        free(nb); free(hb);
         return 0;
     }
     uint64_t total = hdr;
@@ -316,26 +321,30 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
             for (uint32_t g = j; g < groups; g += S)
                 for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
                     bits += len[src[p]];
-            uint64_t words = (bits + 31) / 32;
-            nb[j] = (words + 3) / 4;
-            tw[j] = nb[j] ? words - 4 * (nb[j] - 1) : 0;
-            area += nb[j] ? (nb[j] - 1) * ORC_BLOCK + 4 * tw[j] : 0;
+            uint64_t bytes = (bits + 7) / 8;
+            nb[j] = (bytes + ORC_BLOCK - 1) / ORC_BLOCK;
+            hb[j] = nb[j] ? bytes - ORC_BLOCK * (nb[j] - 1) : 0;
+            if (nb[j] > 0xFFFu) { /* the header keeps 12 bits for it: chunks up to 1 MiB split 32 ways or more fit */
+                free(nb); free(hb);
+                return 0;
+            }
+            area += nb[j] ? (nb[j] - 1) * ORC_BLOCK + hb[j] : 0;
         }
         total += round_up(area, 16);
     }
     if (!out) {
-        free(nb); free(tw);
+        free(nb); free(hb);
         return total;
     }
     if (cap < total) {
-        free(nb); free(tw);
+        free(nb); free(hb);
         return 0;
     }
     memset(out, 0, total);
     for (int v = 0; v < 256; v++)
         out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
     for (uint32_t j = 0; j < S; j++) {
-        uint16_t n16 = (uint16_t)(nb[j] | (tw[j] ? (tw[j] - 1) << 14 : 0));
+        uint16_t n16 = (uint16_t)(nb[j] | (hb[j] ? (hb[j] - 1) << 12 : 0));
         memcpy(out + 128 + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
     }
 
@@ -347,8 +356,9 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         uint32_t nsym = orc_stream_symbols(raw_bytes, S, j);
         st[j] = calloc(nb[j] * ORC_BLOCK + 1, 1);
         used[j] = calloc((size_t)nsym + 1, sizeof(uint64_t));
-        uint64_t bit = 0;
+        uint64_t bit = nb[j] ? 8 * (ORC_BLOCK - hb[j]) : 0; /* block 0 begins with bytes that do not exist */
         uint32_t k = 0;
+        used[j][0] = bit;
         for (uint32_t g = j; g < groups; g += S) {
             for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
                 int l = len[src[p]];
@@ -363,7 +373,7 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         }
     }
 
-    /* set areas: the placement rule for the whole blocks, then the tails in stream order */
+    /* set areas: the placement rule for the whole blocks, then the heads in stream order */
     uint64_t pos = hdr;
     uint32_t steps = step_count(raw_bytes, S);
     for (uint32_t w = 0; w < n_sets; w++) {
@@ -371,13 +381,13 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         memcpy(out + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, &off32, 4);
         uint64_t *f = calloc(W, sizeof(uint64_t));
         for (uint32_t h = 0; h < steps; h++) {
-            int times = h == 0 ? 3 : 1;
+            int times = h == 0 ? 4 : 1;
             for (int t = 0; t < times; t++) {
                 for (uint32_t i = 0; i < W; i++) {
                     uint32_t j = w * W + i;
                     uint64_t c = used[j][symbols_before_step(raw_bytes, S, j, h)];
                     if (f[i] < nb[j] && 128 * f[i] < c + ORC_LOOKAHEAD) {
-                        if (f[i] + 1 < nb[j]) { /* the last block is not stored here */
+                        if (f[i] > 0) { /* block 0 is not stored here */
                             memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
                             pos += ORC_BLOCK;
                         }
@@ -393,8 +403,8 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         for (uint32_t j = w * W; j < (w + 1) * W; j++) {
             if (nb[j] == 0)
                 continue;
-            memcpy(out + pos, st[j] + (nb[j] - 1) * ORC_BLOCK, 4 * tw[j]);
-            pos += 4 * tw[j];
+            memcpy(out + pos, st[j] + (ORC_BLOCK - hb[j]), hb[j]);
+            pos += hb[j];
         }
         pos = round_up(pos, 16);
     }
@@ -404,7 +414,7 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         free(st[j]);
         free(used[j]);
     }
-    free(st); free(used); free(nb); free(tw);
+    free(st); free(used); free(nb); free(hb);
     return total;
 }
 
@@ -455,43 +465,44 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         uint32_t off32;
         memcpy(&off32, payload + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, 4);
         uint64_t pos = off32;
-        /* per stream of the set: blocks in all, words of the last one, where that one lies; its
+        /* per stream of the set: blocks in all, bytes of the first one, where that one lies; its
          * blocks collected so far, bits used */
         uint8_t **st = calloc(W, sizeof(uint8_t *));
         uint64_t *f = calloc(W, sizeof(uint64_t));
         uint64_t *bit = calloc(W, sizeof(uint64_t));
         uint64_t *nb = calloc(W, sizeof(uint64_t));
-        uint64_t *tw = calloc(W, sizeof(uint64_t));
-        uint64_t *tail = calloc(W, sizeof(uint64_t));
-        uint64_t tail_pos = off32;
+        uint64_t *hb = calloc(W, sizeof(uint64_t));
+        uint64_t *head = calloc(W, sizeof(uint64_t));
+        uint64_t head_pos = off32;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
             memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
-            nb[i] = n16 & 0x3FFFu;
-            tw[i] = nb[i] ? (n16 >> 14) + 1u : 0;
+            nb[i] = n16 & 0xFFFu;
+            hb[i] = nb[i] ? (n16 >> 12) + 1u : 0;
             st[i] = calloc((size_t)nb[i] * ORC_BLOCK + 1, 1);
-            tail_pos += nb[i] ? (nb[i] - 1) * ORC_BLOCK : 0;
+            head_pos += nb[i] ? (nb[i] - 1) * ORC_BLOCK : 0;
         }
-        for (uint32_t i = 0; i < W; i++) { /* the tails follow the whole blocks of the set */
-            tail[i] = tail_pos;
-            tail_pos += 4 * tw[i];
+        for (uint32_t i = 0; i < W; i++) { /* the heads follow the whole blocks of the set */
+            head[i] = head_pos;
+            head_pos += hb[i];
+            bit[i] = nb[i] ? 8 * (ORC_BLOCK - hb[i]) : 0;
         }
-        if (tail_pos > comp_bytes)
+        if (head_pos > comp_bytes)
             rc = ORC_E_FORMAT;
         for (uint32_t h = 0; h < steps && rc == ORC_OK; h++) {
-            int times = h == 0 ? 3 : 1;
+            int times = h == 0 ? 4 : 1;
             for (int t = 0; t < times && rc == ORC_OK; t++) {
                 for (uint32_t i = 0; i < W; i++) {
                     if (f[i] < nb[i] && 128 * f[i] < bit[i] + ORC_LOOKAHEAD) {
-                        if (f[i] + 1 < nb[i]) {
-                            if (pos + ORC_BLOCK > tail[0]) { /* more whole blocks asked for than the area has */
+                        if (f[i] > 0) {
+                            if (pos + ORC_BLOCK > head[0]) { /* more whole blocks asked for than the area has */
                                 rc = ORC_E_FORMAT;
                                 break;
                             }
                             memcpy(st[i] + f[i] * ORC_BLOCK, payload + pos, ORC_BLOCK);
                             pos += ORC_BLOCK;
                         } else {
-                            memcpy(st[i] + f[i] * ORC_BLOCK, payload + tail[i], 4 * tw[i]);
+                            memcpy(st[i] + (ORC_BLOCK - hb[i]), payload + head[i], hb[i]);
                         }
                         f[i]++;
                     }
@@ -531,7 +542,7 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         }
         for (uint32_t i = 0; i < W; i++)
             free(st[i]);
-        free(st); free(f); free(bit); free(nb); free(tw); free(tail);
+        free(st); free(f); free(bit); free(nb); free(hb); free(head);
     }
     return rc;
 }

@@ -98,7 +98,6 @@ struct Stream {
     uint32_t next;  // the word that follows buf
     uint32_t tk10;  // 1024 * (blocks asked for so far, f of the placement rule)
     uint32_t nb10;  // 1024 * (blocks of the stream)
-    uint32_t tail_off; // payload offset of the stream's last block, which is stored cut to its used words
     uint32_t pend;  // != 0: blk holds the block asked for at the last step, not yet in the ring
     u32x4 blk;
 };
@@ -107,11 +106,11 @@ struct Stream {
 struct Region {
     const uint8_t *payload8;
     uint32_t next_block; // in 16-byte units from the payload start
-    uint32_t max_off;    // last payload offset 16 bytes may be loaded from without leaving the blob
+    uint32_t max_off;    // last payload offset 20 bytes may be loaded from without leaving the blob
     uint64_t lanes;      // the lanes of the wave that belong to the set
 };
 
-// 16 bytes at an address that is a multiple of 4 only (the cut-down last blocks)
+// 16 bytes at an address that is a multiple of 4 only
 typedef uint32_t u32x4_align4 __attribute__((ext_vector_type(4), aligned(4)));
 
 // Block number b of a stream goes to ring words 4b .. 4b+3.
@@ -129,18 +128,17 @@ __device__ __forceinline__ uint32_t ring_word(uint32_t state, uint32_t ring_lane
     return lds_load32((state & 0xF00u) | ring_lane);
 }
 
-// The lanes with `want` each take their next block: the next of the region, in lane order, or, for
-// the last block of a stream (`last`), the stream's tail.
+// The lanes with `want` each take the next block of the region, in lane order.
 template <bool UNIFORM>
-__device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, bool last, u32x4 &dst)
+__device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u32x4 &dst)
 {
-    const uint64_t m = __ballot(want && !last) & rg.lanes;
+    const uint64_t m = __ballot(want) & rg.lanes;
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     if (want) {
-        uint32_t off = last ? s.tail_off : (rg.next_block + rank) * kBlockBytes;
-        off = off < rg.max_off ? off : rg.max_off;
-        const u32x4_align4 v = *reinterpret_cast<const u32x4_align4 *>(rg.payload8 + off);
-        dst = u32x4{v[0], v[1], v[2], v[3]};
+        uint32_t off = (rg.next_block + rank) * kBlockBytes;
+        const uint32_t limit = rg.max_off & ~15u;
+        off = off < limit ? off : limit;
+        dst = *reinterpret_cast<const u32x4 *>(rg.payload8 + off);
         s.tk10 += 1024;
     }
     rg.next_block += (uint32_t)__popcll(m);
@@ -159,45 +157,63 @@ __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring
     const int32_t short_of = (int32_t)(s.tk10 + 9u * avail) - (int32_t)(s.state + 8u * (DC_LOOKAHEAD_BITS - 32));
     const int32_t left = (int32_t)s.tk10 - (int32_t)s.nb10;
     const bool want = (short_of > left ? short_of : left) < 0; // both negative
-    take_blocks<UNIFORM>(s, rg, want, left == -1024, s.blk);
+    take_blocks<UNIFORM>(s, rg, want, s.blk);
     s.pend = want;
 }
 
-// Start of a sub-stream: step 0 of the rule runs three times (nothing is used yet, so every stream
-// with blocks left takes one each time), then buf and next are loaded.
+// Start of a sub-stream.  Block 0 of a stream is short: its first pad = 16 - hb bytes do not exist and
+// its hb bytes lie among the heads, which follow the whole blocks of the set in lane order.  The lane
+// loads the 20 bytes from the 4-byte boundary at or before the place where block 0 would start and
+// shifts them down, so the ring holds block 0 with foreign bytes in front, and starts reading behind
+// them.  Then step 0 of the rule runs for the three further times (a stream takes a block while it
+// has blocks left and fewer than DC_LOOKAHEAD_BITS bits beyond its position 8*pad), and buf and next
+// are loaded.
 template <bool UNIFORM>
 __device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t field, uint32_t ring_lane)
 {
-    // header field of the stream: blocks in all, and the words of the last block less one
-    const uint32_t nb = field & 0x3FFFu;
-    const uint32_t tw = nb ? ((field >> 14) & 3u) + 1 : 0;
-    // the tails of the set follow its whole blocks, in lane order
+    // header field of the stream: blocks in all, and the bytes of block 0 less one
+    const uint32_t nb = field & 0xFFFu;
+    const uint32_t hb = nb ? ((field >> 12) & 15u) + 1 : 0;
+    const uint32_t pad = nb ? kBlockBytes - hb : 0;
     const uint32_t whole_incl = lanes_prefix_sum<!UNIFORM>(nb ? nb - 1 : 0);
-    const uint32_t tails_incl = lanes_prefix_sum<!UNIFORM>(tw);
+    const uint32_t heads_incl = lanes_prefix_sum<!UNIFORM>(hb);
     uint32_t whole_total = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 63);
     if (!UNIFORM) {
         const uint32_t lower = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 31);
         whole_total = (threadIdx.x & 32u) ? whole_total : lower;
     }
-    s.tail_off = (rg.next_block + whole_total) * kBlockBytes + 4 * (tails_incl - tw);
     s.nb10 = nb << 10;
     s.tk10 = 0;
     s.pend = 0;
+    if (nb) {
+        uint32_t at = (rg.next_block + whole_total) * kBlockBytes + (heads_incl - hb) - pad; // the header lies before it
+        at = at < rg.max_off ? at : rg.max_off;
+        const uint8_t *p = rg.payload8 + (at & ~3u);
+        const u32x4_align4 v = *reinterpret_cast<const u32x4_align4 *>(p);
+        const uint32_t v4 = *reinterpret_cast<const uint32_t *>(p + 16);
+        const uint32_t shift = at & 3u;
+        const u32x4 b0 = {__builtin_amdgcn_alignbyte(v[1], v[0], shift), __builtin_amdgcn_alignbyte(v[2], v[1], shift),
+                          __builtin_amdgcn_alignbyte(v[3], v[2], shift), __builtin_amdgcn_alignbyte(v4, v[3], shift)};
+        push_block(0, b0, ring_lane);
+        s.tk10 = 1024;
+    }
     u32x4 b[3];
     bool got[3];
 #pragma unroll
     for (int t = 0; t < 3; t++) {
-        got[t] = s.tk10 < s.nb10;
-        take_blocks<UNIFORM>(s, rg, got[t], s.tk10 + 1024 == s.nb10, b[t]);
+        got[t] = s.tk10 < s.nb10 && s.tk10 < ((8u * pad + DC_LOOKAHEAD_BITS) << 3); // 128 f < c + look-ahead, times 8
+        take_blocks<UNIFORM>(s, rg, got[t], b[t]);
     }
 #pragma unroll
     for (int t = 0; t < 3; t++)
-        if (got[t]) push_block(t << 10, b[t], ring_lane);
-    const uint32_t lo = ring_word(0 << 8, ring_lane);
-    const uint32_t hi = ring_word(1 << 8, ring_lane);
-    s.buf = (uint64_t)lo | ((uint64_t)hi << 32);
-    s.next = ring_word(2 << 8, ring_lane);
-    s.state = (3 << 8) + 64;
+        if (got[t]) push_block((t + 1) << 10, b[t], ring_lane);
+    // the stream begins `pad` bytes into block 0
+    const uint32_t skip = pad >> 2, bits = 8u * (pad & 3u);
+    const uint32_t lo = ring_word(skip << 8, ring_lane);
+    const uint32_t hi = ring_word((skip + 1) << 8, ring_lane);
+    s.buf = ((uint64_t)lo | ((uint64_t)hi << 32)) >> bits;
+    s.next = ring_word((skip + 2) << 8, ring_lane);
+    s.state = ((skip + 3) << 8) + 64 - bits;
 }
 
 // After this at least 33 bits are valid: enough for three codes of 11 bits.
@@ -510,8 +526,8 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     if (huff) {
         rg.payload8 = payload8;
         // a tail may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
-        const uint64_t room = a.blob_bytes - ent.off - kBlockBytes;
-        rg.max_off = room < 0xFFFFFFF0ull ? (uint32_t)room : 0xFFFFFFF0u;
+        const uint64_t room = a.blob_bytes - ent.off - 20;
+        rg.max_off = room < 0xFFFFFFE0ull ? (uint32_t)room : 0xFFFFFFE0u;
         rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
         rg.next_block = payload[(128 + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
         if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);

@@ -40,10 +40,10 @@ struct EncArgs {
 
 __device__ __forceinline__ uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
 __device__ __forceinline__ uint32_t header_bytes(uint32_t S) { return (128 + 2 * S + 4 * (S / set_width(S)) + 15) / 16 * 16; }
-// A sub-stream of `bits` bits: 32-bit words, 16-byte blocks, and words of the last block that hold bits.
-__device__ __forceinline__ uint32_t words_of(uint32_t bits) { return (bits + 31) / 32; }
-__device__ __forceinline__ uint32_t blocks_of(uint32_t bits) { return (words_of(bits) + 3) / 4; }
-__device__ __forceinline__ uint32_t tail_words_of(uint32_t bits) { return bits ? words_of(bits) - 4 * (blocks_of(bits) - 1) : 0; }
+// A sub-stream of `bits` bits is cut into blocks from its end: bytes, 16-byte blocks, and bytes of the short first block.
+__device__ __forceinline__ uint32_t bytes_of(uint32_t bits) { return (bits + 7) / 8; }
+__device__ __forceinline__ uint32_t blocks_of(uint32_t bits) { return (bytes_of(bits) + DC_BLOCK_BYTES - 1) / DC_BLOCK_BYTES; }
+__device__ __forceinline__ uint32_t head_bytes_of(uint32_t bits) { return bits ? bytes_of(bits) - DC_BLOCK_BYTES * (blocks_of(bits) - 1) : 0; }
 __device__ __forceinline__ uint32_t chunk_len(const EncArgs &a, uint64_t k)
 {
     const uint64_t lo = k * a.chunk_bytes;
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     __syncthreads();
     if (t < a.S) {
         a.bits[k * a.S + t] = sbits[t];
-        if (sbits[t]) atomicAdd(&area_bytes[t / set_width(a.S)], DC_BLOCK_BYTES * (blocks_of(sbits[t]) - 1) + 4 * tail_words_of(sbits[t]));
+        if (sbits[t]) atomicAdd(&area_bytes[t / set_width(a.S)], DC_BLOCK_BYTES * (blocks_of(sbits[t]) - 1) + head_bytes_of(sbits[t]));
     }
     __syncthreads();
     if (t == 0) {
@@ -300,24 +300,24 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     for (uint32_t i = t; i < 128; i += THREADS) out[i] = (uint8_t)(len_of[2 * i] | (len_of[2 * i + 1] << 4));
     const bool has_stream = t < S;
     const uint32_t stream_bits = has_stream ? a.bits[k * S + t] : 0;
-    const uint32_t nb = blocks_of(stream_bits), tw = tail_words_of(stream_bits);
-    if (has_stream) reinterpret_cast<uint16_t *>(out + 128)[t] = (uint16_t)(nb | (tw ? (tw - 1) << 14 : 0));
-    // the area of a stream set: its whole blocks, then the last blocks cut to their words, lane after lane
+    const uint32_t nb = blocks_of(stream_bits), hb = head_bytes_of(stream_bits);
+    const uint32_t pad = nb ? DC_BLOCK_BYTES - hb : 0; // bytes that block 0 of the stream lacks at its front
+    if (has_stream) reinterpret_cast<uint16_t *>(out + 128)[t] = (uint16_t)(nb | (hb ? (hb - 1) << 12 : 0));
+    // the area of a stream set: its whole blocks, then the short first blocks, lane after lane
     const uint32_t whole_incl = lanes_prefix_sum<false>(nb ? nb - 1 : 0);
-    const uint32_t tails_incl = lanes_prefix_sum<false>(tw);
+    const uint32_t heads_incl = lanes_prefix_sum<false>(hb);
     const uint32_t whole_total = (uint32_t)__builtin_amdgcn_readlane((int)whole_incl, 63);
-    const uint32_t tails_total = (uint32_t)__builtin_amdgcn_readlane((int)tails_incl, 63);
-    if (lane == 63) set_bytes[wave] = (DC_BLOCK_BYTES * whole_total + 4 * tails_total + 15u) & ~15u;
+    const uint32_t heads_total = (uint32_t)__builtin_amdgcn_readlane((int)heads_incl, 63);
+    if (lane == 63) set_bytes[wave] = (DC_BLOCK_BYTES * whole_total + heads_total + 15u) & ~15u;
     __syncthreads();
     const uint32_t hdr = header_bytes(S);
     const uint32_t n_sets = S / set_width(S);
     uint32_t region = hdr; // first byte of this wave's area
     for (uint32_t w = 0; w < wave; w++) region += set_bytes[w];
     if (lane == 0 && wave < n_sets) reinterpret_cast<uint32_t *>(out + 128 + 2 * S)[wave] = region;
-    const uint32_t tail_at = region + DC_BLOCK_BYTES * whole_total + 4 * (tails_incl - tw);
+    const uint32_t head_at = region + DC_BLOCK_BYTES * whole_total + (heads_incl - hb);
     if (lane == 63 && wave < n_sets) // padding of the area
-        for (uint32_t p = region + DC_BLOCK_BYTES * whole_total + 4 * tails_total; p < region + set_bytes[wave]; p += 4)
-            *reinterpret_cast<uint32_t *>(out + p) = 0;
+        for (uint32_t p = region + DC_BLOCK_BYTES * whole_total + heads_total; p < region + set_bytes[wave]; p++) out[p] = 0;
     for (uint32_t i = 128 + 2 * S + 4 * n_sets + t; i < hdr; i += THREADS) out[i] = 0;
 
     // ---- canonical codes: numbered in order of (length, byte value).  A wave looks at 64 consecutive
@@ -354,7 +354,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     const uint32_t rounds = (groups + S - 1) / S;
     const uint32_t my_groups = t < groups ? (groups - t + S - 1) / S : 0;
     const uint32_t ring_lane = lds_address(ring + wave * (16 * 64) + lane);
-    uint32_t taken = 0, used = 0;
+    uint32_t taken = 0, used = 8 * pad; // positions count from where block 0 would start
     uint32_t next_block = region / DC_BLOCK_BYTES;
     const uint64_t set_lanes = S < 64 ? (1ull << S) - 1 : ~0ull;
 
@@ -369,7 +369,9 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
         return v;
     };
 
-    Coder c = {0, 0, 0, 0, 0, 0};
+    // the coder starts behind the `pad` bytes that block 0 lacks (zeros in the ring, never stored)
+    Coder c = {0, 8 * (pad & 3u), pad >> 2, 0, 0, 0};
+    for (uint32_t i = 0; i < (pad >> 2); i++) *(lds_u32 *)(uintptr_t)(ring_lane + (i << 8)) = 0;
     if (my_groups) c.bytes = half_group(0, c.n);
     // codes the next half group into the ring: at most 88 bits on top of fewer than 32, so at most
     // three words
@@ -430,7 +432,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
         // block `taken` onwards are still in the ring, 16 words in all), so that the loop below, where
         // lanes diverge, rarely has anything left to do.
         if (c.next_half < 2 * my_groups && c.words + 3 <= 4 * taken + 16) code_half();
-        for (int pass = h == 0 ? 3 : 1; pass > 0; pass--) {
+        for (int pass = h == 0 ? 4 : 1; pass > 0; pass--) {
             const bool want = taken < nb && kBlockBits * taken < used + DC_LOOKAHEAD_BITS;
             if (want) {
                 // code on until block `taken` is complete (or the stream ends, then pad with zeros)
@@ -445,20 +447,18 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
                     }
                 }
             }
-            const bool last = taken + 1 == nb; // the last block goes to the tails, cut to its words
-            const uint64_t m = __ballot(want && !last) & set_lanes;
+            const bool head = taken == 0; // block 0 goes to the heads, without the bytes it lacks
+            const uint64_t m = __ballot(want && !head) & set_lanes;
             if (want) {
                 const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
                 u32x4 blk;
 #pragma unroll
                 for (int i = 0; i < 4; i++) blk[i] = lds_load32(ring_lane + (((4 * taken + i) & 15u) << 8));
-                if (!last) {
+                if (!head) {
                     *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
                 } else {
-                    uint32_t *tail = reinterpret_cast<uint32_t *>(out + tail_at);
-#pragma unroll
-                    for (int i = 0; i < 4; i++)
-                        if ((uint32_t)i < tw) tail[i] = blk[i];
+                    for (uint32_t i = pad; i < DC_BLOCK_BYTES; i++)
+                        out[head_at + i - pad] = (uint8_t)((i < 8 ? (i < 4 ? blk[0] : blk[1]) : (i < 12 ? blk[2] : blk[3])) >> (8 * (i & 3u)));
                 }
                 taken++;
             }

@@ -185,12 +185,12 @@ void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &c
     }
 }
 
-// A sub-stream of `bits` bits: blocks in all, and 32-bit words of the last block that hold bits.
-inline uint32_t words_of(uint64_t bits) { return (uint32_t)((bits + 31) / 32); }
-inline uint32_t blocks_of(uint64_t bits) { return (words_of(bits) + 3) / 4; }
-inline uint32_t tail_words_of(uint64_t bits) { return bits ? words_of(bits) - 4 * (blocks_of(bits) - 1) : 0; }
+// A sub-stream of `bits` bits is cut into blocks from its end: blocks in all, and bytes of the short first block.
+inline uint32_t bytes_of(uint64_t bits) { return (uint32_t)((bits + 7) / 8); }
+inline uint32_t blocks_of(uint64_t bits) { return (bytes_of(bits) + kBlock - 1) / kBlock; }
+inline uint32_t head_bytes_of(uint64_t bits) { return bits ? bytes_of(bits) - kBlock * (blocks_of(bits) - 1) : 0; }
 
-// Header, then per stream set the whole blocks, the cut-down last blocks and padding to 16.
+// Header, then per stream set the whole blocks, the short first blocks and padding to 16.
 uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
 {
     const uint32_t W = set_width(S);
@@ -198,16 +198,16 @@ uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
     for (uint32_t s0 = 0; s0 < S; s0 += W) {
         uint64_t area = 0;
         for (uint32_t j = s0; j < s0 + W; j++)
-            if (bits[j]) area += (uint64_t)(blocks_of(bits[j]) - 1) * kBlock + 4ull * tail_words_of(bits[j]);
+            if (bits[j]) area += (uint64_t)(blocks_of(bits[j]) - 1) * kBlock + head_bytes_of(bits[j]);
         pos += align_up(area, 16);
     }
     return (uint32_t)pos;
 }
 
 // Writes one Huffman payload; `out` has comp_bytes bytes.  Every sub-stream is first coded on its
-// own (whole blocks, zero padded) while the bits it has used before each step are noted; then, stream
-// set by stream set, the blocks but the last of each stream are placed in the order of the placement
-// rule of the format and the last blocks follow, cut to the words that hold bits.
+// own (whole blocks; the first one starts with the bytes that the format leaves out) while its position
+// before each step is noted; then, stream set by stream set, the blocks but the first of each stream are
+// placed in the order of the placement rule of the format and the short first blocks follow.
 void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb,
                         const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
 {
@@ -222,8 +222,8 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
     for (uint32_t j = 0; j < S; j++) {
         nb[j] = blocks_of(bits[j]);
         first_block[j + 1] = first_block[j] + nb[j];
-        const uint32_t tw = tail_words_of(bits[j]);
-        const uint16_t n16 = (uint16_t)(nb[j] | (tw ? (tw - 1) << 14 : 0));
+        const uint32_t hb = head_bytes_of(bits[j]);
+        const uint16_t n16 = (uint16_t)(nb[j] | (hb ? (hb - 1) << 12 : 0));
         std::memcpy(out + 128 + 2 * j, &n16, 2);
     }
     std::vector<uint8_t> coded((size_t)first_block[S] * kBlock + 8, 0);
@@ -232,9 +232,12 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
     for (uint32_t j = 0; j < S; j++) {
         uint32_t *w = reinterpret_cast<uint32_t *>(coded.data() + (size_t)first_block[j] * kBlock);
         uint32_t *u = &used[(size_t)j * (steps + 1)];
+        // positions count from the start of block 0, whose first `pad` bytes do not exist
+        const uint32_t pad = nb[j] ? kBlock - head_bytes_of(bits[j]) : 0;
+        w += pad / 4;
         uint64_t acc = 0;
-        int fill = 0;
-        uint32_t total = 0, h = 0;
+        int fill = 8 * (pad % 4);
+        uint32_t total = 8 * pad, h = 0;
         for (uint32_t g = j; g < groups; g += S) {
             const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16), mid = std::min(hi, lo + 8);
             u[h++] = total;
@@ -262,11 +265,11 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
         std::memcpy(out + 128 + 2 * S + 4 * w, &pos, 4);
         std::fill(f.begin(), f.end(), 0);
         for (uint32_t h = 0; h < steps; h++) {
-            for (int t = (h == 0 ? 3 : 1); t > 0; t--) {
+            for (int t = (h == 0 ? 4 : 1); t > 0; t--) {
                 for (uint32_t i = 0; i < W; i++) {
                     const uint32_t j = s0 + i;
                     if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < (uint64_t)used[(size_t)j * (steps + 1) + h] + DC_LOOKAHEAD_BITS) {
-                        if (f[i] + 1 < nb[j]) { // the last block goes to the tails
+                        if (f[i] > 0) { // block 0 goes to the heads
                             std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
                             pos += kBlock;
                         }
@@ -277,8 +280,8 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
         }
         for (uint32_t j = s0; j < s0 + W; j++) {
             if (nb[j] == 0) continue;
-            const uint32_t n = 4 * tail_words_of(bits[j]);
-            std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + nb[j] - 1) * kBlock, n);
+            const uint32_t n = head_bytes_of(bits[j]);
+            std::memcpy(out + pos, coded.data() + (size_t)first_block[j] * kBlock + (kBlock - n), n);
             pos += n;
         }
         pos = (uint32_t)align_up(pos, 16);
@@ -291,7 +294,7 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.2 (gfx950; canonical Huffman L11, block-interleaved sub-streams, last blocks cut to words)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.2 (gfx950; canonical Huffman L11, block-interleaved sub-streams, short first blocks)"; }
 
 extern "C" const char *dc_strerror(int code)
 {
@@ -568,46 +571,46 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
         uint32_t off;
         std::memcpy(&off, p + 128 + 2 * S + 4 * w, 4);
         if (off != region) return false;
-        std::vector<uint32_t> nb(W), tw(W), tail_at(W), f(W, 0);
+        std::vector<uint32_t> nb(W), hb(W), head_at(W), f(W, 0);
         std::vector<uint64_t> bit(W, 0), have(W, 0);
         std::vector<std::vector<uint32_t>> where(W); // payload offset of each block taken
-        uint64_t whole = 0, tail_words = 0;
+        uint64_t whole = 0, head_bytes = 0;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
             std::memcpy(&n16, p + 128 + 2 * (w * W + i), 2);
-            nb[i] = n16 & 0x3FFFu;
-            tw[i] = nb[i] ? (n16 >> 14) + 1u : 0;
+            nb[i] = n16 & 0xFFFu;
+            hb[i] = nb[i] ? (n16 >> 12) + 1u : 0;
             if (nb[i] == 0 && n16 != 0) return false;
             whole += nb[i] ? nb[i] - 1 : 0;
-            tail_words += tw[i];
+            head_bytes += hb[i];
+            bit[i] = nb[i] ? 8 * (kBlock - hb[i]) : 0; // the position starts behind the bytes block 0 lacks
         }
-        const uint64_t area = align_up(whole * kBlock + 4 * tail_words, 16);
+        const uint64_t area = align_up(whole * kBlock + head_bytes, 16);
         if (area > comp - region) return false;
         uint32_t pos = region;
         {
             uint32_t at = region + (uint32_t)(whole * kBlock);
             for (uint32_t i = 0; i < W; i++) {
-                tail_at[i] = at;
-                at += 4 * tw[i];
+                head_at[i] = at;
+                at += hb[i];
             }
             for (; at < region + area; at++)
                 if (p[at]) return false; // padding of the area
         }
-        const uint32_t tails_begin = region + (uint32_t)(whole * kBlock);
+        const uint32_t heads_begin = region + (uint32_t)(whole * kBlock);
         region += (uint32_t)area;
         for (uint32_t h = 0; h < steps; h++) {
-            for (int t = (h == 0 ? 3 : 1); t > 0; t--)
+            for (int t = (h == 0 ? 4 : 1); t > 0; t--)
                 for (uint32_t i = 0; i < W; i++)
                     if (f[i] < nb[i] && (uint64_t)kBlockBits * f[i] < bit[i] + DC_LOOKAHEAD_BITS) {
-                        if (f[i] + 1 < nb[i]) {
-                            if (pos + kBlock > tails_begin) return false;
+                        if (f[i] > 0) {
+                            if (pos + kBlock > heads_begin) return false;
                             where[i].push_back(pos);
                             pos += kBlock;
-                            have[i] += kBlockBits;
                         } else {
-                            where[i].push_back(tail_at[i]);
-                            have[i] += 32 * tw[i];
+                            where[i].push_back(head_at[i] - (kBlock - hb[i])); // where block 0 would start
                         }
+                        have[i] += kBlockBits;
                         f[i]++;
                     }
             for (uint32_t i = 0; i < W; i++) {
@@ -631,8 +634,8 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
             }
         }
         for (uint32_t i = 0; i < W; i++)
-            if (f[i] != nb[i] || blocks_of(bit[i]) != nb[i] || tail_words_of(bit[i]) != tw[i]) return false;
-        if (pos != tails_begin) return false;
+            if (f[i] != nb[i] || (bit[i] + 7) / 8 != (uint64_t)kBlock * nb[i]) return false;
+        if (pos != heads_begin) return false;
     }
     return region == comp;
 }

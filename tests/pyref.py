@@ -96,14 +96,16 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
     """Decode one Huffman payload by walking bits, from the written format alone.
 
     header: 128 bytes of 4-bit code lengths (value v in nibble v&1 of byte v>>1), then S little-endian
-    u16 (low 14 bits: blocks of the stream; top 2 bits: words of its last block that hold bits, less
+    u16 (low 12 bits: blocks of the stream; top 4 bits: bytes of its first block that exist, less
     one), then one u32 area offset per stream set (W = min(S, 64) streams a set), padded to 16; stream
     bit i = bit (i%8) of stream byte i/8; codes canonical by (length, value), written most significant
-    bit first; bytes of 16-byte group g go to stream g % S.  An area holds the 16-byte blocks of its
-    streams, all but the last of each, in request order, then the last blocks cut to their used words
-    in stream order: before every half group (8 symbols) of all streams, each stream in turn that has
-    blocks left and fewer than 320 placed bits beyond its position takes its next block (the next
-    of the area, or its own cut-down last block); the first such step runs three times.
+    bit first; bytes of 16-byte group g go to stream g % S.  A stream is a whole number of bytes, cut
+    into 16-byte blocks from its end, so that only its first block is short (the bytes missing at its
+    front do not exist; positions count from where that block would start).  An area holds the
+    16-byte blocks of its streams, all but the first of each, in request order, then the short first
+    blocks in stream order: before every half group (8 symbols) of all streams, each stream in turn that
+    has blocks left and fewer than 320 placed bits beyond its position takes its next block (its own
+    short first block, or the next of the area); the first such step runs four times.
     """
     lens = [(payload[v >> 1] >> (4 * (v & 1))) & 15 for v in range(256)]
     book: Dict[tuple, int] = {}
@@ -118,40 +120,42 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
                 prev = l
     W = min(S, 64)
     field = [int.from_bytes(payload[128 + 2 * j:130 + 2 * j], "little") for j in range(S)]
-    nb = [x & 0x3FFF for x in field]
-    last_words = [(x >> 14) + 1 if x & 0x3FFF else 0 for x in field]
+    nb = [x & 0xFFF for x in field]
+    first_bytes = [(x >> 12) + 1 if x & 0xFFF else 0 for x in field]
     out = bytearray(raw_bytes)
     groups = (raw_bytes + 15) // 16
     rounds = (groups + S - 1) // S
     for w in range(S // W):
         o = 128 + 2 * S + 4 * w
         pos = int.from_bytes(payload[o:o + 4], "little")
-        # the cut-down last blocks start where the whole blocks of the set end
+        # the short first blocks start where the whole blocks of the set end
         whole = sum(nb[w * W + i] - 1 for i in range(W) if nb[w * W + i])
-        last_at = []
+        first_at = []
         at = pos + 16 * whole
         for i in range(W):
-            last_at.append(at)
-            at += 4 * last_words[w * W + i]
+            first_at.append(at)
+            at += first_bytes[w * W + i]
         assert at <= len(payload), "area runs past the payload"
         data = [bytearray() for _ in range(W)]  # blocks of each stream, in order
-        bit = [0] * W
+        # the position starts behind the bytes that the first block lacks
+        bit = [8 * (16 - first_bytes[w * W + i]) if nb[w * W + i] else 0 for i in range(W)]
 
         def step():
             nonlocal pos
             for i in range(W):
                 j = w * W + i
                 if len(data[i]) < 16 * nb[j] and 8 * len(data[i]) - bit[i] < 320:
-                    if len(data[i]) < 16 * (nb[j] - 1):
+                    if len(data[i]) > 0:
                         data[i] += payload[pos:pos + 16]
                         pos += 16
                     else:
-                        n = 4 * last_words[j]
-                        data[i] += payload[last_at[i]:last_at[i] + n] + bytes(16 - n)
+                        n = first_bytes[j]
+                        data[i] += bytes(16 - n) + payload[first_at[i]:first_at[i] + n]
 
         for h in range(2 * rounds):
             step()
             if h == 0:
+                step()
                 step()
                 step()
             for i in range(W):
@@ -173,5 +177,5 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
                         assert l < 15, "no code matched"
         for i in range(W):
             assert len(data[i]) == 16 * nb[w * W + i], "blocks left unplaced"
-        assert pos == last_at[0], "whole blocks left over in the area"
+        assert pos == first_at[0], "whole blocks left over in the area"
     return bytes(out)

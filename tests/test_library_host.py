@@ -197,7 +197,7 @@ def test_validate_catches_corruption():
     expect_bad(b, table, k)
     b = blob.copy(); b[o + 128 + 2 * 5] -= 1  # ... one too few: the stream runs out of bits
     expect_bad(b, table, k)
-    b = blob.copy(); b[o + 128 + 2 * 5 + 1] ^= 0x40  # words of the last block of stream 5 changed
+    b = blob.copy(); b[o + 128 + 2 * 5 + 1] ^= 0x10  # bytes of the last block of stream 5 changed
     expect_bad(b, table, k)
     b = blob.copy(); b[o + 128 + 2 * S:o + 128 + 2 * S + 4] = np.frombuffer(np.uint32(1 << 24).tobytes(), np.uint8)
     expect_bad(b, table, k)  # region offset outside the payload
@@ -206,7 +206,7 @@ def test_validate_catches_corruption():
     b = blob.copy(); b[o + 128 + 2 * S + 5] = 1  # header padding not zero
     expect_bad(b, table, k)
     field = np.frombuffer(blob[o + 128:o + 128 + 2 * S].tobytes(), dtype="<u2").astype(int)
-    end = o + 144 + 2 * S + 16 * int(((field & 0x3FFF) - 1).sum()) + 4 * int(((field >> 14) + 1).sum())  # header is 144 + 2 S bytes at S = 32
+    end = o + 144 + 2 * S + 16 * int(((field & 0xFFF) - 1).sum()) + int(((field >> 12) + 1).sum())  # header is 144 + 2 S bytes at S = 32
     if end % 16:  # the area of the one stream set is padded with zeros
         b = blob.copy(); b[end] = 1
         expect_bad(b, table, k)

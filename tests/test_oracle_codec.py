@@ -190,7 +190,8 @@ def test_round_trip_and_independent_decoder_ragged(raw, S):
 def test_lopsided_streams_round_trip_and_lookahead(raw, S):
     """Sub-streams that use the code very unevenly (some all long codes, most all short): round trip
     through the oracle and the independent decoder, and the placement rule keeps every stream between
-    320 and 448 placed bits ahead of its position (or has placed all of its blocks) after every step."""
+    320 and 448 placed bits ahead of its position (or has placed all of its blocks) after every step.
+    Positions count from where the short first block of a stream would start."""
     from tests.helpers import lopsided_bytes
     data = lopsided_bytes(raw, S, raw + S)
     payload = oc.encode_chunk(data, S)
@@ -198,13 +199,14 @@ def test_lopsided_streams_round_trip_and_lookahead(raw, S):
     assert pyref.parse_and_decode(payload.tobytes(), raw, S) == data.tobytes()
     ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
     assert ln.max() >= 9 and ln[0] <= 2
-    nb = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int) & 0x3FFF
+    field = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
+    nb = field & 0xFFF
     groups = (raw + 15) // 16
     rounds = (groups + S - 1) // S
     for j in range(min(S, 3)):  # the extreme streams
-        f, used = 0, 0
+        f, used = 0, 8 * (15 - (field[j] >> 12))
         for h in range(2 * rounds):
-            for _ in range(3 if h == 0 else 1):
+            for _ in range(4 if h == 0 else 1):
                 if f < nb[j] and 128 * f - used < 320:
                     f += 1
             assert f == nb[j] or 320 <= 128 * f - used < 448, (j, h)
@@ -248,71 +250,76 @@ def test_header_layout_and_payload_size_closed_form(raw, S):
     for v in range(256):
         assert (payload[v >> 1] >> (4 * (v & 1))) & 15 == ln[v]
     field = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
-    nb, last_words = field & 0x3FFF, (field >> 14) + 1
+    nb, last_bytes = field & 0xFFF, (field >> 12) + 1
     W = min(S, 64)
     set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
-    for j in range(S):  # a stream is its bits rounded up to 32-bit words: whole blocks, then 1..4 words
-        words = (stream_bits(data, ln, S, j) + 31) // 32
-        assert words > 0 and nb[j] == (words + 3) // 4 and last_words[j] == words - 4 * (nb[j] - 1)
+    for j in range(S):  # a stream is its bits rounded up to bytes: whole blocks, then 1..16 bytes
+        size = (stream_bits(data, ln, S, j) + 7) // 8
+        assert size > 0 and nb[j] == (size + 15) // 16 and last_bytes[j] == size - 16 * (nb[j] - 1)
     pos = header_bytes(S)
     assert not payload[128 + 2 * S + 4 * (S // W):pos].any()
     for w in range(S // W):  # areas back to back after the header, each padded to 16 bytes
         assert set_off[w] == pos
-        end = pos + 16 * int((nb[w * W:(w + 1) * W] - 1).sum()) + 4 * int(last_words[w * W:(w + 1) * W].sum())
+        end = pos + 16 * int((nb[w * W:(w + 1) * W] - 1).sum()) + int(last_bytes[w * W:(w + 1) * W].sum())
         assert not payload[end:(end + 15) // 16 * 16].any()
         pos = (end + 15) // 16 * 16
     assert payload.size == pos
 
 
+def stream_bytes_independently(data, ln, code, S, j):
+    """Sub-stream j written out on its own: codes most significant bit first, bits packed LSB first."""
+    raw = data.size
+    bits = []
+    for g in range(j, (raw + 15) // 16, S):
+        for p in range(16 * g, min(16 * g + 16, raw)):
+            v = int(data[p])
+            bits += [(code[v] >> k) & 1 for k in range(ln[v] - 1, -1, -1)]
+    bits += [0] * (-len(bits) % 8)
+    return np.packbits(np.array(bits, dtype=np.uint8), bitorder="little").tobytes()
+
+
 @pytest.mark.parametrize("raw,S", [(65536, 256), (16384, 32)])
-def test_last_blocks_are_stored_as_their_used_words_in_stream_order(raw, S):
-    """After the whole blocks of a set come the last blocks of its streams, cut to the words that
-    hold bits: compare with every stream written out independently."""
+def test_short_first_blocks_follow_the_whole_blocks_in_stream_order(raw, S):
+    """A stream is cut into 16-byte blocks from its end; after the whole blocks of a set come the
+    short first blocks of its streams: compare with every stream written out independently."""
     data = gaussian_bytes(raw, 25.0, 11)
     payload = oc.encode_chunk(data, S)
     ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
     code = oc.canonical_codes(ln.astype(np.uint8)).astype(int)
     W = min(S, 64)
     set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
+    field = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
     for w in range(S // W):
-        streams = []
-        for j in range(w * W, (w + 1) * W):
-            bits = []
-            for g in range(j, raw // 16, S):
-                for p in range(16 * g, 16 * g + 16):
-                    v = int(data[p])
-                    bits += [(code[v] >> k) & 1 for k in range(ln[v] - 1, -1, -1)]
-            bits += [0] * (-len(bits) % 32)
-            streams.append(np.packbits(np.array(bits, dtype=np.uint8), bitorder="little").tobytes())
+        streams = [stream_bytes_independently(data, ln, code, S, j) for j in range(w * W, (w + 1) * W)]
         pos = set_off[w] + sum((len(b) - 1) // 16 * 16 for b in streams)
-        for b in streams:
-            cut = (len(b) - 1) // 16 * 16  # bytes of the stream in whole blocks before its last block
-            assert payload[pos:pos + len(b) - cut].tobytes() == b[cut:]
-            pos += len(b) - cut
+        for i, b in enumerate(streams):
+            first = (len(b) - 1) % 16 + 1  # bytes of the short first block
+            assert field[w * W + i] == ((len(b) + 15) // 16 | (first - 1) << 12)
+            assert payload[pos:pos + first].tobytes() == b[:first]
+            pos += first
 
 
 def test_first_blocks_of_a_region_are_the_streams_in_turn():
-    """Step 0 runs three times: the region opens with block 0 of every stream in stream order, then
-    block 1 of every stream, then block 2 (all streams here are longer than three blocks)."""
+    """Step 0 runs four times.  The first block a stream takes is its short one, so the region opens
+    with block 1 of every stream in stream order, then block 2; block 3 follows only for the streams
+    whose first block lacks more than 8 bytes (3 blocks are then fewer than 320 bits ahead)."""
     raw, S = 16384, 32
     data = gaussian_bytes(raw, 20.0, 5)
     payload = oc.encode_chunk(data, S)
     ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
     code = oc.canonical_codes(ln.astype(np.uint8)).astype(int)
+    streams = [stream_bytes_independently(data, ln, code, S, j) for j in range(S)]
+    firsts = [(len(b) - 1) % 16 + 1 for b in streams]
+    assert min(len(b) for b in streams) > 64
     pos = header_bytes(S)
-    for b in range(3):
+    for blk in (1, 2, 3):
         for j in range(S):
-            # bits of block b of stream j, written out independently
-            bits = []
-            for g in range(j, raw // 16, S):
-                for p in range(16 * g, 16 * g + 16):
-                    v = int(data[p])
-                    bits += [(code[v] >> k) & 1 for k in range(ln[v] - 1, -1, -1)]
-                if len(bits) >= 128 * (b + 1):
-                    break
-            want = np.packbits(np.array(bits[128 * b:128 * (b + 1)], dtype=np.uint8), bitorder="little")
-            assert payload[pos:pos + 16].tobytes() == want.tobytes(), (b, j)
+            if blk == 3 and not 128 * 3 - 8 * (16 - firsts[j]) < 320:
+                continue
+            lo = firsts[j] + 16 * (blk - 1)
+            assert payload[pos:pos + 16].tobytes() == streams[j][lo:lo + 16], (blk, j)
             pos += 16
+    assert any(f < 8 for f in firsts) and any(f >= 8 for f in firsts)
 
 
 def test_single_value_chunk_closed_form():
@@ -320,7 +327,7 @@ def test_single_value_chunk_closed_form():
     data = np.full(raw, 0xE7, dtype=np.uint8)
     payload = oc.encode_chunk(data, S)
     per_stream = raw // S  # one bit a symbol
-    want = header_bytes(S) + (S * ((per_stream + 31) // 32 * 4) + 15) // 16 * 16
+    want = header_bytes(S) + (S * ((per_stream + 7) // 8) + 15) // 16 * 16
     assert payload.size == want
     assert not payload[128 + 2 * S + 4:].any()  # code 0 everywhere
     assert (oc.decode_chunk(payload, raw, S) == data).all()
