@@ -315,9 +315,8 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     uint32_t region = hdr; // first byte of this wave's area
     for (uint32_t w = 0; w < wave; w++) region += set_bytes[w];
     if (lane == 0 && wave < n_sets) reinterpret_cast<uint32_t *>(out + 128 + 2 * S)[wave] = region;
-    const uint32_t head_at = region + DC_BLOCK_BYTES * whole_total + (heads_incl - hb);
-    if (lane == 63 && wave < n_sets) // padding of the area
-        for (uint32_t p = region + DC_BLOCK_BYTES * whole_total + heads_total; p < region + set_bytes[wave]; p++) out[p] = 0;
+    const uint32_t heads_at = region + DC_BLOCK_BYTES * whole_total;                  // the heads of the set, padded to 16 ...
+    const uint32_t heads_padded = set_bytes[wave] - DC_BLOCK_BYTES * whole_total; // ... take this many bytes
     for (uint32_t i = 128 + 2 * S + 4 * n_sets + t; i < hdr; i += THREADS) out[i] = 0;
 
     // ---- canonical codes: numbered in order of (length, byte value).  A wave looks at 64 consecutive
@@ -355,6 +354,7 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
     const uint32_t my_groups = t < groups ? (groups - t + S - 1) / S : 0;
     const uint32_t ring_lane = lds_address(ring + wave * (16 * 64) + lane);
     uint32_t taken = 0, used = 8 * pad; // positions count from where block 0 would start
+    u32x4 head_blk = {0, 0, 0, 0};
     uint32_t next_block = region / DC_BLOCK_BYTES;
     const uint64_t set_lanes = S < 64 ? (1ull << S) - 1 : ~0ull;
 
@@ -454,12 +454,8 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
                 u32x4 blk;
 #pragma unroll
                 for (int i = 0; i < 4; i++) blk[i] = lds_load32(ring_lane + (((4 * taken + i) & 15u) << 8));
-                if (!head) {
-                    *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
-                } else {
-                    for (uint32_t i = pad; i < DC_BLOCK_BYTES; i++)
-                        out[head_at + i - pad] = (uint8_t)((i < 8 ? (i < 4 ? blk[0] : blk[1]) : (i < 12 ? blk[2] : blk[3])) >> (8 * (i & 3u)));
-                }
+                if (!head) *reinterpret_cast<u32x4 *>(out + (size_t)(next_block + rank) * DC_BLOCK_BYTES) = blk;
+                else head_blk = blk; // written with the other heads of the set, below
                 taken++;
             }
             next_block += (uint32_t)__popcll(m);
@@ -467,6 +463,19 @@ template <int THREADS> __global__ __launch_bounds__(THREADS) void dc_emit_kernel
         // the decoder's position after half group h
         used += bits_of(step_bytes, step_n);
     }
+
+    // ---- the heads of the set: put together in the wave's ring, which is free now (the lanes of a wave
+    // leave the loop together), then written with whole 16-byte stores, the padding of the area included
+    uint8_t *stage = reinterpret_cast<uint8_t *>(ring + wave * (16 * 64));
+    if (lane == 0)
+        for (uint32_t p = heads_total; p < heads_padded; p++) stage[p] = 0;
+    for (uint32_t i = pad; i < DC_BLOCK_BYTES && nb; i++)
+        stage[heads_incl - hb + i - pad] = (uint8_t)((i < 8 ? (i < 4 ? head_blk[0] : head_blk[1]) : (i < 12 ? head_blk[2] : head_blk[3])) >> (8 * (i & 3u)));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (uint32_t o = DC_BLOCK_BYTES * lane; o < heads_padded; o += DC_BLOCK_BYTES * 64)
+        *reinterpret_cast<u32x4 *>(out + heads_at + o) = *reinterpret_cast<const u32x4 *>(stage + o);
 }
 
 template <int THREADS> void launch_emit(const EncArgs &a, hipStream_t stream)
