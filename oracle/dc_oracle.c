@@ -252,7 +252,7 @@ static uint32_t header_bytes(uint32_t S)
 }
 
 /* Upper bound of a Huffman payload: header + 11 bits a symbol + one partial block a stream
- * (more than the tails and the padding of the sets can take). */
+ * (more than the padding of the sets can take). */
 uint64_t orc_huff_bound(uint32_t raw_bytes, uint32_t S)
 {
     return round_up(header_bytes(S) + ((uint64_t)raw_bytes * 11 + 7) / 8 + ORC_BLOCK * (uint64_t)S, 16);
@@ -348,8 +348,8 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         memcpy(out + 128 + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
     }
 
-    /* every stream written out on its own, zero padded to whole blocks; used[j][k] = bits of
-     * stream j taken by its first k symbols */
+    /* every stream written out on its own from where its block 0 would start; used[j][k] = position of
+     * stream j after its first k symbols */
     uint8_t **st = calloc(S, sizeof(uint8_t *));
     uint64_t **used = calloc(S, sizeof(uint64_t *));
     for (uint32_t j = 0; j < S; j++) {

@@ -525,7 +525,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     Stream st;
     if (huff) {
         rg.payload8 = payload8;
-        // a tail may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
+        // a 20-byte load may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
         const uint64_t room = a.blob_bytes - ent.off - 20;
         rg.max_off = room < 0xFFFFFFE0ull ? (uint32_t)room : 0xFFFFFFE0u;
         rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);

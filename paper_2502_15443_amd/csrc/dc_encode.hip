@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     __shared__ uint32_t bought_leaves[kL];
     __shared__ uint8_t len_of[256];
     __shared__ uint32_t sbits[256];
-    __shared__ uint32_t area_bytes[4]; // per stream set: whole blocks and cut-down last blocks
+    __shared__ uint32_t area_bytes[4]; // per stream set: whole blocks and short first blocks
     uint32_t(*level)[512] = reinterpret_cast<uint32_t(*)[512]>(arena);              // weights of the items of the previous / current level
     uint32_t *pack = arena + 1024;                                                    // [256] packages made of the previous level
     uint16_t(*leaves_before)[514] = reinterpret_cast<uint16_t(*)[514]>(arena + 1280); // [kL][514]

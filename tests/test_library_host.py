@@ -197,7 +197,7 @@ def test_validate_catches_corruption():
     expect_bad(b, table, k)
     b = blob.copy(); b[o + 128 + 2 * 5] -= 1  # ... one too few: the stream runs out of bits
     expect_bad(b, table, k)
-    b = blob.copy(); b[o + 128 + 2 * 5 + 1] ^= 0x10  # bytes of the last block of stream 5 changed
+    b = blob.copy(); b[o + 128 + 2 * 5 + 1] ^= 0x10  # bytes of the first block of stream 5 changed
     expect_bad(b, table, k)
     b = blob.copy(); b[o + 128 + 2 * S:o + 128 + 2 * S + 4] = np.frombuffer(np.uint32(1 << 24).tobytes(), np.uint8)
     expect_bad(b, table, k)  # region offset outside the payload

@@ -250,17 +250,17 @@ def test_header_layout_and_payload_size_closed_form(raw, S):
     for v in range(256):
         assert (payload[v >> 1] >> (4 * (v & 1))) & 15 == ln[v]
     field = np.frombuffer(payload[128:128 + 2 * S].tobytes(), dtype="<u2").astype(int)
-    nb, last_bytes = field & 0xFFF, (field >> 12) + 1
+    nb, first_bytes = field & 0xFFF, (field >> 12) + 1
     W = min(S, 64)
     set_off = np.frombuffer(payload[128 + 2 * S:128 + 2 * S + 4 * (S // W)].tobytes(), dtype="<u4").astype(int)
-    for j in range(S):  # a stream is its bits rounded up to bytes: whole blocks, then 1..16 bytes
+    for j in range(S):  # a stream is its bits rounded up to bytes: a first block of 1..16 bytes, then whole blocks
         size = (stream_bits(data, ln, S, j) + 7) // 8
-        assert size > 0 and nb[j] == (size + 15) // 16 and last_bytes[j] == size - 16 * (nb[j] - 1)
+        assert size > 0 and nb[j] == (size + 15) // 16 and first_bytes[j] == size - 16 * (nb[j] - 1)
     pos = header_bytes(S)
     assert not payload[128 + 2 * S + 4 * (S // W):pos].any()
     for w in range(S // W):  # areas back to back after the header, each padded to 16 bytes
         assert set_off[w] == pos
-        end = pos + 16 * int((nb[w * W:(w + 1) * W] - 1).sum()) + int(last_bytes[w * W:(w + 1) * W].sum())
+        end = pos + 16 * int((nb[w * W:(w + 1) * W] - 1).sum()) + int(first_bytes[w * W:(w + 1) * W].sum())
         assert not payload[end:(end + 15) // 16 * 16].any()
         pos = (end + 15) // 16 * 16
     assert payload.size == pos
