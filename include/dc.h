@@ -220,7 +220,8 @@ int dc_compress_chunks(const int8_t *src_host, uint64_t raw_bytes, const dc_para
  * The same compression on the GPU (Section 3.1; Section 4.2 reports compression speed as well).
  * Device to device, asynchronous on hip_stream, three launches.  The blob and table are byte for
  * byte those of dc_compress_chunks for the same input and params.  Policies: DC_POLICY_ALL_HUFF,
- * DC_POLICY_AUTO, DC_POLICY_BLOCK_LAST (the others need a host-side selection: DC_E_ARG).
+ * DC_POLICY_AUTO, DC_POLICY_RAW_FRACTION, DC_POLICY_BLOCK_LAST (DC_POLICY_RAW_MASK names a mask in
+ * host memory: DC_E_ARG).
  *   src_dev         raw_bytes int8 values, 16-byte aligned
  *   blob_dev        out, 16-byte aligned, blob_cap bytes (dc_compress_bound gives a safe size)
  *   table_dev       out, table_cap >= number of chunks entries

@@ -27,6 +27,7 @@ struct EncArgs {
     uint32_t S;
     uint32_t policy;
     uint32_t block_chunks;
+    uint64_t n_raw; // DC_POLICY_RAW_FRACTION: chunks that stay raw
     // workspace
     uint8_t *lens;  // [n_chunks][256] code lengths
     uint32_t *bits; // [n_chunks][S] bits of every sub-stream
@@ -210,26 +211,83 @@ __global__ __launch_bounds__(256) void dc_codes_kernel(EncArgs a)
     }
 }
 
-// Size of chunk k in the blob and whether it stays raw.
-__device__ __forceinline__ uint32_t stored_size(const EncArgs &a, uint64_t k, bool &is_raw)
+// Gain of Huffman coding a chunk (raw size less Huffman payload size) as an unsigned key in the same order.
+__device__ __forceinline__ uint32_t gain_key(const EncArgs &a, uint64_t k)
 {
-    const uint32_t raw = chunk_len(a, k);
-    const uint32_t huff = a.comp[k];
-    is_raw = false;
-    if (a.policy == DC_POLICY_AUTO) is_raw = (int64_t)raw - (int64_t)huff <= 0;
-    else if (a.policy == DC_POLICY_BLOCK_LAST) is_raw = (k % a.block_chunks) != a.block_chunks - 1;
-    return is_raw ? (raw + 15u) & ~15u : huff;
+    return (uint32_t)((int64_t)chunk_len(a, k) - (int64_t)a.comp[k] + (int64_t)0x80000000ll);
 }
 
+// Which chunks stay raw.  DC_POLICY_RAW_FRACTION: the n_raw chunks of lowest gain, lower index first
+// among equal gains, i.e. the chunks with key < threshold and the first `equal_raw` chunks with
+// key == threshold.
+struct RawRule {
+    uint32_t threshold;
+    uint32_t equal_raw;
+};
+
+__device__ __forceinline__ bool stays_raw(const EncArgs &a, const RawRule &r, uint64_t k, uint32_t &equal_seen)
+{
+    if (a.policy == DC_POLICY_AUTO) return gain_key(a, k) <= 0x80000000u;
+    if (a.policy == DC_POLICY_BLOCK_LAST) return (k % a.block_chunks) != a.block_chunks - 1;
+    if (a.policy == DC_POLICY_RAW_FRACTION) {
+        const uint32_t key = gain_key(a, k);
+        if (key != r.threshold) return key < r.threshold;
+        return equal_seen++ < r.equal_raw;
+    }
+    return false;
+}
+
+// One workgroup; thread t looks after the chunks [t * per, (t + 1) * per).
 __global__ __launch_bounds__(256) void dc_layout_kernel(EncArgs a)
 {
     __shared__ uint64_t part[256];
+    __shared__ uint32_t digit_count[256];
+    __shared__ uint32_t equal_part[256];
+    __shared__ uint32_t sel_prefix, sel_rank;
     const uint32_t t = threadIdx.x;
     const uint64_t per = (a.n_chunks + 255) / 256;
-    const uint64_t k0 = t * per, k1 = k0 + per < a.n_chunks ? k0 + per : a.n_chunks;
+    const uint64_t k0 = t * per < a.n_chunks ? t * per : a.n_chunks, k1 = k0 + per < a.n_chunks ? k0 + per : a.n_chunks;
+
+    RawRule rule = {0, 0};
+    uint32_t equal_before = 0; // chunks before k0 whose key is the threshold
+    if (a.policy == DC_POLICY_RAW_FRACTION && a.n_raw > 0) {
+        // Radix select, most significant byte first: the key of rank n_raw - 1 in ascending order.
+        if (t == 0) {
+            sel_prefix = 0;
+            sel_rank = (uint32_t)(a.n_raw - 1);
+        }
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            digit_count[t] = 0;
+            __syncthreads();
+            const uint32_t prefix = sel_prefix;
+            for (uint64_t k = k0; k < k1; k++) {
+                const uint32_t key = gain_key(a, k);
+                if (shift == 24 || ((key ^ prefix) >> (shift + 8)) == 0) atomicAdd(&digit_count[(key >> shift) & 0xFFu], 1u);
+            }
+            __syncthreads();
+            if (t == 0) {
+                uint32_t rank = sel_rank, d = 0;
+                while (d < 255 && rank >= digit_count[d]) rank -= digit_count[d++]; // the rank lies among the counted keys
+                sel_prefix = prefix | (d << shift);
+                sel_rank = rank;
+            }
+            __syncthreads();
+        }
+        rule.threshold = sel_prefix;
+        rule.equal_raw = sel_rank + 1;
+        uint32_t mine = 0;
+        for (uint64_t k = k0; k < k1; k++) mine += gain_key(a, k) == rule.threshold;
+        equal_part[t] = mine;
+        __syncthreads();
+        for (uint32_t i = 0; i < t; i++) equal_before += equal_part[i];
+    }
+
     uint64_t sum = 0;
-    bool is_raw;
-    for (uint64_t k = k0; k < k1; k++) sum += stored_size(a, k, is_raw);
+    uint32_t equal_seen = equal_before;
+    for (uint64_t k = k0; k < k1; k++) {
+        const uint32_t raw = chunk_len(a, k);
+        sum += stays_raw(a, rule, k, equal_seen) ? (raw + 15u) & ~15u : a.comp[k];
+    }
     part[t] = sum;
     __syncthreads();
     if (t == 0) {
@@ -246,12 +304,15 @@ __global__ __launch_bounds__(256) void dc_layout_kernel(EncArgs a)
     }
     __syncthreads();
     uint64_t off = part[t];
+    equal_seen = equal_before;
     for (uint64_t k = k0; k < k1; k++) {
-        const uint32_t size = stored_size(a, k, is_raw);
+        const uint32_t raw = chunk_len(a, k);
+        const bool is_raw = stays_raw(a, rule, k, equal_seen);
+        const uint32_t size = is_raw ? (raw + 15u) & ~15u : a.comp[k];
         dc_chunk e;
         e.off = off;
         e.comp_bytes = size;
-        e.raw_bytes_flags = chunk_len(a, k) | (is_raw ? DC_CHUNK_RAW : 0u);
+        e.raw_bytes_flags = raw | (is_raw ? DC_CHUNK_RAW : 0u);
         a.table[k] = e;
         off += size;
     }
@@ -489,6 +550,7 @@ bool enc_params_ok(const dc_params *p)
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
     if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128 && p->n_streams != 256) return false;
     if (p->policy == DC_POLICY_BLOCK_LAST) return p->block_chunks != 0;
+    if (p->policy == DC_POLICY_RAW_FRACTION) return p->raw_fraction >= 0.0f && p->raw_fraction <= 1.0f;
     return p->policy == DC_POLICY_ALL_HUFF || p->policy == DC_POLICY_AUTO;
 }
 
@@ -527,6 +589,11 @@ extern "C" int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes,
     a.S = params->n_streams;
     a.policy = params->policy;
     a.block_chunks = params->block_chunks;
+    a.n_raw = 0;
+    if (params->policy == DC_POLICY_RAW_FRACTION) {
+        a.n_raw = (uint64_t)((double)params->raw_fraction * (double)nc + 0.5);
+        if (a.n_raw > nc) a.n_raw = nc;
+    }
     uint8_t *ws = static_cast<uint8_t *>(workspace_dev);
     a.lens = ws;
     a.bits = reinterpret_cast<uint32_t *>(ws + align256(nc * 256));

@@ -35,10 +35,10 @@ def dev_compress(data: np.ndarray, params, blob_cap=None):
     return blob_d[:cap].cpu().numpy(), table_d.cpu().numpy().view(dc.CHUNK_DTYPE), int(r[0]), int(r[1])
 
 
-def check_equal_to_oracle(data, C, S, policy=oc.ALL_HUFF, block=0):
-    p = dc.Params(C, S, policy, 0.0, block)
+def check_equal_to_oracle(data, C, S, policy=oc.ALL_HUFF, block=0, f=0.0):
+    p = dc.Params(C, S, policy, f, block)
     blob, table, used, status = dev_compress(data, p)
-    c = oc.compress(data, C, S, policy, block=block, threads=8)
+    c = oc.compress(data, C, S, policy, f, block=block, threads=8)
     assert status == 0 and used == c.blob.size
     assert np.array_equal(table, c.table)
     assert np.array_equal(blob[:used], c.blob)
@@ -96,7 +96,31 @@ def test_device_compress_reports_small_blob():
     c = oc.compress(data, 4096, 64)
     assert status == E_CAP_U64 and used == c.blob.size and np.array_equal(table, c.table)
     with pytest.raises(dc.DCError):
-        dev_compress(data, dc.Params(4096, 64, dc.POLICY_RAW_FRACTION, 0.5))
+        dev_compress(data, dc.Params(4096, 64, dc.POLICY_RAW_FRACTION, 1.5))
+    with pytest.raises(dc.DCError):
+        dev_compress(data, dc.Params(4096, 64, dc.POLICY_RAW_MASK))  # needs a host-side mask
+
+
+@pytest.mark.parametrize("f", [0.0, 0.1, 0.25, 0.5, 0.75, 1.0])
+def test_device_compress_raw_fraction_is_the_oracles_selection(f):
+    """The gain-ranked choice of raw chunks (lowest gain first, lower index first among equal gains) made
+    on the device: 300 chunks of mixed compressibility with many equal gains among them."""
+    print(f"case dev compress raw fraction f={f}", flush=True)
+    C, S = 4096, 64
+    r = np.random.default_rng(17)
+    parts = []
+    for k in range(300):
+        kind = k % 5
+        if kind == 0:
+            parts.append(np.zeros(C, np.uint8))                       # many chunks of exactly equal gain
+        elif kind == 1:
+            parts.append(r.integers(0, 256, C, dtype=np.uint8))      # negative gain
+        elif kind == 2:
+            parts.append(np.tile(np.array([1, 2, 3, 4], np.uint8), C // 4))  # equal gains again
+        else:
+            parts.append(weightlike_bytes(C, 1000 + k))
+    data = np.concatenate(parts + [weightlike_bytes(1234, 5)])
+    check_equal_to_oracle(data, C, S, oc.RAW_FRACTION, f=f)
 
 
 @pytest.mark.parametrize("S", [32, 256])
