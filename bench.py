@@ -90,6 +90,19 @@ def time_launches(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall / steps
 
 
+def time_each_launch(torch, fn, n, first):
+    """Median and minimum duration (ms) of n launches of fn(), each between its own pair of HIP events."""
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    torch.cuda.synchronize()
+    for i, (e0, e1) in enumerate(pairs):
+        e0.record()
+        fn(first + i)
+        e1.record()
+    torch.cuda.synchronize()
+    t = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
+    return t[len(t) // 2], t[0]
+
+
 def layer_streaming(torch, dc, synth, params, n_layers=8, reps=10):
     """The paper's runtime loop (Section 3.3, case (b): everything in GPU memory) on the Llama-7B-shaped
     layer: per-layer latency of batch-1 inference (seven matrix-vector products a layer) with the
@@ -330,6 +343,9 @@ def main() -> int:
         dc.decompress_chunks(blobs_d[b], blob.size, table_d, n_chunks, params, dsts[b], raw_bytes, stream)
 
     ms, wall_ms = time_launches(torch, decode, args.steps, args.warmup)
+    med_ms, min_ms = time_each_launch(torch, decode, 30, args.warmup + args.steps)
+    # the same launch on one blob and one destination every time (no rotation through distinct copies)
+    same_ms, _ = time_launches(torch, lambda i: decode(0), 30, 3)
     ok = all(bool(torch.equal(d.cpu(), torch.from_numpy(q.view(np.uint8)))) for d in dsts)
     if not ok:
         print("bench.py: decoded bytes differ from the quantised input", file=sys.stderr)
@@ -365,6 +381,10 @@ def main() -> int:
                      "kernel": f"dc_decode_kernel<{S},int8>", "algorithmic_bytes_per_launch": int(algo_bytes),
                      "avg_launch_ms": round(ms, 5)},
         "wall_ms_per_step": round(wall_ms, 5),
+        "launch_ms_each_timed_alone": {"median": round(med_ms, 5), "min": round(min_ms, 5), "n": 30},
+        "same_buffers_every_launch": {"ms": round(same_ms, 5), "decoded_GBps": round(raw_bytes / same_ms / 1e6, 1),
+                                      "note": "no rotation: blob and destination may partly stay in the 256 MB "
+                                              "memory-side cache; not the headline"},
         "roofline_limited_decoded_gbps": round(HBM_PEAK_GBPS / (1 + 1 / ratio), 1),
     }
 
@@ -516,10 +536,24 @@ def main() -> int:
                 break
         dt = (time.perf_counter() - t0) / reps
         assert np.array_equal(ref, q[:sample_raw].view(np.uint8))
+        # one thread, and the oracle's encoder, on the first 128 chunks
+        n_small = min(128, layer["slices"][0]["n_chunks"])  # inside the first matrix, whose blob the library made alone
+        small_raw = min(raw_bytes, n_small * C)
+        t0 = time.perf_counter()
+        oc.decompress(blob, table[:n_small], C, S, small_raw, threads=1)
+        one_thread = small_raw / (time.perf_counter() - t0) / 1e9
+        t0 = time.perf_counter()
+        enc = oc.compress(q[:small_raw], C, S, threads=threads)
+        encode = small_raw / (time.perf_counter() - t0) / 1e9
+        assert np.array_equal(enc.blob[:-64], blob[:int(table["off"][n_small - 1]) + int(table["comp_bytes"][n_small - 1])])
         out["cpu_baseline"] = {"value": round(sample_raw / dt / 1e9, 3), "unit": "GB/s", "cores": threads,
                                "kind": "oracle",
                                "sample": f"first {n_sample} chunks ({sample_raw} decoded bytes) of the same blob, "
-                                         f"{reps} passes, bit-serial C oracle, chunk range split over {threads} threads"}
+                                         f"{reps} passes, bit-serial C oracle, chunk range split over {threads} threads",
+                               "one_thread_GBps": round(one_thread, 4),
+                               "encode_GBps": round(encode, 4),
+                               "encode_sample": f"first {n_small} chunks compressed by the oracle on {threads} threads; "
+                                                "its blob equals the library's"}
 
     print(json.dumps(out))
     return 0
