@@ -132,7 +132,8 @@ typedef struct {
     uint32_t chunk_bytes;   /* decoded bytes per chunk: multiple of 16, 16..DC_MAX_CHUNK_BYTES */
     uint32_t n_streams;     /* S: sub-streams per chunk, one of 32, 64, 128, 256 */
     uint32_t policy;        /* DC_POLICY_*; only the compressor reads it */
-    float raw_fraction;     /* DC_POLICY_RAW_FRACTION: share of chunks kept raw, 0..1 */
+    float raw_fraction;     /* DC_POLICY_RAW_FRACTION: share of chunks kept raw, 0..1; the count is
+                               floor((double)raw_fraction * n_chunks + 0.5) of this 32-bit value */
     uint32_t block_chunks;  /* DC_POLICY_BLOCK_LAST: chunks per block, >= 1 */
     uint32_t reserved;      /* 0 */
     const uint8_t *raw_mask; /* DC_POLICY_RAW_MASK: host array of n_chunks bytes, else NULL */

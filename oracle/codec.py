@@ -186,7 +186,9 @@ def compress(data, chunk_bytes: int, n_streams: int, policy: int = ALL_HUFF, raw
                 nc, threads)
     is_raw = np.zeros(nc, dtype=np.uint8)
     m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
-    rc = L.orc_select_raw(_ptr(huff), n, chunk_bytes, nc, policy, float(raw_fraction), block,
+    # the fraction is a parameter of the method, a 32-bit float at the library's boundary: both sides are
+    # given the same value (0.9 as a float is just below 0.9, which matters when f * n_chunks + 1/2 is whole)
+    rc = L.orc_select_raw(_ptr(huff), n, chunk_bytes, nc, policy, float(np.float32(raw_fraction)), block,
                           None if m is None else _ptr(m), _ptr(is_raw))
     if rc != 0:
         raise ValueError(f"orc_select_raw failed: {rc}")

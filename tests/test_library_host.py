@@ -126,6 +126,18 @@ def test_raw_policies_match_oracle(policy, kw):
     dc.validate(blob, table, p)
 
 
+def test_raw_fraction_is_taken_as_a_32_bit_float_on_both_sides():
+    """25 chunks at f = 0.9: f * n + 1/2 is 23 exactly in real numbers and just below 23 for the 32-bit
+    value of 0.9 that the parameter block carries; the count of raw chunks follows the carried value."""
+    C, S = 4096, 32
+    data = weightlike_bytes(25 * C, 3)
+    p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, 0.9)
+    blob, table = dc.compress_chunks(data, p)
+    c = oc.compress(data, C, S, oc.RAW_FRACTION, 0.9)
+    assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob)
+    assert int((table["raw_bytes_flags"] >> 31).sum()) == int(np.float64(np.float32(0.9)) * 25 + 0.5) == 22
+
+
 def test_raw_mask_policy():
     C, S = 4096, 64
     data = weightlike_bytes(10 * C, 6)
