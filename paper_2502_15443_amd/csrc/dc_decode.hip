@@ -306,15 +306,16 @@ __device__ __forceinline__ uint32_t bf16x2(float a, float b)
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Four int8 values in a word -> fp32.  q = (byte ^ 0x80) - 128, so q*s = fma(float(byte^0x80), s, -128 s)
-// with a single rounding.
-__device__ __forceinline__ void word_to_scaled_f32(uint32_t w, float s, float bias, float f[4])
+// int8 value number N of a word as fp32: one v_cvt_f32_i32 whose operand selects the byte and sign-extends it
+template <int N> __device__ __forceinline__ float byte_f32(uint32_t w) { return (float)(int)(int8_t)(w >> (8 * N)); }
+
+// Four int8 values in a word -> fp32, times the row scale (one rounding, as the dequantisation is defined).
+__device__ __forceinline__ void word_to_scaled_f32(uint32_t w, float s, float f[4])
 {
-    const uint32_t u = w ^ 0x80808080u;
-    f[0] = __builtin_fmaf((float)(u & 0xFFu), s, bias);
-    f[1] = __builtin_fmaf((float)((u >> 8) & 0xFFu), s, bias);
-    f[2] = __builtin_fmaf((float)((u >> 16) & 0xFFu), s, bias);
-    f[3] = __builtin_fmaf((float)(u >> 24), s, bias);
+    f[0] = byte_f32<0>(w) * s;
+    f[1] = byte_f32<1>(w) * s;
+    f[2] = byte_f32<2>(w) * s;
+    f[3] = byte_f32<3>(w) * s;
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -597,20 +598,16 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const uint32_t wa[2] = {x02[0], x13[0]}, wb[2] = {x02[1], x13[1]};
             const uint32_t base = r * round_bytes;
             if (raw >= base + ct_a * 16 + 16) {
-                const float s = s_a;
-                const float bias = -128.0f * s;
                 float f[8];
-                word_to_scaled_f32(wa[0], s, bias, f);
-                word_to_scaled_f32(wa[1], s, bias, f + 4);
+                word_to_scaled_f32(wa[0], s_a, f);
+                word_to_scaled_f32(wa[1], s_a, f + 4);
                 store16_stream(out + (pos_a + base + 8 * upper), bf16x2(f[0], f[1]), bf16x2(f[2], f[3]), bf16x2(f[4], f[5]),
                                bf16x2(f[6], f[7]));
             }
             if (raw >= base + ct_b * 16 + 16) {
-                const float s = s_b;
-                const float bias = -128.0f * s;
                 float f[8];
-                word_to_scaled_f32(wb[0], s, bias, f);
-                word_to_scaled_f32(wb[1], s, bias, f + 4);
+                word_to_scaled_f32(wb[0], s_b, f);
+                word_to_scaled_f32(wb[1], s_b, f + 4);
                 store16_stream(out + (pos_b + base + 8 * upper), bf16x2(f[0], f[1]), bf16x2(f[2], f[3]), bf16x2(f[4], f[5]),
                                bf16x2(f[6], f[7]));
             }
@@ -623,8 +620,8 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     }
 
     if (MODE == kModeGemv) {
-        // Partial dot products of byte^0x80 (1..255) with x; the -128*sum(x) term and the row scale
-        // are applied once per row by dc_gemv_finish_kernel.  A lane keeps the sum of its groups of
+        // Partial dot products of the int8 values with x; the row scale is applied once per row by
+        // dc_gemv_finish_kernel.  A lane keeps the sum of its groups of
         // one row; when some lane of the wave moves to another row, the wave adds its sums to y, one
         // atomic per row it holds.
         uint32_t cur_row = 0xFFFFFFFFu;
@@ -651,11 +648,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    const uint32_t u = w[i] ^ 0x80808080u;
-                    acc = __builtin_fmaf((float)(u & 0xFFu), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
-                    acc = __builtin_fmaf((float)((u >> 8) & 0xFFu), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
-                    acc = __builtin_fmaf((float)((u >> 16) & 0xFFu), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
-                    acc = __builtin_fmaf((float)(u >> 24), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
+                    acc = __builtin_fmaf(byte_f32<0>(w[i]), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
+                    acc = __builtin_fmaf(byte_f32<1>(w[i]), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
+                    acc = __builtin_fmaf(byte_f32<2>(w[i]), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
+                    acc = __builtin_fmaf(byte_f32<3>(w[i]), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
                 }
             }
             col += round_bytes;
@@ -681,26 +677,16 @@ __global__ __launch_bounds__(256) void dc_gemv_zero_kernel(RowBlocks rb)
     if (i < rb.mats[mi].rows) rb.mats[mi].y_accum[i] = 0.0f;
 }
 
-// y_i = scale_i * (acc_i - 128 * sum_j x_j); every block re-reduces x (at most 32 KiB, cache resident).
+// y_i = scale_i * acc_i
 __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
 {
     uint32_t mi = 0;
     for (uint32_t i = 1; i < rb.n_mats; i++)
         if (blockIdx.x >= rb.first_block[i]) mi = i;
     const MatrixArgs &m = rb.mats[mi];
-    __shared__ float part[256];
-    float s = 0.0f;
-    for (uint32_t j = threadIdx.x; j < m.cols; j += 256) s += bf16_bits_to_f32(m.x_bf16[j]);
-    part[threadIdx.x] = s;
-    __syncthreads();
-    for (int d = 128; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
-        __syncthreads();
-    }
-    const float xsum = part[0];
     const uint32_t i = (blockIdx.x - rb.first_block[mi]) * 256 + threadIdx.x;
     if (i < m.rows) {
-        const float y = m.row_scale[i] * (m.y_accum[i] - 128.0f * xsum);
+        const float y = m.row_scale[i] * m.y_accum[i];
         m.y_accum[i] = y;
         if (m.y_bf16) m.y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
@@ -708,14 +694,14 @@ __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
 
 // Batch-1 product on weights that are already decoded: y_i = scale_i * sum_j q_ij x_j, q int8 row-major.
 // A workgroup owns kGemvRows consecutive rows; its 256 threads walk the columns 16 bytes a thread
-// (4 KiB a workgroup and row), so that x is converted once for all the rows; the weights enter as
-// byte ^ 0x80 (one conversion instruction a byte) and the -128 * sum(x) term is taken out at the end.
+// (4 KiB a workgroup and row), so that x is converted once for all the rows; a weight costs one
+// conversion (sign-extending byte select) and one fused multiply-add.
 constexpr int kGemvRows = 4;
 __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restrict__ q, const float *__restrict__ row_scale,
                                                          uint32_t rows, uint32_t cols, const uint16_t *__restrict__ x_bf16,
                                                          float *__restrict__ y_f32, uint16_t *__restrict__ y_bf16)
 {
-    __shared__ float part[4][kGemvRows + 1];
+    __shared__ float part[4][kGemvRows];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const uint32_t row0 = blockIdx.x * kGemvRows;
     const uint8_t *qr[kGemvRows];
@@ -725,7 +711,6 @@ __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restri
         qr[r] = q + (size_t)row * cols;
     }
     float acc[kGemvRows] = {0.0f, 0.0f, 0.0f, 0.0f};
-    float xsum = 0.0f;
     for (uint32_t c = threadIdx.x * 16; c < cols; c += 4096) {
         u32x4 w[kGemvRows];
 #pragma unroll
@@ -738,34 +723,29 @@ __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restri
         for (int i = 0; i < 8; i++) {
             xf[2 * i] = bf16_bits_to_f32(xs[i] & 0xFFFFu);
             xf[2 * i + 1] = __uint_as_float(xs[i] & 0xFFFF0000u);
-            xsum += xf[2 * i] + xf[2 * i + 1];
         }
 #pragma unroll
         for (int r = 0; r < kGemvRows; r++) {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const uint32_t u = w[r][i] ^ 0x80808080u;
-                acc[r] = __builtin_fmaf((float)(u & 0xFFu), xf[4 * i], acc[r]);
-                acc[r] = __builtin_fmaf((float)((u >> 8) & 0xFFu), xf[4 * i + 1], acc[r]);
-                acc[r] = __builtin_fmaf((float)((u >> 16) & 0xFFu), xf[4 * i + 2], acc[r]);
-                acc[r] = __builtin_fmaf((float)(u >> 24), xf[4 * i + 3], acc[r]);
+                acc[r] = __builtin_fmaf(byte_f32<0>(w[r][i]), xf[4 * i], acc[r]);
+                acc[r] = __builtin_fmaf(byte_f32<1>(w[r][i]), xf[4 * i + 1], acc[r]);
+                acc[r] = __builtin_fmaf(byte_f32<2>(w[r][i]), xf[4 * i + 2], acc[r]);
+                acc[r] = __builtin_fmaf(byte_f32<3>(w[r][i]), xf[4 * i + 3], acc[r]);
             }
         }
     }
-    xsum = lanes_sum(xsum);
 #pragma unroll
     for (int r = 0; r < kGemvRows; r++) acc[r] = lanes_sum(acc[r]);
     if (lane == 63) {
 #pragma unroll
         for (int r = 0; r < kGemvRows; r++) part[wave][r] = acc[r];
-        part[wave][kGemvRows] = xsum;
     }
     __syncthreads();
     if (threadIdx.x < kGemvRows && row0 + threadIdx.x < rows) {
         const uint32_t r = threadIdx.x;
         const float total = part[0][r] + part[1][r] + part[2][r] + part[3][r];
-        const float xs4 = part[0][kGemvRows] + part[1][kGemvRows] + part[2][kGemvRows] + part[3][kGemvRows];
-        const float y = row_scale[row0 + r] * (total - 128.0f * xs4);
+        const float y = row_scale[row0 + r] * total;
         y_f32[row0 + r] = y;
         if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
