@@ -241,3 +241,41 @@ def test_compress_bound_holds_on_worst_case():
     cap, nc = dc.compress_bound(data.size, p)
     blob, table = dc.compress_chunks(data, p)
     assert nc == 8 and blob.size <= cap
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_inputs_host_compressor_equals_oracle(seed):
+    """Seeded random sweep on the CPU: the library's host compressor writes the oracle's blob and table for
+    sizes, chunk sizes, sub-stream counts, data kinds and policies drawn together; the validator accepts
+    it, the oracle decodes it back, and the independent Python decoder agrees on the small chunks."""
+    from tests import pyref
+    from tests.helpers import lopsided_bytes
+    r = np.random.default_rng(seed)
+    for it in range(120):
+        S = int(r.choice([32, 64, 128, 256]))
+        C = int(r.choice([16, 48, 512, 4096, 16384, 65536]))
+        n_chunks = int(r.integers(1, 5)) if C >= 16384 else int(r.integers(1, 30))
+        n = (n_chunks - 1) * C + int(r.integers(1, C + 1))
+        kind = int(r.integers(0, 4))
+        if kind == 0:
+            data = weightlike_bytes(n, int(r.integers(1 << 30)))
+        elif kind == 1:
+            data = lopsided_bytes(n, S, int(r.integers(1 << 30)))
+        elif kind == 2:
+            data = r.integers(0, 256, n, dtype=np.uint8)
+        else:
+            data = np.full(n, int(r.integers(256)), np.uint8)
+        policy = int(r.choice([dc.POLICY_ALL_HUFF, dc.POLICY_AUTO, dc.POLICY_RAW_FRACTION, dc.POLICY_BLOCK_LAST]))
+        f = float(r.choice([0.0, 0.1, 0.3, 0.7, 0.9, 1.0]))
+        block = int(r.integers(1, 6))
+        p = dc.Params(C, S, policy, f, block)
+        blob, table = dc.compress_chunks(data, p)
+        c = oc.compress(data, C, S, policy, f, block=block)
+        assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob), (seed, it, S, C, n, policy, f, block)
+        dc.validate(blob, table, p)
+        assert np.array_equal(oc.decompress(blob, table, C, S, n), data)
+        if C <= 512:
+            k = int(r.integers(len(table)))
+            if not table["raw_bytes_flags"][k] & dc.CHUNK_RAW:
+                o, size, raw = int(table["off"][k]), int(table["comp_bytes"][k]), int(table["raw_bytes_flags"][k])
+                assert pyref.parse_and_decode(blob[o:o + size].tobytes(), raw, S) == data[k * C:k * C + raw].tobytes()
