@@ -87,3 +87,29 @@ def gemv_ref(q: np.ndarray, scale: np.ndarray, x_bf16: np.ndarray) -> np.ndarray
     """y_i = scale_i * sum_j q_ij x_j in fp64 (Eq. 1 for one activation row)."""
     x = bf16_to_f64(x_bf16)
     return (q.astype(np.float64) @ x) * scale.astype(np.float64)
+
+
+def quantise_vector(x: np.ndarray):
+    """Symmetric absmax INT8 of one activation row (Eq. 4, "Quant(X')"; Section 4.1: weight and activation
+    are both quantised to INT8).  The paper gives no granularity for activations; one scale for the row:
+    scale = max |x| / 127 (fp32 division; 1 if x is all zero), xq = clip(rint(x / scale), -127, 127)."""
+    assert x.dtype == np.float32 and x.ndim == 1
+    m = np.max(np.abs(x)) if x.size else np.float32(0)
+    scale = np.float32(1.0) if m == 0 else np.float32(m / np.float32(127.0))
+    xq = np.clip(np.rint(x / scale), -127, 127).astype(np.int8)
+    return xq, scale
+
+
+def gemv_w8a8_acc(q: np.ndarray, xq: np.ndarray) -> np.ndarray:
+    """acc_i = sum_j q_ij xq_j, exact integers (Eq. 4: the product of the two quantised operands)."""
+    return q.astype(np.int64) @ xq.astype(np.int64)
+
+
+def gemv_w8a8(q: np.ndarray, scale: np.ndarray, xq: np.ndarray, x_scale) -> np.ndarray:
+    """y_i = fp32(fp32(acc_i) * scale_i) * x_scale: the integer sum is converted to fp32 (round to nearest
+    even), multiplied by the weight scale of the row, then by the activation scale, each product rounded
+    once.  The order is fixed so that the result has one right value."""
+    acc = gemv_w8a8_acc(q, xq)
+    assert np.abs(acc).max(initial=0) < 2 ** 31
+    y = acc.astype(np.float32) * scale.astype(np.float32)
+    return (y * np.float32(x_scale)).astype(np.float32)

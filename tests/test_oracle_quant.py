@@ -168,3 +168,48 @@ def test_generator_is_deterministic_and_shaped():
     assert [m.rows * m.cols for m in synth.LLAMA7B_LAYER] == [4096 * 4096] * 4 + [11008 * 4096] * 3
     assert sum(m.rows * m.cols for m in synth.LLAMA7B_LAYER) == 202375168
     assert sum(m.rows * m.cols for m in synth.LLAMA13B_LAYER) == 317194240
+
+
+# ---------------------------------------------------------------- W8A8 product (Eq. 4)
+
+def test_quantise_vector_closed_forms():
+    x = np.array([0.0, 1.0, -2.0, 0.5, 2.0], dtype=np.float32)
+    xq, s = oq.quantise_vector(x)
+    assert s == np.float32(2.0) / np.float32(127.0)
+    assert xq.tolist() == [0, 64, -127, 32, 127]  # 63.5 rounds to the even 64, 31.75 to 32
+    xq, s = oq.quantise_vector(np.zeros(7, dtype=np.float32))
+    assert s == 1.0 and not xq.any()
+    r = np.random.default_rng(3)
+    x = r.standard_normal(1000).astype(np.float32)
+    xq, s = oq.quantise_vector(x)
+    assert np.abs(xq).max() == 127 and np.abs(xq.astype(np.float64) * float(s) - x).max() <= float(s) * 0.5 * (1 + 1e-6)
+
+
+def test_w8a8_sum_is_exact_and_matches_python_integers():
+    r = np.random.default_rng(4)
+    q = r.integers(-127, 128, (9, 48), dtype=np.int64).astype(np.int8)
+    xq = r.integers(-127, 128, 48, dtype=np.int64).astype(np.int8)
+    want = [sum(int(a) * int(b) for a, b in zip(row, xq)) for row in q]
+    assert oq.gemv_w8a8_acc(q, xq).tolist() == want
+    # the largest sum the library allows (16384 columns of 127 * 127) is far inside 32 bits
+    big = oq.gemv_w8a8_acc(np.full((1, 16384), 127, np.int8), np.full(16384, -127, np.int8))
+    assert big.tolist() == [-16384 * 127 * 127] and abs(int(big[0])) < 2 ** 31
+
+
+def test_w8a8_result_against_real_arithmetic_and_special_cases():
+    r = np.random.default_rng(5)
+    q = r.integers(-127, 128, (40, 512), dtype=np.int64).astype(np.int8)
+    scale = ((r.random(40) + 0.5) * 0.01).astype(np.float32)
+    x = r.standard_normal(512).astype(np.float32)
+    xq, sx = oq.quantise_vector(x)
+    y = oq.gemv_w8a8(q, scale, xq, sx)
+    real = oq.gemv_w8a8_acc(q, xq).astype(np.float64) * scale.astype(np.float64) * float(sx)
+    assert y.dtype == np.float32
+    assert (np.abs(y - real) <= np.abs(real) * 2.0 ** -22).all()  # an int-to-float rounding and two products
+    # sums below 2^24 convert exactly, a power-of-two scale multiplies exactly: the result is the integer sum, scaled
+    y2 = oq.gemv_w8a8(q[:, :64], np.full(40, 0.25, np.float32), xq[:64], np.float32(0.5))
+    assert np.array_equal(y2.astype(np.float64), oq.gemv_w8a8_acc(q[:, :64], xq[:64]) * 0.125)
+    # dequantise-then-multiply in fp64 is the same product up to the quantisation of x
+    deq = (q.astype(np.float64) * scale.astype(np.float64)[:, None]) @ x.astype(np.float64)
+    bound = np.abs(q.astype(np.float64) * scale.astype(np.float64)[:, None]).sum(axis=1) * float(sx) * 0.5
+    assert (np.abs(y - deq) <= bound * (1 + 1e-6) + 1e-6).all()
