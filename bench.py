@@ -219,6 +219,35 @@ def layer_streaming(torch, dc, synth, params, n_layers=8, reps=10):
     out["overhead_vs_resident"] = {"one_stream": round(ser_ms / i_ms - 1, 3), "second_stream": round(ovl_ms / i_ms - 1, 3),
                                    "fused": round(f_ms / i_ms - 1, 3)}
     out["compression_ratio"] = round(raw_bytes / (lay["blob"].size + lay["table"].nbytes), 5)
+
+    # The same loop in the paper's own arithmetic (Eq. 4: weights and activations both INT8): the product on
+    # resident weights, and the fused decode + product.  Integer sums: the two must agree bit for bit.
+    xq = []
+    for sl in lay["slices"]:
+        v, sc = dc.quantize_vector(np.random.default_rng(sl["seed"] & 0xFFFFFFFF).standard_normal(sl["cols"]).astype(np.float32))
+        xq.append((torch.from_numpy(v).cuda(), sc))
+    yw = [torch.empty(sl["rows"], dtype=torch.float32, device="cuda") for sl in lay["slices"]]
+
+    def compute_w8a8(buf, st):
+        for j, sl in enumerate(lay["slices"]):
+            dc.gemv_w8a8(buf.data_ptr() + int(offs[j]), scales[j], sl["rows"], sl["cols"], xq[j][0], xq[j][1], yw[j], None,
+                         st.cuda_stream)
+
+    mats_w = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales[j], y_accum_dev=ys[j], x_i8_dev=xq[j][0], x_scale=xq[j][1])
+              for j, sl in enumerate(lay["slices"])]
+
+    def fused_w8a8(main):
+        for i in range(n_layers):
+            dc.decompress_gemv_w8a8_layer(blobs[i % 2], lay["blob"].size, table, len(lay["table"]), params, mats_w,
+                                          main.cuda_stream)
+
+    iw_ms = wall(lambda main: [compute_w8a8(bufs[i % 2], main) for i in range(n_layers)])
+    fw_ms = wall(fused_w8a8)
+    same = all(bool(torch.equal(a, b)) for a, b in zip(ys, yw))
+    out["w8a8"] = {"ms_per_layer": {"resident_compute_I": round(iw_ms, 4), "fused_decode_product": round(fw_ms, 4)},
+                   "overhead_vs_resident_fused": round(fw_ms / iw_ms - 1, 3),
+                   "fused_weights_GBps": round(raw_bytes / fw_ms / 1e6, 1),
+                   "fused_equals_resident_bit_for_bit": same}
     del blobs, table
     partial = []
     for f in (0.5, 0.8):

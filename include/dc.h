@@ -150,6 +150,8 @@ typedef struct {
     const uint16_t *x_bf16_dev;   /* gemv: cols bf16 activations, 16-byte aligned; cols <= 16384 */
     float *y_accum_dev;           /* gemv: rows fp32 results (zeroed by the call) */
     uint16_t *y_bf16_dev;         /* gemv: rows bf16 results, may be NULL */
+    const int8_t *x_i8_dev;       /* gemv_w8a8: cols int8 activations, 16-byte aligned; cols <= 16384 */
+    float x_scale;                /* gemv_w8a8: scale of the activations (activation = x_i8 * x_scale) */
 } dc_matrix;
 
 /* Library identification string (static storage). */
@@ -299,6 +301,35 @@ int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_t blob_byte
 int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                              uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
                              uint32_t n_mats, void *hip_stream);
+
+/*
+ * Decompression fused with the batch-1 product in the paper's own arithmetic: weights and activations
+ * both INT8 (Section 3.2, Eq. 4, Y_INT8 = Quant(X') * Quant(W'); Section 4.1).  Per row i
+ *   sum_i = sum_j q_ij * xq_j            exact, 32-bit integers (cols <= 16384 keeps it inside)
+ *   y_i   = (float(sum_i) * row_scale[i]) * x_scale   conversion and each product rounded once, in this order
+ * so the result has one right value whatever the order of the additions.  x_i8_dev: cols int8 values,
+ * 16-byte aligned; x_scale: their scale (dc_quantize_vector makes both).  y_accum_dev: rows fp32 results
+ * (it holds the integer sums while the call runs); y_bf16_dev: the same rounded to bf16, may be NULL.
+ * Three launches on hip_stream; nothing decoded is written to memory.  Errors as dc_decompress_gemv.
+ * The _layer form takes x_i8_dev and x_scale from the matrix descriptors.
+ */
+int dc_decompress_gemv_w8a8(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                            uint64_t n_chunks, const dc_params *params, const float *row_scale_dev, uint32_t rows,
+                            uint32_t cols, const int8_t *x_i8_dev, float x_scale, float *y_accum_dev,
+                            uint16_t *y_bf16_dev, void *hip_stream);
+int dc_decompress_gemv_w8a8_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                  uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                  uint32_t n_mats, void *hip_stream);
+/* The same product on weights that are already in the decompression buffer (q_dev and x_i8_dev 16-byte
+ * aligned, cols a multiple of 16, at most 16384).  One launch. */
+int dc_gemv_w8a8(const int8_t *q_dev, const float *row_scale_dev, uint32_t rows, uint32_t cols,
+                 const int8_t *x_i8_dev, float x_scale, float *y_f32_dev, uint16_t *y_bf16_dev, void *hip_stream);
+/*
+ * INT8 quantisation of one activation row (Eq. 4, "Quant(X')"; the paper states no granularity for
+ * activations: one scale for the row).  Host to host.  scale = max |x| / 127 in fp32 (1 if x is all
+ * zero), xq_j = clamp(round-half-even(x_j / scale), -127, 127).
+ */
+int dc_quantize_vector(const float *x_host, uint32_t n, int8_t *xq_host, float *scale_host);
 
 /*
  * Batch-1 product on weights that are already in the decompression buffer: the "model inference

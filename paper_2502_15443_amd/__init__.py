@@ -32,5 +32,9 @@ from .binding import (  # noqa: F401
     decompress_gemv_layer,
     Matrix,
     gemv_i8,
+    decompress_gemv_w8a8,
+    decompress_gemv_w8a8_layer,
+    gemv_w8a8,
+    quantize_vector,
     device_copy,
 )

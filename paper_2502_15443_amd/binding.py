@@ -35,7 +35,8 @@ class _CParams(C.Structure):
 class _CMatrix(C.Structure):
     _fields_ = [("first_chunk", C.c_uint64), ("rows", C.c_uint32), ("cols", C.c_uint32),
                 ("row_scale_dev", C.c_void_p), ("dst_bf16_dev", C.c_void_p), ("dst_cap_elems", C.c_uint64),
-                ("x_bf16_dev", C.c_void_p), ("y_accum_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p)]
+                ("x_bf16_dev", C.c_void_p), ("y_accum_dev", C.c_void_p), ("y_bf16_dev", C.c_void_p),
+                ("x_i8_dev", C.c_void_p), ("x_scale", C.c_float)]
 
 
 @dataclass
@@ -50,6 +51,8 @@ class Matrix:
     x_bf16_dev: object = None
     y_accum_dev: object = None
     y_bf16_dev: object = None
+    x_i8_dev: object = None
+    x_scale: float = 0.0
 
 
 @dataclass
@@ -124,6 +127,14 @@ def _load():
     L.dc_decompress_gemv_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
     L.dc_gemv_i8.restype = i32
     L.dc_gemv_i8.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
+    L.dc_decompress_gemv_w8a8.restype = i32
+    L.dc_decompress_gemv_w8a8.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, C.c_float, vp, vp, vp]
+    L.dc_decompress_gemv_w8a8_layer.restype = i32
+    L.dc_decompress_gemv_w8a8_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
+    L.dc_gemv_w8a8.restype = i32
+    L.dc_gemv_w8a8.argtypes = [vp, vp, u32, u32, vp, C.c_float, vp, vp, vp]
+    L.dc_quantize_vector.restype = i32
+    L.dc_quantize_vector.argtypes = [vp, u32, vp, vp]
     L.dc_device_copy.restype = i32
     L.dc_device_copy.argtypes = [vp, vp, u64, vp]
     return L
@@ -271,7 +282,7 @@ def _matrices(mats):
     for i, m in enumerate(mats):
         arr[i] = _CMatrix(m.first_chunk, m.rows, m.cols, _dev(m.row_scale_dev) or None, _dev(m.dst_bf16_dev) or None,
                           m.dst_cap_elems, _dev(m.x_bf16_dev) or None, _dev(m.y_accum_dev) or None,
-                          _dev(m.y_bf16_dev) or None)
+                          _dev(m.y_bf16_dev) or None, _dev(m.x_i8_dev) or None, float(m.x_scale))
     return arr
 
 
@@ -294,6 +305,38 @@ def decompress_gemv_layer(blob_dev, blob_bytes: int, table_dev, n_chunks: int, p
 def gemv_i8(q_dev, row_scale_dev, rows: int, cols: int, x_bf16_dev, y_f32_dev, y_bf16_dev=None, stream: int = 0) -> None:
     _check(_L.dc_gemv_i8(_dev(q_dev), _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_f32_dev),
                          _dev(y_bf16_dev), stream), "dc_gemv_i8")
+
+
+def decompress_gemv_w8a8(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, row_scale_dev,
+                         rows: int, cols: int, x_i8_dev, x_scale: float, y_accum_dev, y_bf16_dev=None,
+                         stream: int = 0) -> None:
+    cp = params._c()
+    _check(_L.dc_decompress_gemv_w8a8(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
+                                      _dev(row_scale_dev), rows, cols, _dev(x_i8_dev), float(x_scale), _dev(y_accum_dev),
+                                      _dev(y_bf16_dev), stream), "dc_decompress_gemv_w8a8")
+
+
+def decompress_gemv_w8a8_layer(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, mats,
+                               stream: int = 0) -> None:
+    cp = params._c()
+    arr = _matrices(mats)
+    _check(_L.dc_decompress_gemv_w8a8_layer(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp), arr,
+                                            len(mats), stream), "dc_decompress_gemv_w8a8_layer")
+
+
+def gemv_w8a8(q_dev, row_scale_dev, rows: int, cols: int, x_i8_dev, x_scale: float, y_f32_dev, y_bf16_dev=None,
+              stream: int = 0) -> None:
+    _check(_L.dc_gemv_w8a8(_dev(q_dev), _dev(row_scale_dev), rows, cols, _dev(x_i8_dev), float(x_scale),
+                           _dev(y_f32_dev), _dev(y_bf16_dev), stream), "dc_gemv_w8a8")
+
+
+def quantize_vector(x: np.ndarray) -> Tuple[np.ndarray, float]:
+    """dc_quantize_vector: fp32 x[n] -> (int8 xq[n], fp32 scale)."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    xq = np.empty(x.size, dtype=np.int8)
+    sc = np.empty(1, dtype=np.float32)
+    _check(_L.dc_quantize_vector(_host(x), x.size, _host(xq), _host(sc)), "dc_quantize_vector")
+    return xq, float(sc[0])
 
 
 def device_copy(src_dev, dst_dev, nbytes: int, stream: int = 0) -> None:

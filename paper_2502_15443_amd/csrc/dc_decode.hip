@@ -28,7 +28,7 @@ constexpr int kTableEntries = 1 << kPeekBits;
 constexpr int kRingWords = 16;                 // per lane
 constexpr uint32_t kBlockBytes = DC_BLOCK_BYTES; // bitstream fetch granule
 
-enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2 };
+enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2, kModeGemvW8A8 = 3 };
 
 template <int S> struct Geometry {
     static constexpr int kLanesPerChunk = S < 64 ? S : 64;       // lanes of one wave that serve a chunk
@@ -46,8 +46,10 @@ struct MatrixArgs {
     const float *row_scale;
     void *dst;              // kModeBf16: bf16 [rows][cols]
     const uint16_t *x_bf16; // kModeGemv
-    float *y_accum;         // kModeGemv
-    uint16_t *y_bf16;       // kModeGemv, may be null
+    float *y_accum;         // kModeGemv; kModeGemvW8A8: int32 sums until the finish kernel has run
+    uint16_t *y_bf16;       // both products, may be null
+    const int8_t *x_i8;     // kModeGemvW8A8
+    float x_scale;          // kModeGemvW8A8
 };
 
 struct DecodeArgs {
@@ -64,16 +66,17 @@ struct DecodeArgs {
     MatrixArgs mats[DC_MAX_MATRICES];
 };
 
-// Sums `val` over runs of consecutive lanes with equal `key` (keys do not decrease with the lane;
-// key 0xFFFFFFFF = lane takes no part) and adds each run's sum to y[key] with one atomic, issued by
-// the last lane of the run.
-template <bool HALVES> __device__ __forceinline__ void lanes_add_by_key(float *__restrict__ y, uint32_t key, float val)
+// Sums `val` (float or int32) over runs of consecutive lanes with equal `key` (keys do not decrease with
+// the lane; key 0xFFFFFFFF = lane takes no part) and adds each run's sum to y[key] with one atomic,
+// issued by the last lane of the run.
+template <bool HALVES, typename T> __device__ __forceinline__ void lanes_add_by_key(T *__restrict__ y, uint32_t key, T val)
 {
+    static_assert(sizeof(T) == 4, "one register");
 #define DC_SEG_STEP(CTRL, MASK)                                                                              \
     {                                                                                                        \
         const uint32_t k2 = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, CTRL, MASK, 0xF, false);     \
-        const float v2 = __uint_as_float(dpp_or_zero<CTRL, MASK>(__float_as_uint(val)));                     \
-        val += k2 == key ? v2 : 0.0f;                                                                        \
+        const T v2 = __builtin_bit_cast(T, dpp_or_zero<CTRL, MASK>(__builtin_bit_cast(uint32_t, val)));      \
+        val += k2 == key ? v2 : T(0);                                                                        \
     }
     DC_SEG_STEP(0x111, 0xF)
     DC_SEG_STEP(0x112, 0xF)
@@ -637,7 +640,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
             if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) {
-                lanes_add_by_key<CPW == 2>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
+                lanes_add_by_key<CPW == 2, float>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
                 acc = 0.0f;
                 cur_row = 0xFFFFFFFFu;
             }
@@ -657,7 +660,42 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             col += round_bytes;
             while (col >= cols) { col -= cols; row++; }
         }
-        lanes_add_by_key<CPW == 2>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
+        lanes_add_by_key<CPW == 2, float>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
+    }
+
+    if (MODE == kModeGemvW8A8) {
+        // The same walk with int8 activations (Eq. 4 of the paper): four v_dot4 per group, exact int32
+        // sums, integer atomics, so the result does not depend on the order of the additions.
+        int32_t *y_sum = reinterpret_cast<int32_t *>(mat.y_accum);
+        uint32_t cur_row = 0xFFFFFFFFu;
+        int32_t acc = 0;
+        for (uint32_t r = 0; r < rounds; r++) {
+            const uint32_t start = r * round_bytes + ct * 16;
+            const bool whole = raw >= start + 16;
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (huff) {
+                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
+            } else if (whole) {
+                const u32x4 v = load16_stream(payload8 + start);
+                w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+            }
+            if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) {
+                lanes_add_by_key<CPW == 2, int32_t>(y_sum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
+                acc = 0;
+                cur_row = 0xFFFFFFFFu;
+            }
+            if (whole) {
+                cur_row = row;
+                const uint4 x = *reinterpret_cast<const uint4 *>(mat.x_i8 + col);
+                acc = __builtin_amdgcn_sdot4((int)w[0], (int)x.x, acc, false);
+                acc = __builtin_amdgcn_sdot4((int)w[1], (int)x.y, acc, false);
+                acc = __builtin_amdgcn_sdot4((int)w[2], (int)x.z, acc, false);
+                acc = __builtin_amdgcn_sdot4((int)w[3], (int)x.w, acc, false);
+            }
+            col += round_bytes;
+            while (col >= cols) { col -= cols; row++; }
+        }
+        lanes_add_by_key<CPW == 2, int32_t>(y_sum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
     }
 }
 
@@ -677,8 +715,8 @@ __global__ __launch_bounds__(256) void dc_gemv_zero_kernel(RowBlocks rb)
     if (i < rb.mats[mi].rows) rb.mats[mi].y_accum[i] = 0.0f;
 }
 
-// y_i = scale_i * acc_i
-__global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
+// y_i = scale_i * acc_i; W8A8: y_i = (float(sum_i) * scale_i) * x_scale, each step rounded once, in this order
+template <bool W8A8> __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
 {
     uint32_t mi = 0;
     for (uint32_t i = 1; i < rb.n_mats; i++)
@@ -686,7 +724,9 @@ __global__ __launch_bounds__(256) void dc_gemv_finish_kernel(RowBlocks rb)
     const MatrixArgs &m = rb.mats[mi];
     const uint32_t i = (blockIdx.x - rb.first_block[mi]) * 256 + threadIdx.x;
     if (i < m.rows) {
-        const float y = m.row_scale[i] * m.y_accum[i];
+        float y;
+        if (W8A8) y = ((float)reinterpret_cast<const int32_t *>(m.y_accum)[i] * m.row_scale[i]) * m.x_scale;
+        else y = m.row_scale[i] * m.y_accum[i];
         m.y_accum[i] = y;
         if (m.y_bf16) m.y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
@@ -746,6 +786,51 @@ __global__ __launch_bounds__(256) void dc_gemv_i8_kernel(const uint8_t *__restri
         const uint32_t r = threadIdx.x;
         const float total = part[0][r] + part[1][r] + part[2][r] + part[3][r];
         const float y = row_scale[row0 + r] * total;
+        y_f32[row0 + r] = y;
+        if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
+    }
+}
+
+// The same product with int8 activations (Eq. 4): y_i = (float(sum_j q_ij xq_j) * scale_i) * x_scale.
+// Same decomposition; four v_dot4 per 16 weights, exact int32 sums.
+__global__ __launch_bounds__(256) void dc_gemv_w8a8_kernel(const uint8_t *__restrict__ q, const float *__restrict__ row_scale,
+                                                           uint32_t rows, uint32_t cols, const int8_t *__restrict__ x_i8,
+                                                           float x_scale, float *__restrict__ y_f32,
+                                                           uint16_t *__restrict__ y_bf16)
+{
+    __shared__ int32_t part[4][kGemvRows];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t row0 = blockIdx.x * kGemvRows;
+    const uint8_t *qr[kGemvRows];
+#pragma unroll
+    for (int r = 0; r < kGemvRows; r++) {
+        const uint32_t row = row0 + r < rows ? row0 + r : rows - 1; // rows past the end repeat the last one
+        qr[r] = q + (size_t)row * cols;
+    }
+    int32_t acc[kGemvRows] = {0, 0, 0, 0};
+    for (uint32_t c = threadIdx.x * 16; c < cols; c += 4096) {
+        u32x4 w[kGemvRows];
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++) w[r] = load16_stream(qr[r] + c);
+        const uint4 x = *reinterpret_cast<const uint4 *>(x_i8 + c);
+        const uint32_t xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) acc[r] = __builtin_amdgcn_sdot4((int)w[r][i], (int)xs[i], acc[r], false);
+    }
+#pragma unroll
+    for (int r = 0; r < kGemvRows; r++)
+        acc[r] = __builtin_bit_cast(int32_t, lanes_prefix_sum<false>(__builtin_bit_cast(uint32_t, acc[r]))); // total in lane 63
+    if (lane == 63) {
+#pragma unroll
+        for (int r = 0; r < kGemvRows; r++) part[wave][r] = acc[r];
+    }
+    __syncthreads();
+    if (threadIdx.x < kGemvRows && row0 + threadIdx.x < rows) {
+        const uint32_t r = threadIdx.x;
+        const int32_t total = part[0][r] + part[1][r] + part[2][r] + part[3][r];
+        const float y = ((float)total * row_scale[row0 + r]) * x_scale;
         y_f32[row0 + r] = y;
         if (y_bf16) y_bf16[row0 + r] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
@@ -823,7 +908,7 @@ namespace {
 
 // Host checks shared by the fused calls, and the kernel arguments built from the matrix list.
 int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev, uint64_t n_chunks,
-               const dc_params *params, const dc_matrix *mats, uint32_t n_mats, bool gemv, DecodeArgs &a)
+               const dc_params *params, const dc_matrix *mats, uint32_t n_mats, int mode, DecodeArgs &a)
 {
     if (!decode_params_ok(params) || !blob_dev || !table_dev || !mats || n_mats == 0 || n_mats > DC_MAX_MATRICES ||
         n_chunks == 0 || blob_bytes < 16)
@@ -840,8 +925,11 @@ int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
     for (uint32_t i = 0; i < n_mats; i++) {
         const dc_matrix &m = mats[i];
         if (m.rows == 0 || m.cols == 0 || m.cols % 16 || !m.row_scale_dev) return DC_E_ARG;
-        if (gemv) {
+        const bool gemv = mode != kModeBf16;
+        if (mode == kModeGemv) {
             if (!m.x_bf16_dev || !m.y_accum_dev || m.cols > 16384 || !aligned16(m.x_bf16_dev)) return DC_E_ARG;
+        } else if (mode == kModeGemvW8A8) {
+            if (!m.x_i8_dev || !m.y_accum_dev || m.cols > 16384 || !aligned16(m.x_i8_dev)) return DC_E_ARG;
         } else {
             if (!m.dst_bf16_dev || !aligned16(m.dst_bf16_dev)) return DC_E_ARG;
         }
@@ -859,6 +947,8 @@ int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
         k.x_bf16 = m.x_bf16_dev;
         k.y_accum = m.y_accum_dev;
         k.y_bf16 = m.y_bf16_dev;
+        k.x_i8 = m.x_i8_dev;
+        k.x_scale = m.x_scale;
     }
     if (next_chunk != n_chunks) return DC_E_ARG;
     return DC_OK;
@@ -871,17 +961,20 @@ extern "C" int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_
                                                 uint32_t n_mats, void *hip_stream)
 {
     DecodeArgs a;
-    const int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, false, a);
+    const int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, kModeBf16, a);
     if (rc != DC_OK) return rc;
     return launch_decode<kModeBf16>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
 }
 
-extern "C" int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
-                                        uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
-                                        uint32_t n_mats, void *hip_stream)
+namespace {
+
+// zero y, decode with the product fused in, scale y: three launches
+template <int MODE>
+int gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev, uint64_t n_chunks,
+               const dc_params *params, const dc_matrix *mats_host, uint32_t n_mats, void *hip_stream)
 {
     DecodeArgs a;
-    int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, true, a);
+    int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, MODE, a);
     if (rc != DC_OK) return rc;
     RowBlocks rb = {};
     rb.n_mats = n_mats;
@@ -891,10 +984,42 @@ extern "C" int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_b
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipLaunchKernelGGL(dc_gemv_zero_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
-    rc = launch_decode<kModeGemv>(a, params->n_streams, stream);
+    rc = launch_decode<MODE>(a, params->n_streams, stream);
     if (rc != DC_OK) return rc;
-    hipLaunchKernelGGL(dc_gemv_finish_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
+    hipLaunchKernelGGL(dc_gemv_finish_kernel<MODE == kModeGemvW8A8>, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
     return launch_status();
+}
+
+} // namespace
+
+extern "C" int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                        uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                        uint32_t n_mats, void *hip_stream)
+{
+    return gemv_layer<kModeGemv>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, hip_stream);
+}
+
+extern "C" int dc_decompress_gemv_w8a8_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                             uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
+                                             uint32_t n_mats, void *hip_stream)
+{
+    return gemv_layer<kModeGemvW8A8>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, hip_stream);
+}
+
+extern "C" int dc_decompress_gemv_w8a8(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                       uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
+                                       uint32_t rows, uint32_t cols, const int8_t *x_i8_dev, float x_scale,
+                                       float *y_accum_dev, uint16_t *y_bf16_dev, void *hip_stream)
+{
+    dc_matrix m = {};
+    m.rows = rows;
+    m.cols = cols;
+    m.row_scale_dev = row_scale_dev;
+    m.x_i8_dev = x_i8_dev;
+    m.x_scale = x_scale;
+    m.y_accum_dev = y_accum_dev;
+    m.y_bf16_dev = y_bf16_dev;
+    return dc_decompress_gemv_w8a8_layer(blob_dev, blob_bytes, table_dev, n_chunks, params, &m, 1, hip_stream);
 }
 
 extern "C" int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
@@ -927,6 +1052,19 @@ extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, 
 }
 
 extern "C" const char *dc_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
+
+extern "C" int dc_gemv_w8a8(const int8_t *q_dev, const float *row_scale_dev, uint32_t rows, uint32_t cols,
+                            const int8_t *x_i8_dev, float x_scale, float *y_f32_dev, uint16_t *y_bf16_dev, void *hip_stream)
+{
+    if (!q_dev || !row_scale_dev || !x_i8_dev || !y_f32_dev || rows == 0 || cols == 0 || cols % 16 || cols > 16384)
+        return DC_E_ARG;
+    if (!aligned16(q_dev) || !aligned16(x_i8_dev)) return DC_E_ARG;
+    const uint32_t blocks = (rows + kGemvRows - 1) / kGemvRows;
+    hipLaunchKernelGGL(dc_gemv_w8a8_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const uint8_t *>(q_dev), row_scale_dev, rows, cols, x_i8_dev, x_scale, y_f32_dev,
+                       y_bf16_dev);
+    return launch_status();
+}
 
 extern "C" int dc_gemv_i8(const int8_t *q_dev, const float *row_scale_dev, uint32_t rows, uint32_t cols,
                           const uint16_t *x_bf16_dev, float *y_f32_dev, uint16_t *y_bf16_dev, void *hip_stream)

@@ -360,6 +360,21 @@ extern "C" int dc_quantize_rows(const float *w, uint32_t rows, uint32_t cols, co
     return DC_OK;
 }
 
+extern "C" int dc_quantize_vector(const float *x, uint32_t n, int8_t *xq, float *scale)
+{
+    if (!x || !xq || !scale || n == 0) return DC_E_ARG;
+    float m = 0.0f;
+    for (uint32_t j = 0; j < n; j++) m = std::max(m, std::fabs(x[j]));
+    const float sc = m == 0.0f ? 1.0f : m / 127.0f;
+    for (uint32_t j = 0; j < n; j++) {
+        float r = std::nearbyintf(x[j] / sc); // round-half-even in the default mode
+        r = std::min(127.0f, std::max(-127.0f, r));
+        xq[j] = (int8_t)r;
+    }
+    *scale = sc;
+    return DC_OK;
+}
+
 extern "C" int dc_quantize_tensor(const float *w, uint32_t rows, uint32_t cols, const float *act_absmax,
                                   double alpha, double sparsity, int8_t *q, float *tensor_scale,
                                   float *col_scale_out)

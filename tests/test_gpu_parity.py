@@ -257,6 +257,77 @@ def test_gemv_within_tolerance(S, rows, cols, C, f):
     assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
 
 
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
+@pytest.mark.parametrize("rows,cols,C,f", [(160, 1024, 16384, 0.0), (50, 5120, 65536, 0.0), (37, 13824, 65536, 0.3),
+                                           (64, 2752, 16384, 0.5), (3, 16384, 4096, 0.0)])
+def test_gemv_w8a8_bit_exact(S, rows, cols, C, f):
+    """Weights and activations both INT8: the integer sums are exact and the two scalings have a fixed
+    order, so the fused call must give the oracle's fp32 values bit for bit (and their bf16 roundings)."""
+    print(f"case gemv w8a8 S={S} {rows}x{cols} C={C} f={f}", flush=True)
+    seed = synth.matrix_seed(6, 3)
+    q, scale = oracle_matrix(rows, cols, seed, False)
+    if rows >= 3:
+        q = q.copy()
+        q[1] = 0  # a row of zeros gives exactly zero
+        q[2] = 127  # and one of the largest sums
+    c = oc.compress(q, C, S, oc.RAW_FRACTION, f)
+    x = np.random.default_rng(seed & 0xFFFF).standard_normal(cols).astype(np.float32) * np.float32(3.0)
+    xq, sx = oq.quantise_vector(x)
+    if rows >= 3:
+        xq = xq.copy()
+        xq[:] = np.where(np.arange(cols) % 7 == 0, xq, 127).astype(np.int8)  # large sums of one sign in row 2
+    y_ref = oq.gemv_w8a8(q, scale, xq, sx)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    xq_d = torch.from_numpy(xq).cuda()
+    y32 = torch.full((rows + 5,), 7.0, dtype=torch.float32, device="cuda")
+    y16 = torch.zeros(rows, dtype=torch.int16, device="cuda")
+    dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, xq_d,
+                            float(sx), y32, y16, stream())
+    torch.cuda.synchronize()
+    y = y32.cpu().numpy()
+    assert (y[rows:] == 7.0).all()
+    assert np.array_equal(y[:rows].view(np.uint32), y_ref.view(np.uint32))
+    assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y_ref))
+    # the same product on the decoded weights in a buffer
+    z32 = torch.full((rows + 5,), 7.0, dtype=torch.float32, device="cuda")
+    dc.gemv_w8a8(dev(q), scale_d, rows, cols, xq_d, float(sx), z32, None, stream())
+    torch.cuda.synchronize()
+    z = z32.cpu().numpy()
+    assert (z[rows:] == 7.0).all() and np.array_equal(z[:rows].view(np.uint32), y_ref.view(np.uint32))
+    if rows >= 3:
+        assert y_ref[1] == 0.0
+        if cols >= 2048:
+            assert abs(int(oq.gemv_w8a8_acc(q, xq)[2])) > 2 ** 24  # beyond the integers fp32 holds exactly
+
+
+def test_gemv_w8a8_whole_layer_call_and_argument_checks():
+    C, S = 16384, 256
+    shapes = [(96, 1024), (40, 2752), (33, 5120)]
+    blobs, tables, mats, refs, keep = [], [], [], [], []
+    off = k0 = 0
+    for i, (rows, cols) in enumerate(shapes):
+        q, scale = oracle_matrix(rows, cols, synth.matrix_seed(7, i), False)
+        c = oc.compress(q, C, S)
+        t = c.table.copy(); t["off"] += off
+        blobs.append(c.blob); tables.append(t); off += c.blob.size
+        xq, sx = oq.quantise_vector(np.random.default_rng(i).standard_normal(cols).astype(np.float32))
+        s_d, x_d = torch.from_numpy(scale).cuda(), torch.from_numpy(xq).cuda()
+        y32 = torch.full((rows,), 7.0, dtype=torch.float32, device="cuda")
+        mats.append(dc.Matrix(k0, rows, cols, s_d, y_accum_dev=y32, x_i8_dev=x_d, x_scale=float(sx)))
+        refs.append((oq.gemv_w8a8(q, scale, xq, sx), y32)); keep += [s_d, x_d]
+        k0 += len(t)
+    blob, table = np.concatenate(blobs), np.concatenate(tables)
+    p = dc.Params(C, S)
+    dc.decompress_gemv_w8a8_layer(dev(blob), blob.size, dev(table), len(table), p, mats, stream())
+    torch.cuda.synchronize()
+    for y_ref, y32 in refs:
+        assert np.array_equal(y32.cpu().numpy().view(np.uint32), y_ref.view(np.uint32))
+    bad = [dc.Matrix(m.first_chunk, m.rows, m.cols, m.row_scale_dev, y_accum_dev=m.y_accum_dev, x_i8_dev=None)
+           for m in mats]
+    with pytest.raises(dc.DCError):
+        dc.decompress_gemv_w8a8_layer(dev(blob), blob.size, dev(table), len(table), p, bad, stream())
+
+
 @pytest.mark.parametrize("rows,cols", [(1, 16), (7, 1040), (64, 4096), (37, 13824), (530, 5120)])
 def test_gemv_i8_on_decoded_weights(rows, cols):
     """The plain product on weights in the decompression buffer against the fp64 reference."""

@@ -243,6 +243,22 @@ def test_compress_bound_holds_on_worst_case():
     assert nc == 8 and blob.size <= cap
 
 
+def test_quantize_vector_matches_oracle_bit_for_bit():
+    r = np.random.default_rng(8)
+    for n, mult in [(1, 1.0), (16, 3.0), (4096, 1.0), (13824, 40.0), (5, 1e-20)]:
+        x = (r.standard_normal(n) * mult).astype(np.float32)
+        x[r.integers(n)] *= 8
+        xq, s = dc.quantize_vector(x)
+        xq_ref, s_ref = oq.quantise_vector(x)
+        assert np.array_equal(xq, xq_ref) and np.float32(s) == s_ref
+    xq, s = dc.quantize_vector(np.zeros(9, np.float32))
+    assert s == 1.0 and not xq.any()
+    halves = (np.arange(-8, 9, dtype=np.float32) + 0.5) * np.float32(127.0 / 127.0)  # ties, scale exactly 1/...
+    x = np.concatenate([halves, np.array([127.0], np.float32)])
+    xq, s = dc.quantize_vector(x)
+    assert np.array_equal(xq, oq.quantise_vector(x)[0])
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_random_inputs_host_compressor_equals_oracle(seed):
     """Seeded random sweep on the CPU: the library's host compressor writes the oracle's blob and table for
