@@ -104,4 +104,14 @@ def test_random_valid_inputs_all_entry_points(seed):
         assert (y[rows:] == 7.0).all()
         rms = float(np.sqrt(np.mean(y_ref ** 2)))
         assert (np.abs(y[:rows] - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
+        # weights and activations both INT8: exact sums, the oracle's fp32 bits
+        xq = r.integers(-127, 128, cols).astype(np.int8)
+        sx = np.float32(0.013)
+        z32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
+        dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols,
+                                torch.from_numpy(xq).cuda(), float(sx), z32, None, st)
+        torch.cuda.synchronize()
+        z = z32.cpu().numpy()
+        assert (z[rows:] == 7.0).all()
+        assert np.array_equal(z[:rows].view(np.uint32), oq.gemv_w8a8(q, scale, xq, sx).view(np.uint32))
     assert fused >= 30
