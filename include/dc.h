@@ -259,6 +259,9 @@ int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *t
  *   dst_dev, dst_cap       destination, 16-byte aligned; needs (n_chunks-1)*chunk_bytes + last chunk's
  *                          raw_bytes bytes; the host checks dst_cap >= (n_chunks-1)*chunk_bytes + 1 and
  *                          the kernel skips any chunk that would end beyond dst_cap
+ * A part of a blob (a layer of a model, say) is decoded by passing table_dev + k0 and the number of
+ * chunks wanted with the same blob: offsets in the table count from blob_dev, and chunk k0 + i then
+ * decodes to dst_dev + i * chunk_bytes.
  */
 int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                          uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,

@@ -91,6 +91,20 @@ def test_decode_block_last_policy():
     assert np.array_equal(gpu_decode(c.blob, c.table, dc.Params(C, S), data.size), data)
 
 
+def test_decode_a_range_of_chunks_of_a_blob():
+    """A layer out of a model: the table pointer advanced to the first chunk wanted, the same blob."""
+    C, S, n = 4096, 64, 11 * 4096 + 500
+    data = weightlike_bytes(n, 31)
+    c = oc.compress(data, C, S, oc.RAW_FRACTION, 0.3)
+    blob_d, table_d = dev(c.blob), dev(c.table)
+    k0, count = 4, 5
+    dst = torch.full((count * C + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, c.blob.size, table_d.data_ptr() + 16 * k0, count, dc.Params(C, S), dst, count * C, stream())
+    torch.cuda.synchronize()
+    out = dst.cpu().numpy()
+    assert np.array_equal(out[:count * C], data[k0 * C:(k0 + count) * C]) and (out[count * C:] == 0x5A).all()
+
+
 def test_destination_untouched_beyond_decoded_bytes():
     C, S, n = 4096, 32, 3 * 4096 + 100
     data = weightlike_bytes(n, 23)
