@@ -219,7 +219,8 @@ __device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t fiel
     s.state = ((skip + 3) << 8) + 64 - bits;
 }
 
-// After this at least 33 bits are valid: enough for three codes of 11 bits.
+// Takes the look-ahead word into the buffer when at most 32 bits are valid.  After it at least 32 bits
+// are valid, and exactly 32 only if the buffer was empty: enough for two codes of 11 bits.
 __device__ __forceinline__ void refill(Stream &s, uint32_t ring_lane)
 {
     if ((s.state & 0xFFu) <= 32) {
@@ -227,6 +228,14 @@ __device__ __forceinline__ void refill(Stream &s, uint32_t ring_lane)
         s.next = ring_word(s.state, ring_lane);
         s.state += 256 + 32;
     }
+}
+
+// Three codes of 11 bits need 33 bits.  A buffer that was empty holds 32 after one refill (the three codes
+// before it used all 33 bits it had: rare, but it happens); the second call then takes one more word.
+__device__ __forceinline__ void refill33(Stream &s, uint32_t ring_lane)
+{
+    refill(s, ring_lane);
+    refill(s, ring_lane);
 }
 
 // Table entry = (length - 1) | symbol << 8: the field a 32-bit shift reads (its low 5 bits) is the
@@ -268,9 +277,9 @@ template <int HALF>
 __device__ __forceinline__ void decode8(Stream &s, uint32_t tbl, uint32_t ring_lane, uint32_t out[4])
 {
     uint32_t e[8];
-    refill(s, ring_lane);
+    refill33(s, ring_lane);
     symbols<3>(s, tbl, e);
-    refill(s, ring_lane);
+    refill33(s, ring_lane);
     symbols<3>(s, tbl, e + 3);
     refill(s, ring_lane);
     symbols<2>(s, tbl, e + 6);

@@ -51,3 +51,49 @@ def lopsided_bytes(n: int, S: int, seed: int) -> np.ndarray:
         elif j == 1:
             out[lo:hi] = np.where(r.random(hi - lo) < 0.5, rare[lo:hi], 0)
     return out
+
+
+def empty_buffer_before_three_codes(data: np.ndarray, S: int):
+    """Walk of a decoder that keeps a 64-bit buffer per sub-stream, refills it by 32 bits whenever at most 32
+    bits are valid, and decodes each half group of 8 symbols as 3 + 3 + 2 codes: the places (lane, group,
+    half, first symbol of the batch) where a batch of three 11-bit codes (33 bits) begins on a buffer that the
+    batch before it emptied completely, so that one refill leaves 32 bits.  Code lengths from the oracle."""
+    raw = data.size
+    ln = oc.code_lengths(np.bincount(data, minlength=256).astype(np.uint64)).astype(int)
+    groups = (raw + 15) // 16
+    hits = []
+    for j in range(min(S, groups)):
+        lens = [ln[data[16 * g:16 * g + 16]] for g in range(j, groups, S)]
+        size = (int(sum(int(x.sum()) for x in lens)) + 7) // 8
+        avail = 64 - 8 * (((-size) % 16) & 3)  # the stream starts pad bytes into its first block
+        for gi, gl in enumerate(lens):
+            if gl.size < 16:
+                break
+            for half in (0, 1):
+                h = gl[8 * half:8 * half + 8]
+                for lo, hi in ((0, 3), (3, 6), (6, 8)):
+                    if avail <= 32:
+                        if avail == 0 and int(h[lo:hi].sum()) == 33:
+                            hits.append((j, gi, half, lo))
+                        avail += 32
+                    avail -= int(h[lo:hi].sum())
+    return hits
+
+
+def emptied_buffer_bytes(S: int) -> np.ndarray:
+    """24 rounds of a chunk in which sub-stream 0 is nearly all rare byte values (10- and 11-bit codes) and
+    the other sub-streams are a geometric mix of ten frequent ones; drawn again (seeded) until the walk above
+    meets its case."""
+    r = np.random.default_rng(1)
+    p = np.array([2.0 ** -(k + 1) for k in range(10)])
+    for _ in range(50):
+        n = 16 * S * 24
+        data = r.choice(np.arange(10), size=n, p=p / p.sum()).astype(np.uint8)
+        for rd in range(24):
+            grp = r.integers(100, 164, 16).astype(np.uint8)
+            k = int(r.integers(0, 4))
+            grp[r.integers(0, 16, k)] = r.integers(0, 3, k)
+            data[16 * rd * S:16 * rd * S + 16] = grp
+        if empty_buffer_before_three_codes(data, S):
+            return data
+    raise AssertionError("no such input found")

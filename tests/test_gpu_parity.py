@@ -91,6 +91,35 @@ def test_decode_block_last_policy():
     assert np.array_equal(gpu_decode(c.blob, c.table, dc.Params(C, S), data.size), data)
 
 
+@pytest.mark.parametrize("S", [32, 64])
+def test_three_longest_codes_on_a_buffer_that_was_just_emptied(S):
+    """Three 11-bit codes need 33 bits, one refill of an empty bit buffer gives 32: the decoder must take a
+    second word there.  The input is built so that this happens (checked by a walk over the code lengths);
+    every decode mode must still give the oracle's result.  Found by a random sweep: one such case in
+    about ten thousand chunks of weight-like data."""
+    from tests.helpers import emptied_buffer_bytes, empty_buffer_before_three_codes
+    data = emptied_buffer_bytes(S)
+    assert empty_buffer_before_three_codes(data, S)
+    n, C = data.size, data.size
+    c = oc.compress(data, C, S)
+    assert np.array_equal(gpu_decode(c.blob, c.table, dc.Params(C, S), n), data)
+    cols = 16 * S
+    rows = n // cols
+    q = data.view(np.int8).reshape(rows, cols)
+    scale = np.full(rows, 0.0123, np.float32)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    out16 = torch.zeros(n, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, out16, n,
+                               stream())
+    xq = (np.arange(cols) % 5 - 2).astype(np.int8)
+    y32 = torch.zeros(rows, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols,
+                            torch.from_numpy(xq).cuda(), 0.5, y32, None, stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(out16.cpu().numpy().view(np.uint16).reshape(rows, cols), oq.dequant_bf16(q, scale))
+    assert np.array_equal(y32.cpu().numpy().view(np.uint32), oq.gemv_w8a8(q, scale, xq, np.float32(0.5)).view(np.uint32))
+
+
 def test_decode_a_range_of_chunks_of_a_blob():
     """A layer out of a model: the table pointer advanced to the first chunk wanted, the same blob."""
     C, S, n = 4096, 64, 11 * 4096 + 500
