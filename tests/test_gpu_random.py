@@ -26,7 +26,7 @@ def draw_case(r):
     n = (n_chunks - 1) * C + int(r.integers(1, C + 1))
     if r.random() < 0.5:
         n = max(16, n // 16 * 16)  # a whole number of 16-byte groups: the fused calls apply
-    kind = int(r.integers(0, 5))
+    kind = int(r.integers(0, 7))
     if kind == 0:
         data = weightlike_bytes(n, int(r.integers(1 << 30)))
     elif kind == 1:
@@ -36,8 +36,11 @@ def draw_case(r):
     elif kind == 3:
         sigma = float(r.choice([0.3, 2, 8, 40]))
         data = np.clip(np.rint(r.standard_normal(n) * sigma), -127, 127).astype(np.int8).view(np.uint8)
-    else:
+    elif kind == 4:
         data = np.full(n, int(r.integers(256)), np.uint8)
+    else:  # a wide alphabet with a long tail: many codes at the length limit
+        pz = 1.0 / np.arange(1, 257) ** float(r.uniform(0.7, 1.8))
+        data = r.permutation(256).astype(np.uint8)[r.choice(256, size=n, p=pz / pz.sum())]
     policy = int(r.choice([oc.ALL_HUFF, oc.AUTO, oc.RAW_FRACTION, oc.BLOCK_LAST]))
     f = float(r.choice([0.0, 0.2, 0.5, 0.9, 1.0]))
     block = int(r.integers(1, 6))
