@@ -346,8 +346,8 @@ def full_model(torch, dc, synth, n_layers, sweep):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=5000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--streams", type=int, default=int(os.environ.get("DC_BENCH_STREAMS", "256")),
                     help="sub-streams per chunk (32, 64, 128 or 256)")
     ap.add_argument("--chunk", type=int, default=65536)
