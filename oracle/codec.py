@@ -204,6 +204,10 @@ def decompress(blob, table, chunk_bytes: int, n_streams: int, raw_bytes: int, th
     L = lib()
     b = _bytes(blob)
     t = np.ascontiguousarray(table, dtype=CHUNK_DTYPE)
+    # the destination is sized by the caller: the table must describe exactly that many bytes
+    sizes = (t["raw_bytes_flags"] & np.uint32(0x7FFFFFFF)).astype(np.int64)
+    if t.size == 0 or (sizes[:-1] != chunk_bytes).any() or (t.size - 1) * chunk_bytes + int(sizes[-1]) != raw_bytes:
+        raise ValueError("the table does not describe raw_bytes bytes")
     dst = np.zeros(raw_bytes, dtype=np.uint8)
     _run_ranges(lambda a, c: L.orc_decompress(_ptr(b), b.size, _ptr(t), a, c, chunk_bytes, n_streams, _ptr(dst)),
                 int(t.size), threads)
