@@ -15,6 +15,8 @@ _SRC = os.path.join(_HERE, "dc_oracle.c")
 _LIB = os.path.join(_HERE, "libdc_oracle.so")
 
 ALL_HUFF, AUTO, RAW_FRACTION, RAW_MASK, BLOCK_LAST = 0, 1, 2, 3, 4
+HUFFMAN, TANS = 0, 1  # the coder of the chunks that are not raw
+TANS_L = 2048
 RAW_FLAG = 0x80000000
 
 CHUNK_DTYPE = np.dtype([("off", "<u8"), ("comp_bytes", "<u4"), ("raw_bytes_flags", "<u4")])
@@ -53,6 +55,25 @@ def lib():
             L.orc_encode_chunk.restype = C.c_uint64
             L.orc_decode_chunk.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, vp]
             L.orc_decode_chunk.restype = C.c_int
+            L.orc_payload_bound.argtypes = [C.c_uint32, C.c_uint32, C.c_int]
+            L.orc_payload_bound.restype = C.c_uint64
+            L.orc_encode_chunk_codec.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_int, C.c_int, vp, C.c_uint64]
+            L.orc_encode_chunk_codec.restype = C.c_uint64
+            L.orc_decode_chunk_codec.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int, vp]
+            L.orc_decode_chunk_codec.restype = C.c_int
+            L.orc_tans_normalise.argtypes = [vp, vp]
+            L.orc_tans_normalise.restype = C.c_int
+            L.orc_tans_states.argtypes = [vp, vp, vp]
+            L.orc_tans_states.restype = C.c_int
+            L.orc_chunk_sizes_codec.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int, C.c_uint64,
+                                                C.c_uint64, vp]
+            L.orc_chunk_sizes_codec.restype = C.c_int
+            L.orc_emit_codec.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int, vp, C.c_uint64,
+                                         C.c_uint64, vp]
+            L.orc_emit_codec.restype = C.c_int
+            L.orc_decompress_codec.argtypes = [vp, C.c_uint64, vp, C.c_uint64, C.c_uint64, C.c_uint32,
+                                               C.c_uint32, C.c_int, vp]
+            L.orc_decompress_codec.restype = C.c_int
             L.orc_num_chunks.argtypes = [C.c_uint64, C.c_uint32]
             L.orc_num_chunks.restype = C.c_uint64
             L.orc_chunk_sizes.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, vp]
@@ -108,20 +129,42 @@ def stream_symbols(raw_bytes: int, S: int, j: int) -> int:
     return int(lib().orc_stream_symbols(raw_bytes, S, j))
 
 
-def encode_chunk(data, S: int, max_len: int = 11) -> np.ndarray:
+def tans_normalise(cnt) -> np.ndarray:
+    """Frequencies normalised to TANS_L by the format's rule."""
+    cnt = np.ascontiguousarray(cnt, dtype=np.uint64)
+    assert cnt.size == 256
+    q = np.zeros(256, dtype=np.uint16)
+    rc = lib().orc_tans_normalise(_ptr(cnt), _ptr(q))
+    if rc != 0:
+        raise ValueError(f"orc_tans_normalise failed: {rc}")
+    return q
+
+
+def tans_states(q):
+    """(value_of[x], number_of[x]) for the TANS_L states of normalised frequencies q."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    value_of = np.zeros(TANS_L, dtype=np.uint8)
+    number_of = np.zeros(TANS_L, dtype=np.uint16)
+    rc = lib().orc_tans_states(_ptr(q), _ptr(value_of), _ptr(number_of))
+    if rc != 0:
+        raise ValueError(f"orc_tans_states failed: {rc}")
+    return value_of, number_of
+
+
+def encode_chunk(data, S: int, max_len: int = 11, codec: int = HUFFMAN) -> np.ndarray:
     src = _bytes(data)
-    cap = int(lib().orc_huff_bound(src.size, S))
+    cap = int(lib().orc_payload_bound(src.size, S, codec))
     out = np.zeros(cap, dtype=np.uint8)
-    n = int(lib().orc_encode_chunk(_ptr(src), src.size, S, max_len, _ptr(out), cap))
+    n = int(lib().orc_encode_chunk_codec(_ptr(src), src.size, S, codec, max_len, _ptr(out), cap))
     if n == 0:
         raise ValueError("orc_encode_chunk failed")
     return out[:n].copy()
 
 
-def decode_chunk(payload, raw_bytes: int, S: int) -> np.ndarray:
+def decode_chunk(payload, raw_bytes: int, S: int, codec: int = HUFFMAN) -> np.ndarray:
     p = _bytes(payload)
     dst = np.zeros(raw_bytes, dtype=np.uint8)
-    rc = lib().orc_decode_chunk(_ptr(p), p.size, raw_bytes, S, _ptr(dst))
+    rc = lib().orc_decode_chunk_codec(_ptr(p), p.size, raw_bytes, S, codec, _ptr(dst))
     if rc != 0:
         raise ValueError(f"orc_decode_chunk failed: {rc}")
     return dst
@@ -134,6 +177,7 @@ class Compressed:
     raw_bytes: int
     chunk_bytes: int
     n_streams: int
+    codec: int = HUFFMAN
 
     @property
     def n_chunks(self) -> int:
@@ -175,14 +219,14 @@ def _run_ranges(fn, n: int, threads: int):
 
 
 def compress(data, chunk_bytes: int, n_streams: int, policy: int = ALL_HUFF, raw_fraction: float = 0.0,
-             block: int = 0, mask: Optional[np.ndarray] = None, threads: int = 1) -> Compressed:
+             block: int = 0, mask: Optional[np.ndarray] = None, threads: int = 1, codec: int = HUFFMAN) -> Compressed:
     """Whole-buffer compression.  `threads` only splits the chunk range; each chunk is coded alone."""
     L = lib()
     src = _bytes(data)
     n = src.size
     nc = int(L.orc_num_chunks(n, chunk_bytes))
     huff = np.zeros(nc, dtype=np.uint32)
-    _run_ranges(lambda a, b: L.orc_chunk_sizes(_ptr(src), n, chunk_bytes, n_streams, a, b, _ptr(huff)),
+    _run_ranges(lambda a, b: L.orc_chunk_sizes_codec(_ptr(src), n, chunk_bytes, n_streams, codec, a, b, _ptr(huff)),
                 nc, threads)
     is_raw = np.zeros(nc, dtype=np.uint8)
     m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
@@ -195,12 +239,13 @@ def compress(data, chunk_bytes: int, n_streams: int, policy: int = ALL_HUFF, raw
     table = np.zeros(nc, dtype=CHUNK_DTYPE)
     total = int(L.orc_layout(_ptr(huff), _ptr(is_raw), n, chunk_bytes, nc, _ptr(table)))
     blob = np.zeros(total, dtype=np.uint8)
-    _run_ranges(lambda a, b: L.orc_emit(_ptr(src), n, chunk_bytes, n_streams, _ptr(table), a, b, _ptr(blob)),
-                nc, threads)
-    return Compressed(blob, table, n, chunk_bytes, n_streams)
+    _run_ranges(lambda a, b: L.orc_emit_codec(_ptr(src), n, chunk_bytes, n_streams, codec, _ptr(table), a, b,
+                                              _ptr(blob)), nc, threads)
+    return Compressed(blob, table, n, chunk_bytes, n_streams, codec)
 
 
-def decompress(blob, table, chunk_bytes: int, n_streams: int, raw_bytes: int, threads: int = 1) -> np.ndarray:
+def decompress(blob, table, chunk_bytes: int, n_streams: int, raw_bytes: int, threads: int = 1,
+               codec: int = HUFFMAN) -> np.ndarray:
     L = lib()
     b = _bytes(blob)
     t = np.ascontiguousarray(table, dtype=CHUNK_DTYPE)
@@ -209,6 +254,6 @@ def decompress(blob, table, chunk_bytes: int, n_streams: int, raw_bytes: int, th
     if t.size == 0 or (sizes[:-1] != chunk_bytes).any() or (t.size - 1) * chunk_bytes + int(sizes[-1]) != raw_bytes:
         raise ValueError("the table does not describe raw_bytes bytes")
     dst = np.zeros(raw_bytes, dtype=np.uint8)
-    _run_ranges(lambda a, c: L.orc_decompress(_ptr(b), b.size, _ptr(t), a, c, chunk_bytes, n_streams, _ptr(dst)),
-                int(t.size), threads)
+    _run_ranges(lambda a, c: L.orc_decompress_codec(_ptr(b), b.size, _ptr(t), a, c, chunk_bytes, n_streams, codec,
+                                                    _ptr(dst)), int(t.size), threads)
     return dst

@@ -283,94 +283,324 @@ static uint32_t step_count(uint32_t raw_bytes, uint32_t S)
     return 2 * ((groups + S - 1) / S);
 }
 
-/* ------------------------------------------------------------------ chunk encode */
+/* ----------------------------------------------------------------------- tANS model */
 
 /*
- * Encode one chunk as a Huffman payload.  Returns the payload size (multiple of
- * 16) or 0 on error (capacity too small, bad arguments).  out may be NULL to
- * only measure.  max_len is 11 in the format; tests may pass less.
+ * The second coder of the container: tabled asymmetric numeral systems with L =
+ * 2048 states (the paper, Section 4.2, compares entropy coders and settles on
+ * ANS).  Only the front of the chunk header and what a sub-stream holds differ
+ * from the Huffman payload:
+ *
+ *   tANS payload
+ *     [0,384)          normalised frequency q[v] of byte value v, 12 bits each:
+ *                      bits 12v .. 12v+11 of the 384 bytes read as one bit string
+ *                      (bit i of the string = bit i%8 of byte i/8); the q add up
+ *                      to L; q[v] = 0 for an absent value
+ *     [384,384+2S)     the u16 per sub-stream, then set_off, then padding, as in
+ *                      the Huffman payload
+ *   states             position p = 0 .. L-1 in the list of byte values in
+ *                      ascending order, value v taking q[v] consecutive places, is
+ *                      state x = p with its 11 bits reversed.  The states of v
+ *                      taken in ascending x are numbered k = q[v] .. 2q[v]-1.
+ *                      A state with number k has nb = 11 - floor(log2 k) and
+ *                      base = (k << nb) - L.
+ *   sub-stream         bit fields, least significant bit first.  Decoder: x = the
+ *                      first 11 bits; for every symbol: the symbol is the value of
+ *                      state x, then x = base(x) + the next nb(x) bits.  Encoder:
+ *                      X = L; for the symbols from the last to the first, v being
+ *                      the symbol: nb = the smallest n with (X >> n) < 2q[v]; the
+ *                      symbol's field is the low nb bits of X; X = L + the state
+ *                      of v with number X >> nb.  The stream is X - L after the
+ *                      first symbol, then the fields in symbol order.  (So the
+ *                      decoder ends in state 0.)
+ *   placement rule     as for Huffman, c[j] counting every bit read; the 11 bits
+ *                      of the first state are read after the third and before the
+ *                      fourth carrying out of step 0.
+ *   frequencies        (what the compressor stores) with n the chunk's size:
+ *                      q[v] = max(1, floor(count[v]*L/n)) for present values.
+ *                      While the sum is below L: add one to the value with the
+ *                      largest count[v]/q[v] (as exact fractions; lower value
+ *                      among equals).  While the sum is above L: take one from
+ *                      the value with q[v] > 1 and the smallest
+ *                      count[v]/(q[v]-1) (lower value among equals).
  */
-uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, int max_len,
-                          uint8_t *out, uint64_t cap)
+#define ORC_CODEC_HUFFMAN 0
+#define ORC_CODEC_TANS 1
+#define ORC_TANS_BITS 11
+#define ORC_TANS_L 2048u
+
+/* Frequencies normalised to L by the rule above. */
+int orc_tans_normalise(const uint64_t *cnt, uint16_t *q)
+{
+    uint64_t n = 0, sum = 0;
+    for (int v = 0; v < 256; v++)
+        n += cnt[v];
+    if (n == 0)
+        return ORC_E_ARG;
+    for (int v = 0; v < 256; v++) {
+        uint64_t f = cnt[v] * ORC_TANS_L / n;
+        q[v] = cnt[v] == 0 ? 0 : (uint16_t)(f < 1 ? 1 : f);
+        sum += q[v];
+    }
+    while (sum < ORC_TANS_L) {
+        int best = -1;
+        for (int v = 0; v < 256; v++) {
+            if (cnt[v] == 0)
+                continue;
+            /* cnt[v]/q[v] > cnt[best]/q[best] */
+            if (best < 0 || cnt[v] * q[best] > cnt[best] * q[v])
+                best = v;
+        }
+        q[best]++;
+        sum++;
+    }
+    while (sum > ORC_TANS_L) {
+        int best = -1;
+        for (int v = 0; v < 256; v++) {
+            if (q[v] < 2)
+                continue;
+            /* cnt[v]/(q[v]-1) < cnt[best]/(q[best]-1) */
+            if (best < 0 || cnt[v] * (uint64_t)(q[best] - 1) < cnt[best] * (uint64_t)(q[v] - 1))
+                best = v;
+        }
+        if (best < 0)
+            return ORC_E_ARG; /* more than L present values cannot happen with 256 values */
+        q[best]--;
+        sum--;
+    }
+    return ORC_OK;
+}
+
+static unsigned reverse_bits(unsigned x, int bits)
+{
+    unsigned r = 0;
+    for (int i = 0; i < bits; i++)
+        if ((x >> i) & 1u)
+            r |= 1u << (bits - 1 - i);
+    return r;
+}
+
+/*
+ * The states: value_of[x] and number_of[x] for every state x.  Returns
+ * ORC_E_FORMAT when the frequencies do not add up to L.
+ */
+int orc_tans_states(const uint16_t *q, uint8_t *value_of, uint16_t *number_of)
+{
+    unsigned p = 0, next[256];
+    for (int v = 0; v < 256; v++)
+        p += q[v];
+    if (p != ORC_TANS_L)
+        return ORC_E_FORMAT;
+    p = 0;
+    for (int v = 0; v < 256; v++) {
+        for (unsigned i = 0; i < q[v]; i++, p++)
+            value_of[reverse_bits(p, ORC_TANS_BITS)] = (uint8_t)v;
+        next[v] = q[v];
+    }
+    for (unsigned x = 0; x < ORC_TANS_L; x++) /* ascending x: q[v], q[v]+1, ... */
+        number_of[x] = (uint16_t)next[value_of[x]]++;
+    return ORC_OK;
+}
+
+static int floor_log2(unsigned k)
+{
+    int l = 0;
+    while (k >> (l + 1))
+        l++;
+    return l;
+}
+
+/* ------------------------------------------------------------- one sub-stream, written */
+
+static void put_bit(uint8_t *st, uint64_t *bit, unsigned b)
+{
+    if (st && b)
+        st[*bit >> 3] |= (uint8_t)(1u << (*bit & 7));
+    (*bit)++;
+}
+
+/* The positions of the symbols of stream j, in order; returns how many. */
+static uint32_t stream_positions(uint32_t raw_bytes, uint32_t S, uint32_t j, uint32_t *pos)
+{
+    uint32_t groups = (raw_bytes + 15) / 16, n = 0;
+    for (uint32_t g = j; g < groups; g += S)
+        for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
+            pos[n++] = p;
+    return n;
+}
+
+/*
+ * Huffman: the codes of the stream's symbols from bit `bit` of st on, most
+ * significant code bit first.  used[k] = position after the first k symbols.
+ * st and used may be NULL (only the end position is wanted).
+ */
+static uint64_t huff_stream(const uint8_t *src, const uint32_t *pos, uint32_t n, const uint8_t *len,
+                            const uint16_t *code, uint8_t *st, uint64_t bit, uint64_t *used)
+{
+    if (used)
+        used[0] = bit;
+    for (uint32_t k = 0; k < n; k++) {
+        int l = len[src[pos[k]]];
+        unsigned c = code[src[pos[k]]];
+        for (int b = l - 1; b >= 0; b--)
+            put_bit(st, &bit, (c >> b) & 1u);
+        if (used)
+            used[k + 1] = bit;
+    }
+    return bit;
+}
+
+/*
+ * tANS: the first state and then the fields of the stream's symbols from bit
+ * `bit` of st on.  state_of[cum[v] + i] is the state of value v with number
+ * q[v] + i.  used[k] = position after the state and the first k fields.
+ * scratch holds n fields and n widths.
+ */
+static uint64_t tans_stream(const uint8_t *src, const uint32_t *pos, uint32_t n, const uint16_t *q,
+                            const uint16_t *cum, const uint16_t *state_of, uint16_t *field, uint8_t *width,
+                            uint8_t *st, uint64_t bit, uint64_t *used)
+{
+    if (n == 0) {
+        if (used)
+            used[0] = bit;
+        return bit;
+    }
+    unsigned X = ORC_TANS_L;
+    for (uint32_t k = n; k-- > 0;) {
+        unsigned v = src[pos[k]], nb = 0;
+        while ((X >> nb) >= 2u * q[v])
+            nb++;
+        field[k] = (uint16_t)(X & ((1u << nb) - 1u));
+        width[k] = (uint8_t)nb;
+        X = ORC_TANS_L + state_of[cum[v] + ((X >> nb) - q[v])];
+    }
+    for (int b = 0; b < ORC_TANS_BITS; b++)
+        put_bit(st, &bit, ((X - ORC_TANS_L) >> b) & 1u);
+    if (used)
+        used[0] = bit;
+    for (uint32_t k = 0; k < n; k++) {
+        for (unsigned b = 0; b < width[k]; b++)
+            put_bit(st, &bit, (field[k] >> b) & 1u);
+        if (used)
+            used[k + 1] = bit;
+    }
+    return bit;
+}
+
+/* ------------------------------------------------------------------ chunk encode */
+
+static uint32_t front_bytes(int codec) { return codec == ORC_CODEC_TANS ? 384u : 128u; }
+static uint32_t header_bytes_codec(uint32_t S, int codec)
+{
+    return (uint32_t)round_up(front_bytes(codec) + 2 * (uint64_t)S + 4 * (uint64_t)(S / set_width(S)), 16);
+}
+
+/* Upper bound of a coded payload of either kind: header + 11 bits a symbol + 11 bits and one
+ * partial block a stream (more than the padding of the sets can take). */
+uint64_t orc_payload_bound(uint32_t raw_bytes, uint32_t S, int codec)
+{
+    return round_up(header_bytes_codec(S, codec) + ((uint64_t)raw_bytes * 11 + 7) / 8 + (ORC_BLOCK + 2) * (uint64_t)S, 16);
+}
+
+/*
+ * Encode one chunk as a Huffman (codec 0) or tANS (codec 1) payload.  Returns the
+ * payload size (multiple of 16) or 0 on error (capacity too small, bad
+ * arguments).  out may be NULL to only measure.  max_len (Huffman only) is 11
+ * in the format; tests may pass less.
+ */
+uint64_t orc_encode_chunk_codec(const uint8_t *src, uint32_t raw_bytes, uint32_t S, int codec, int max_len,
+                                uint8_t *out, uint64_t cap)
 {
     uint64_t cnt[256];
     uint8_t len[256];
     uint16_t code[256];
+    uint16_t q[256], cum[257], number_of[ORC_TANS_L], state_of[ORC_TANS_L];
+    uint8_t value_of[ORC_TANS_L];
     if (raw_bytes == 0 || S == 0 || max_len > 11 || S % set_width(S) != 0)
         return 0;
-    orc_histogram(src, raw_bytes, cnt);
-    if (orc_code_lengths(cnt, max_len, len) != ORC_OK)
+    if (codec != ORC_CODEC_HUFFMAN && codec != ORC_CODEC_TANS)
         return 0;
-    orc_canonical_codes(len, code);
+    orc_histogram(src, raw_bytes, cnt);
+    if (codec == ORC_CODEC_HUFFMAN) {
+        if (orc_code_lengths(cnt, max_len, len) != ORC_OK)
+            return 0;
+        orc_canonical_codes(len, code);
+    } else {
+        if (orc_tans_normalise(cnt, q) != ORC_OK || orc_tans_states(q, value_of, number_of) != ORC_OK)
+            return 0;
+        cum[0] = 0;
+        for (int v = 0; v < 256; v++)
+            cum[v + 1] = (uint16_t)(cum[v] + q[v]);
+        for (unsigned x = 0; x < ORC_TANS_L; x++)
+            state_of[cum[value_of[x]] + (number_of[x] - q[value_of[x]])] = (uint16_t)x;
+    }
 
     /* size: header, then set by set the whole blocks of the streams (all but the first block of
      * each) and the first blocks cut down to the bytes that hold bits, the set padded to 16 */
-    uint32_t groups = (raw_bytes + 15) / 16;
-    uint32_t W = set_width(S), n_sets = S / W, hdr = header_bytes(S);
+    uint32_t W = set_width(S), n_sets = S / W, hdr = header_bytes_codec(S, codec), front = front_bytes(codec);
+    uint32_t max_sym = 16 * (((raw_bytes + 15) / 16 + S - 1) / S);
     uint64_t *nb = calloc(S, sizeof(uint64_t));
     uint64_t *hb = calloc(S, sizeof(uint64_t));
-    if (!nb || !hb) {
-        free(nb); free(hb);
+    uint32_t *pos_of = calloc(max_sym + 1, sizeof(uint32_t));
+    uint16_t *field = calloc(max_sym + 1, sizeof(uint16_t));
+    uint8_t *width = calloc(max_sym + 1, 1);
+    if (!nb || !hb || !pos_of || !field || !width) {
+        free(nb); free(hb); free(pos_of); free(field); free(width);
         return 0;
     }
     uint64_t total = hdr;
     for (uint32_t w = 0; w < n_sets; w++) {
         uint64_t area = 0;
         for (uint32_t j = w * W; j < (w + 1) * W; j++) {
-            uint64_t bits = 0;
-            for (uint32_t g = j; g < groups; g += S)
-                for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++)
-                    bits += len[src[p]];
+            uint32_t nsym = stream_positions(raw_bytes, S, j, pos_of);
+            uint64_t bits = codec == ORC_CODEC_HUFFMAN
+                                ? huff_stream(src, pos_of, nsym, len, code, NULL, 0, NULL)
+                                : tans_stream(src, pos_of, nsym, q, cum, state_of, field, width, NULL, 0, NULL);
             uint64_t bytes = (bits + 7) / 8;
             nb[j] = (bytes + ORC_BLOCK - 1) / ORC_BLOCK;
             hb[j] = nb[j] ? bytes - ORC_BLOCK * (nb[j] - 1) : 0;
-            if (nb[j] > 0xFFFu) { /* the header keeps 12 bits for it: chunks up to 1 MiB split 32 ways or more fit */
-                free(nb); free(hb);
-                return 0;
-            }
+            if (nb[j] > 0xFFFu) /* the header keeps 12 bits for it: chunks up to 1 MiB split 32 ways or more fit */
+                total = 0;
             area += nb[j] ? (nb[j] - 1) * ORC_BLOCK + hb[j] : 0;
         }
-        total += round_up(area, 16);
+        if (total)
+            total += round_up(area, 16);
     }
-    if (!out) {
-        free(nb); free(hb);
+    if (!out || total == 0 || cap < total) {
+        if (out)
+            total = 0;
+        free(nb); free(hb); free(pos_of); free(field); free(width);
         return total;
     }
-    if (cap < total) {
-        free(nb); free(hb);
-        return 0;
-    }
     memset(out, 0, total);
-    for (int v = 0; v < 256; v++)
-        out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
+    if (codec == ORC_CODEC_HUFFMAN) {
+        for (int v = 0; v < 256; v++)
+            out[v >> 1] |= (uint8_t)(len[v] << (4 * (v & 1)));
+    } else {
+        for (int v = 0; v < 256; v++)
+            for (int b = 0; b < 12; b++)
+                if ((q[v] >> b) & 1u)
+                    out[(12 * v + b) >> 3] |= (uint8_t)(1u << ((12 * v + b) & 7));
+    }
     for (uint32_t j = 0; j < S; j++) {
         uint16_t n16 = (uint16_t)(nb[j] | (hb[j] ? (hb[j] - 1) << 12 : 0));
-        memcpy(out + 128 + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
+        memcpy(out + front + 2 * (uint64_t)j, &n16, 2); /* little-endian host */
     }
 
-    /* every stream written out on its own from where its block 0 would start; used[j][k] = position of
-     * stream j after its first k symbols */
+    /* every stream written out on its own from where its block 0 would start; start[j] = its first
+     * position, used[j][k] = its position after its first k symbols (tANS: and the first state) */
     uint8_t **st = calloc(S, sizeof(uint8_t *));
     uint64_t **used = calloc(S, sizeof(uint64_t *));
+    uint64_t *start = calloc(S, sizeof(uint64_t));
     for (uint32_t j = 0; j < S; j++) {
-        uint32_t nsym = orc_stream_symbols(raw_bytes, S, j);
+        uint32_t nsym = stream_positions(raw_bytes, S, j, pos_of);
         st[j] = calloc(nb[j] * ORC_BLOCK + 1, 1);
         used[j] = calloc((size_t)nsym + 1, sizeof(uint64_t));
-        uint64_t bit = nb[j] ? 8 * (ORC_BLOCK - hb[j]) : 0; /* block 0 begins with bytes that do not exist */
-        uint32_t k = 0;
-        used[j][0] = bit;
-        for (uint32_t g = j; g < groups; g += S) {
-            for (uint32_t p = 16 * g; p < 16 * g + 16 && p < raw_bytes; p++) {
-                int l = len[src[p]];
-                unsigned c = code[src[p]];
-                for (int b = l - 1; b >= 0; b--) { /* most significant code bit first */
-                    if ((c >> b) & 1)
-                        st[j][bit >> 3] |= (uint8_t)(1u << (bit & 7));
-                    bit++;
-                }
-                used[j][++k] = bit;
-            }
-        }
+        start[j] = nb[j] ? 8 * (ORC_BLOCK - hb[j]) : 0; /* block 0 begins with bytes that do not exist */
+        if (codec == ORC_CODEC_HUFFMAN)
+            huff_stream(src, pos_of, nsym, len, code, st[j], start[j], used[j]);
+        else
+            tans_stream(src, pos_of, nsym, q, cum, state_of, field, width, st[j], start[j], used[j]);
     }
 
     /* set areas: the placement rule for the whole blocks, then the heads in stream order */
@@ -378,14 +608,15 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
     uint32_t steps = step_count(raw_bytes, S);
     for (uint32_t w = 0; w < n_sets; w++) {
         uint32_t off32 = (uint32_t)pos;
-        memcpy(out + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, &off32, 4);
+        memcpy(out + front + 2 * (uint64_t)S + 4 * (uint64_t)w, &off32, 4);
         uint64_t *f = calloc(W, sizeof(uint64_t));
         for (uint32_t h = 0; h < steps; h++) {
             int times = h == 0 ? 4 : 1;
             for (int t = 0; t < times; t++) {
                 for (uint32_t i = 0; i < W; i++) {
                     uint32_t j = w * W + i;
-                    uint64_t c = used[j][symbols_before_step(raw_bytes, S, j, h)];
+                    /* the first three times of step 0 come before anything of the stream is read */
+                    uint64_t c = (h == 0 && t < 3) ? start[j] : used[j][symbols_before_step(raw_bytes, S, j, h)];
                     if (f[i] < nb[j] && 128 * f[i] < c + ORC_LOOKAHEAD) {
                         if (f[i] > 0) { /* block 0 is not stored here */
                             memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
@@ -414,34 +645,56 @@ uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, in
         free(st[j]);
         free(used[j]);
     }
-    free(st); free(used); free(nb); free(hb);
+    free(st); free(used); free(start); free(nb); free(hb); free(pos_of); free(field); free(width);
     return total;
+}
+
+uint64_t orc_encode_chunk(const uint8_t *src, uint32_t raw_bytes, uint32_t S, int max_len,
+                          uint8_t *out, uint64_t cap)
+{
+    return orc_encode_chunk_codec(src, raw_bytes, S, ORC_CODEC_HUFFMAN, max_len, out, cap);
 }
 
 /* ------------------------------------------------------------------ chunk decode */
 
+/* One stream bit, or -1 when the stream has no block that holds it yet. */
+static int stream_bit(const uint8_t *st, uint64_t *bit, uint64_t blocks_held)
+{
+    if (*bit >= 8 * ORC_BLOCK * blocks_held)
+        return -1;
+    int b = (st[*bit >> 3] >> (*bit & 7)) & 1;
+    (*bit)++;
+    return b;
+}
+
 /*
- * Decode one Huffman payload bit by bit: grow the code one bit at a time and
- * stop when it falls inside the range of codes of its length.  Symbol counts
- * come from raw_bytes, never from the stream.  The blocks of a stream are
- * collected from its set's region by the placement rule as decoding goes.
+ * Decode one payload bit by bit.  Huffman: grow the code one bit at a time and
+ * stop when it falls inside the range of codes of its length.  tANS: walk the
+ * states.  Symbol counts come from raw_bytes, never from the stream.  The
+ * blocks of a stream are collected from its set's region by the placement rule
+ * as decoding goes.
  */
-int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_bytes, uint32_t S,
-                     uint8_t *dst)
+int orc_decode_chunk_codec(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_bytes, uint32_t S,
+                           int codec, uint8_t *dst)
 {
     uint8_t len[256];
     unsigned count[16] = {0}, first[16] = {0}, base[16] = {0};
     uint8_t sorted[256];
-    if (S == 0 || S % set_width(S) != 0 || comp_bytes < header_bytes(S))
+    uint16_t q[256], number_of[ORC_TANS_L];
+    uint8_t value_of[ORC_TANS_L];
+    if (codec != ORC_CODEC_HUFFMAN && codec != ORC_CODEC_TANS)
+        return ORC_E_ARG;
+    uint32_t front = front_bytes(codec);
+    if (S == 0 || S % set_width(S) != 0 || comp_bytes < header_bytes_codec(S, codec))
         return ORC_E_FORMAT;
-    for (int v = 0; v < 256; v++) {
-        len[v] = (payload[v >> 1] >> (4 * (v & 1))) & 15;
-        if (len[v] > 11)
-            return ORC_E_FORMAT;
-        count[len[v]]++;
-    }
-    count[0] = 0;
-    {
+    if (codec == ORC_CODEC_HUFFMAN) {
+        for (int v = 0; v < 256; v++) {
+            len[v] = (payload[v >> 1] >> (4 * (v & 1))) & 15;
+            if (len[v] > 11)
+                return ORC_E_FORMAT;
+            count[len[v]]++;
+        }
+        count[0] = 0;
         /* symbols in order of (length, byte value); first code and first rank of each length */
         int k = 0;
         unsigned code = 0;
@@ -456,6 +709,14 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         }
         if (k == 0)
             return ORC_E_FORMAT;
+    } else {
+        for (int v = 0; v < 256; v++) {
+            q[v] = 0;
+            for (int b = 0; b < 12; b++)
+                q[v] |= (uint16_t)(((payload[(12 * v + b) >> 3] >> ((12 * v + b) & 7)) & 1u) << b);
+        }
+        if (orc_tans_states(q, value_of, number_of) != ORC_OK)
+            return ORC_E_FORMAT;
     }
     uint32_t groups = (raw_bytes + 15) / 16;
     uint32_t W = set_width(S), n_sets = S / W;
@@ -463,20 +724,21 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
     int rc = ORC_OK;
     for (uint32_t w = 0; w < n_sets && rc == ORC_OK; w++) {
         uint32_t off32;
-        memcpy(&off32, payload + 128 + 2 * (uint64_t)S + 4 * (uint64_t)w, 4);
+        memcpy(&off32, payload + front + 2 * (uint64_t)S + 4 * (uint64_t)w, 4);
         uint64_t pos = off32;
         /* per stream of the set: blocks in all, bytes of the first one, where that one lies; its
-         * blocks collected so far, bits used */
+         * blocks collected so far, bits used; tANS: its state */
         uint8_t **st = calloc(W, sizeof(uint8_t *));
         uint64_t *f = calloc(W, sizeof(uint64_t));
         uint64_t *bit = calloc(W, sizeof(uint64_t));
         uint64_t *nb = calloc(W, sizeof(uint64_t));
         uint64_t *hb = calloc(W, sizeof(uint64_t));
         uint64_t *head = calloc(W, sizeof(uint64_t));
+        unsigned *x = calloc(W, sizeof(unsigned));
         uint64_t head_pos = off32;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
-            memcpy(&n16, payload + 128 + 2 * (uint64_t)(w * W + i), 2);
+            memcpy(&n16, payload + front + 2 * (uint64_t)(w * W + i), 2);
             nb[i] = n16 & 0xFFFu;
             hb[i] = nb[i] ? (n16 >> 12) + 1u : 0;
             st[i] = calloc((size_t)nb[i] * ORC_BLOCK + 1, 1);
@@ -492,6 +754,24 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
         for (uint32_t h = 0; h < steps && rc == ORC_OK; h++) {
             int times = h == 0 ? 4 : 1;
             for (int t = 0; t < times && rc == ORC_OK; t++) {
+                if (codec == ORC_CODEC_TANS && h == 0 && t == 3) {
+                    /* the first state of every stream that has symbols */
+                    for (uint32_t i = 0; i < W && rc == ORC_OK; i++) {
+                        if (w * W + i >= groups)
+                            continue;
+                        x[i] = 0;
+                        for (int b = 0; b < ORC_TANS_BITS; b++) {
+                            int v = stream_bit(st[i], &bit[i], f[i]);
+                            if (v < 0) {
+                                rc = ORC_E_FORMAT;
+                                break;
+                            }
+                            x[i] |= (unsigned)v << b;
+                        }
+                    }
+                    if (rc != ORC_OK)
+                        break;
+                }
                 for (uint32_t i = 0; i < W; i++) {
                     if (f[i] < nb[i] && 128 * f[i] < bit[i] + ORC_LOOKAHEAD) {
                         if (f[i] > 0) {
@@ -519,32 +799,58 @@ int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_b
                 if (hi > raw_bytes)
                     hi = raw_bytes;
                 for (uint32_t p = lo; p < hi && rc == ORC_OK; p++) {
-                    unsigned code = 0;
-                    int l = 0, found = 0;
-                    while (l < 11) {
-                        if (bit[i] >= 8 * ORC_BLOCK * f[i]) {
+                    if (codec == ORC_CODEC_HUFFMAN) {
+                        unsigned code = 0;
+                        int l = 0, found = 0;
+                        while (l < 11) {
+                            int v = stream_bit(st[i], &bit[i], f[i]);
+                            if (v < 0) {
+                                rc = ORC_E_FORMAT;
+                                break;
+                            }
+                            code = (code << 1) | (unsigned)v;
+                            l++;
+                            if (code >= first[l] && code - first[l] < count[l]) {
+                                dst[p] = sorted[base[l] + (code - first[l])];
+                                found = 1;
+                                break;
+                            }
+                        }
+                        if (!found)
                             rc = ORC_E_FORMAT;
-                            break;
+                    } else {
+                        unsigned k = number_of[x[i]];
+                        int n = ORC_TANS_BITS - floor_log2(k);
+                        unsigned field = 0;
+                        dst[p] = value_of[x[i]];
+                        for (int b = 0; b < n; b++) {
+                            int v = stream_bit(st[i], &bit[i], f[i]);
+                            if (v < 0) {
+                                rc = ORC_E_FORMAT;
+                                break;
+                            }
+                            field |= (unsigned)v << b;
                         }
-                        code = (code << 1) | ((st[i][bit[i] >> 3] >> (bit[i] & 7)) & 1u);
-                        bit[i]++;
-                        l++;
-                        if (code >= first[l] && code - first[l] < count[l]) {
-                            dst[p] = sorted[base[l] + (code - first[l])];
-                            found = 1;
-                            break;
-                        }
+                        x[i] = (k << n) - ORC_TANS_L + field;
                     }
-                    if (!found)
-                        rc = ORC_E_FORMAT;
                 }
             }
         }
+        if (codec == ORC_CODEC_TANS && rc == ORC_OK)
+            for (uint32_t i = 0; i < W; i++)
+                if (w * W + i < groups && x[i] != 0)
+                    rc = ORC_E_FORMAT; /* the encoder started from state 0 */
         for (uint32_t i = 0; i < W; i++)
             free(st[i]);
-        free(st); free(f); free(bit); free(nb); free(hb); free(head);
+        free(st); free(f); free(bit); free(nb); free(hb); free(head); free(x);
     }
     return rc;
+}
+
+int orc_decode_chunk(const uint8_t *payload, uint64_t comp_bytes, uint32_t raw_bytes, uint32_t S,
+                     uint8_t *dst)
+{
+    return orc_decode_chunk_codec(payload, comp_bytes, raw_bytes, S, ORC_CODEC_HUFFMAN, dst);
 }
 
 /* ------------------------------------------------------- whole-buffer operations */
@@ -558,17 +864,23 @@ static uint32_t chunk_raw_bytes(uint64_t n, uint32_t C, uint64_t k)
 
 uint64_t orc_num_chunks(uint64_t n, uint32_t C) { return (n + C - 1) / C; }
 
-/* Huffman payload size of chunks k0 <= k < k1 (no output written). */
-int orc_chunk_sizes(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, uint64_t k0, uint64_t k1,
-                    uint32_t *huff_bytes)
+/* Coded payload size of chunks k0 <= k < k1 (no output written). */
+int orc_chunk_sizes_codec(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, int codec, uint64_t k0,
+                          uint64_t k1, uint32_t *huff_bytes)
 {
     for (uint64_t k = k0; k < k1; k++) {
-        uint64_t sz = orc_encode_chunk(src + k * C, chunk_raw_bytes(n, C, k), S, 11, NULL, 0);
+        uint64_t sz = orc_encode_chunk_codec(src + k * C, chunk_raw_bytes(n, C, k), S, codec, 11, NULL, 0);
         if (sz == 0)
             return ORC_E_ARG;
         huff_bytes[k] = (uint32_t)sz;
     }
     return ORC_OK;
+}
+
+int orc_chunk_sizes(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, uint64_t k0, uint64_t k1,
+                    uint32_t *huff_bytes)
+{
+    return orc_chunk_sizes_codec(src, n, C, S, ORC_CODEC_HUFFMAN, k0, k1, huff_bytes);
 }
 
 /*
@@ -651,8 +963,8 @@ uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t 
 }
 
 /* Write the payloads of chunks k0 <= k < k1 at the offsets the table gives. */
-int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_chunk *table,
-             uint64_t k0, uint64_t k1, uint8_t *blob)
+int orc_emit_codec(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, int codec, const orc_chunk *table,
+                   uint64_t k0, uint64_t k1, uint8_t *blob)
 {
     for (uint64_t k = k0; k < k1; k++) {
         uint32_t raw = table[k].raw_bytes_flags & ~ORC_RAW_FLAG;
@@ -663,7 +975,7 @@ int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_c
             memset(out, 0, table[k].comp_bytes);
             memcpy(out, src + k * C, raw);
         } else {
-            uint64_t sz = orc_encode_chunk(src + k * C, raw, S, 11, out, table[k].comp_bytes);
+            uint64_t sz = orc_encode_chunk_codec(src + k * C, raw, S, codec, 11, out, table[k].comp_bytes);
             if (sz != table[k].comp_bytes)
                 return ORC_E_ARG;
         }
@@ -671,9 +983,15 @@ int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_c
     return ORC_OK;
 }
 
+int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_chunk *table,
+             uint64_t k0, uint64_t k1, uint8_t *blob)
+{
+    return orc_emit_codec(src, n, C, S, ORC_CODEC_HUFFMAN, table, k0, k1, blob);
+}
+
 /* Decode chunks k0 <= k < k1: chunk k lands at dst + k*C. */
-int orc_decompress(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *table, uint64_t k0,
-                   uint64_t k1, uint32_t C, uint32_t S, uint8_t *dst)
+int orc_decompress_codec(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *table, uint64_t k0,
+                         uint64_t k1, uint32_t C, uint32_t S, int codec, uint8_t *dst)
 {
     for (uint64_t k = k0; k < k1; k++) {
         uint32_t raw = table[k].raw_bytes_flags & ~ORC_RAW_FLAG;
@@ -687,10 +1005,16 @@ int orc_decompress(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *ta
                 return ORC_E_FORMAT;
             memcpy(dst + k * C, in, raw);
         } else {
-            int rc = orc_decode_chunk(in, table[k].comp_bytes, raw, S, dst + k * C);
+            int rc = orc_decode_chunk_codec(in, table[k].comp_bytes, raw, S, codec, dst + k * C);
             if (rc != ORC_OK)
                 return rc;
         }
     }
     return ORC_OK;
+}
+
+int orc_decompress(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *table, uint64_t k0,
+                   uint64_t k1, uint32_t C, uint32_t S, uint8_t *dst)
+{
+    return orc_decompress_codec(blob, blob_bytes, table, k0, k1, C, S, ORC_CODEC_HUFFMAN, dst);
 }

@@ -92,8 +92,23 @@ def dp_limited_cost(cnt: Sequence[int], max_len: int) -> int:
     return int(min(f[n]))
 
 
-def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
-    """Decode one Huffman payload by walking bits, from the written format alone.
+def tans_state_table(q: Sequence[int]):
+    """(value, number) of every state of a tANS payload, from the written format alone: the byte values in
+    ascending order take q[v] consecutive places each; place p is the state whose 11 bits are those of p
+    reversed; the states of a value, sorted, are numbered q[v], q[v] + 1, ..."""
+    assert sum(q) == 2048, "frequencies do not add up to the number of states"
+    table = [None] * 2048
+    place = 0
+    for v in range(256):
+        states = sorted(int(format(p, "011b")[::-1], 2) for p in range(place, place + q[v]))
+        for i, x in enumerate(states):
+            table[x] = (v, q[v] + i)
+        place += q[v]
+    return table
+
+
+def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False) -> bytes:
+    """Decode one Huffman (or, with `tans`, tANS) payload by walking bits, from the written format alone.
 
     header: 128 bytes of 4-bit code lengths (value v in nibble v&1 of byte v>>1), then S little-endian
     u16 (low 12 bits: blocks of the stream; top 4 bits: bytes of its first block that exist, less
@@ -106,27 +121,39 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
     blocks in stream order: before every half group (8 symbols) of all streams, each stream in turn that
     has blocks left and fewer than 320 placed bits beyond its position takes its next block (its own
     short first block, or the next of the area); the first such step runs four times.
+
+    tANS payload: the front of the header is 384 bytes, the 12-bit frequencies of the 256 byte values as one
+    little-endian bit string; a stream is the 11 bits of its first state and then, for every symbol, as many
+    bits as the state asks for (fields least significant bit first): the symbol is the state's value, and with
+    k the state's number and n = 11 - floor(log2 k) the next state is (k << n) - 2048 + the next n bits.  The
+    first state is read after the third and before the fourth run of the first step; the last state is 0.
     """
-    lens = [(payload[v >> 1] >> (4 * (v & 1))) & 15 for v in range(256)]
+    front = 384 if tans else 128
     book: Dict[tuple, int] = {}
-    code = 0
-    prev = 0
-    for l in range(1, 16):
-        for v in range(256):
-            if lens[v] == l:
-                if prev:
-                    code = (code + 1) << (l - prev)
-                book[(l, code)] = v
-                prev = l
+    table = None
+    if tans:
+        bits = int.from_bytes(payload[:384], "little")
+        table = tans_state_table([(bits >> (12 * v)) & 0xFFF for v in range(256)])
+    else:
+        lens = [(payload[v >> 1] >> (4 * (v & 1))) & 15 for v in range(256)]
+        code = 0
+        prev = 0
+        for l in range(1, 16):
+            for v in range(256):
+                if lens[v] == l:
+                    if prev:
+                        code = (code + 1) << (l - prev)
+                    book[(l, code)] = v
+                    prev = l
     W = min(S, 64)
-    field = [int.from_bytes(payload[128 + 2 * j:130 + 2 * j], "little") for j in range(S)]
+    field = [int.from_bytes(payload[front + 2 * j:front + 2 + 2 * j], "little") for j in range(S)]
     nb = [x & 0xFFF for x in field]
     first_bytes = [(x >> 12) + 1 if x & 0xFFF else 0 for x in field]
     out = bytearray(raw_bytes)
     groups = (raw_bytes + 15) // 16
     rounds = (groups + S - 1) // S
     for w in range(S // W):
-        o = 128 + 2 * S + 4 * w
+        o = front + 2 * S + 4 * w
         pos = int.from_bytes(payload[o:o + 4], "little")
         # the short first blocks start where the whole blocks of the set end
         whole = sum(nb[w * W + i] - 1 for i in range(W) if nb[w * W + i])
@@ -152,11 +179,25 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
                         n = first_bytes[j]
                         data[i] += bytes(16 - n) + payload[first_at[i]:first_at[i] + n]
 
+        def take(i, n):
+            """the next n bits of stream i, first bit least significant"""
+            v = 0
+            for b in range(n):
+                assert bit[i] < 8 * len(data[i]), "stream ran past its placed blocks"
+                v |= ((data[i][bit[i] >> 3] >> (bit[i] & 7)) & 1) << b
+                bit[i] += 1
+            return v
+
+        state = [0] * W
         for h in range(2 * rounds):
             step()
             if h == 0:
                 step()
                 step()
+                if tans:
+                    for i in range(W):
+                        if w * W + i < groups:
+                            state[i] = take(i, 11)
                 step()
             for i in range(W):
                 g = w * W + i + (h // 2) * S
@@ -164,17 +205,21 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int) -> bytes:
                     continue
                 lo = 16 * g + 8 * (h % 2)
                 for p in range(lo, min(lo + 8, raw_bytes)):
+                    if tans:
+                        out[p], k = table[state[i]]
+                        n = 11 - (k.bit_length() - 1)
+                        state[i] = (k << n) - 2048 + take(i, n)
+                        continue
                     l = 0
                     c = 0
                     while True:
-                        assert bit[i] < 8 * len(data[i]), "stream ran past its placed blocks"
-                        c = (c << 1) | ((data[i][bit[i] >> 3] >> (bit[i] & 7)) & 1)
-                        bit[i] += 1
+                        c = (c << 1) | take(i, 1)
                         l += 1
                         if (l, c) in book:
                             out[p] = book[(l, c)]
                             break
                         assert l < 15, "no code matched"
+        assert not any(state), "a tANS stream does not end in state 0"
         for i in range(W):
             assert len(data[i]) == 16 * nb[w * W + i], "blocks left unplaced"
         assert pos == first_at[0], "whole blocks left over in the area"
