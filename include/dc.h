@@ -80,15 +80,42 @@
  *                        128*f[j] - c[j] < DC_LOOKAHEAD_BITS, the stream takes block f[j] and
  *                        f[j] grows by one; block 0 is the stream's head and takes no place in
  *                        the region, any other block is placed next in the region.  Step 0 is
- *                        carried out four times in a row, every later step once.  (Three blocks
+ *                        carried out five times in a row, every later step once.  (Three blocks
  *                        are 384 - 8*pad[j] bits beyond the first position, hence the fourth
- *                        time.  Half a group uses at most 88 bits, so after every step a stream
+ *                        time; the fifth changes nothing in a Huffman payload, where c[j] is
+ *                        still 8*pad[j] <= 120 and a fifth block would start 512 bits on; in a
+ *                        tANS payload the first state is read before it.
+ *                        Half a group uses at most 88 bits, so after every step a stream
  *                        has at least DC_LOOKAHEAD_BITS bits placed beyond its position, or all
  *                        of its blocks; every block is placed by the last step.)
  *       codes            canonical: lengths from package-merge with limit 11
  *                        (leaves ordered by count then byte value, a leaf before
  *                        a package of equal weight); codes numbered in order of
  *                        (length, byte value), first code 0.
+ *   tANS payload (params.codec = DC_CODEC_TANS; the paper's Section 4.2 settles on ANS among the entropy
+ *   coders): the same container; only the front of the header and what a sub-stream holds differ.
+ *       [0,384)          normalised frequency q[v] of byte value v, 12 bits each: bits 12v .. 12v+11 of
+ *                        the 384 bytes read as one little-endian bit string; the q add up to L = 2048;
+ *                        q[v] = 0 for an absent value
+ *       [384,384+2S)     the u16 per sub-stream, then set_off, then padding, as in the Huffman payload
+ *       states           place p = 0 .. L-1 in the list of byte values in ascending order, value v taking
+ *                        q[v] consecutive places, is state x = p with its 11 bits reversed.  The states of v
+ *                        taken in ascending x are numbered k = q[v] .. 2q[v]-1.  A state numbered k has
+ *                        nb = 11 - floor(log2 k) and base = (k << nb) - L.
+ *       sub-stream       bit fields, least significant bit first.  Decoder: x = the first 11 bits; for every
+ *                        symbol: the symbol is the value of state x, then x = base(x) + the next nb(x) bits.
+ *                        Encoder: X = L; for the symbols from the last to the first, v being the symbol:
+ *                        nb = the smallest n with (X >> n) < 2q[v]; the symbol's field is the low nb bits of
+ *                        X; X = L + the state of v numbered X >> nb.  The stream is X - L after the first
+ *                        symbol, then the fields in symbol order; the decoder ends in state 0.  A field has
+ *                        at most 11 bits, like a code.
+ *       placement rule   as above, c[j] counting every bit read; the 11 bits of the first state are read
+ *                        after the fourth and before the fifth carrying out of step 0.
+ *       frequencies      what the compressor stores, n being the chunk's size: q[v] = max(1,
+ *                        floor(count[v]*L/n)) for present values; while the sum is below L, one more for the
+ *                        value with the largest count[v]/q[v] (exact fractions; the lower value among equals);
+ *                        while it is above L, one less for the value with q[v] > 1 and the smallest
+ *                        count[v]/(q[v]-1) (the lower value among equals).
  */
 #ifndef DC_MI355X_H
 #define DC_MI355X_H
@@ -112,6 +139,14 @@ extern "C" {
 #define DC_BLOCK_BYTES 16
 #define DC_LOOKAHEAD_BITS 320
 #define DC_MAX_MATRICES 16
+#define DC_TANS_STATE_BITS 11
+
+/* the coder of the chunks that are not raw (Section 4.2 of the paper compares entropy coders) */
+#define DC_CODEC_HUFFMAN 0 /* canonical Huffman, code length <= 11 */
+#define DC_CODEC_TANS 1    /* tabled asymmetric numeral systems, 2048 states; n_streams 64, 128 or 256;
+                              decoded by dc_decompress_chunks, written by dc_compress_chunks, checked by
+                              dc_validate; the fused calls and dc_compress_chunks_dev take Huffman blobs only
+                              (DC_E_ARG otherwise) */
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */
@@ -135,7 +170,7 @@ typedef struct {
     float raw_fraction;     /* DC_POLICY_RAW_FRACTION: share of chunks kept raw, 0..1; the count is
                                floor((double)raw_fraction * n_chunks + 0.5) of this 32-bit value */
     uint32_t block_chunks;  /* DC_POLICY_BLOCK_LAST: chunks per block, >= 1 */
-    uint32_t reserved;      /* 0 */
+    uint32_t codec;         /* DC_CODEC_*: the coder of the chunks that are not raw */
     const uint8_t *raw_mask; /* DC_POLICY_RAW_MASK: host array of n_chunks bytes, else NULL */
 } dc_params;
 

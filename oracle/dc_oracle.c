@@ -58,9 +58,13 @@
  * blocks of stream j placed so far: at a step, for j ascending over the set, if
  * f[j] < nb[j] and 128*f[j] - c[j] < 320 then the stream takes block f[j] and
  * f[j] grows by one: block 0 is the stream's head, any other block is the next
- * one in the area.  Step 0 is carried out four times, every later step once.
+ * one in the area.  Step 0 is carried out five times, every later step once.
  * (c[j] counts from the start of block 0: it is 8*pad[j] before the first
- * symbol, which is why a stream may need a fourth block before it starts.)
+ * symbol, which is why a stream may need a fourth block before it starts.  For
+ * a Huffman payload the fifth time changes nothing: c[j] is what it was, and a
+ * fifth block would have to start less than 320 bits beyond a position of at
+ * most 120.  In a tANS payload the first state is read between the fourth and
+ * the fifth time.)
  *
  * Every function is written for a reader to check by eye, not for speed:
  * one bit at a time, explicit item lists, no tables.
@@ -314,8 +318,8 @@ static uint32_t step_count(uint32_t raw_bytes, uint32_t S)
  *                      first symbol, then the fields in symbol order.  (So the
  *                      decoder ends in state 0.)
  *   placement rule     as for Huffman, c[j] counting every bit read; the 11 bits
- *                      of the first state are read after the third and before the
- *                      fourth carrying out of step 0.
+ *                      of the first state are read after the fourth and before the
+ *                      fifth carrying out of step 0.
  *   frequencies        (what the compressor stores) with n the chunk's size:
  *                      q[v] = max(1, floor(count[v]*L/n)) for present values.
  *                      While the sum is below L: add one to the value with the
@@ -611,12 +615,12 @@ uint64_t orc_encode_chunk_codec(const uint8_t *src, uint32_t raw_bytes, uint32_t
         memcpy(out + front + 2 * (uint64_t)S + 4 * (uint64_t)w, &off32, 4);
         uint64_t *f = calloc(W, sizeof(uint64_t));
         for (uint32_t h = 0; h < steps; h++) {
-            int times = h == 0 ? 4 : 1;
+            int times = h == 0 ? 5 : 1;
             for (int t = 0; t < times; t++) {
                 for (uint32_t i = 0; i < W; i++) {
                     uint32_t j = w * W + i;
-                    /* the first three times of step 0 come before anything of the stream is read */
-                    uint64_t c = (h == 0 && t < 3) ? start[j] : used[j][symbols_before_step(raw_bytes, S, j, h)];
+                    /* the first four times of step 0 come before anything of the stream is read */
+                    uint64_t c = (h == 0 && t < 4) ? start[j] : used[j][symbols_before_step(raw_bytes, S, j, h)];
                     if (f[i] < nb[j] && 128 * f[i] < c + ORC_LOOKAHEAD) {
                         if (f[i] > 0) { /* block 0 is not stored here */
                             memcpy(out + pos, st[j] + f[i] * ORC_BLOCK, ORC_BLOCK);
@@ -752,9 +756,9 @@ int orc_decode_chunk_codec(const uint8_t *payload, uint64_t comp_bytes, uint32_t
         if (head_pos > comp_bytes)
             rc = ORC_E_FORMAT;
         for (uint32_t h = 0; h < steps && rc == ORC_OK; h++) {
-            int times = h == 0 ? 4 : 1;
+            int times = h == 0 ? 5 : 1;
             for (int t = 0; t < times && rc == ORC_OK; t++) {
-                if (codec == ORC_CODEC_TANS && h == 0 && t == 3) {
+                if (codec == ORC_CODEC_TANS && h == 0 && t == 4) {
                     /* the first state of every stream that has symbols */
                     for (uint32_t i = 0; i < W && rc == ORC_OK; i++) {
                         if (w * W + i >= groups)

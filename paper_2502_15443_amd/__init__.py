@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     DCError,
     Params,
     CHUNK_DTYPE,
+    CODEC_HUFFMAN,
+    CODEC_TANS,
     POLICY_ALL_HUFF,
     POLICY_AUTO,
     POLICY_RAW_FRACTION,

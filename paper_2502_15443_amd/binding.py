@@ -16,6 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libdc_mi355x.so")
 
 POLICY_ALL_HUFF, POLICY_AUTO, POLICY_RAW_FRACTION, POLICY_RAW_MASK, POLICY_BLOCK_LAST = 0, 1, 2, 3, 4
+CODEC_HUFFMAN, CODEC_TANS = 0, 1
 CHUNK_RAW = 0x80000000
 CHUNK_DTYPE = np.dtype([("off", "<u8"), ("comp_bytes", "<u4"), ("raw_bytes_flags", "<u4")])
 
@@ -28,7 +29,7 @@ class DCError(RuntimeError):
 
 class _CParams(C.Structure):
     _fields_ = [("chunk_bytes", C.c_uint32), ("n_streams", C.c_uint32), ("policy", C.c_uint32),
-                ("raw_fraction", C.c_float), ("block_chunks", C.c_uint32), ("reserved", C.c_uint32),
+                ("raw_fraction", C.c_float), ("block_chunks", C.c_uint32), ("codec", C.c_uint32),
                 ("raw_mask", C.c_void_p)]
 
 
@@ -63,10 +64,11 @@ class Params:
     raw_fraction: float = 0.0
     block_chunks: int = 0
     raw_mask: Optional[np.ndarray] = None
+    codec: int = CODEC_HUFFMAN
 
     def _c(self) -> _CParams:
         p = _CParams(self.chunk_bytes, self.n_streams, self.policy, float(self.raw_fraction),
-                     self.block_chunks, 0, None)
+                     self.block_chunks, self.codec, None)
         if self.raw_mask is not None:
             self._mask_keepalive = np.ascontiguousarray(self.raw_mask, dtype=np.uint8)
             p.raw_mask = self._mask_keepalive.ctypes.data

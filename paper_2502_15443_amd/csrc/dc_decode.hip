@@ -102,6 +102,7 @@ struct Stream {
     uint32_t tk10;  // 1024 * (blocks asked for so far, f of the placement rule)
     uint32_t nb10;  // 1024 * (blocks of the stream)
     uint32_t pend;  // != 0: blk holds the block asked for at the last step, not yet in the ring
+    uint32_t x4;    // tANS: 4 * state = byte offset of the state's table entry
     u32x4 blk;
 };
 
@@ -170,7 +171,8 @@ __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring
 // shifts them down, so the ring holds block 0 with foreign bytes in front, and starts reading behind
 // them.  Then step 0 of the rule runs for the three further times (a stream takes a block while it
 // has blocks left and fewer than DC_LOOKAHEAD_BITS bits beyond its position 8*pad), and buf and next
-// are loaded.
+// are loaded.  (The step at the head of the decode loop is the fifth time; a tANS stream has read its
+// first state by then.)
 template <bool UNIFORM>
 __device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t field, uint32_t ring_lane)
 {
@@ -264,6 +266,40 @@ template <int N> __device__ __forceinline__ void symbols(Stream &s, uint32_t tbl
     s.state -= used & 0xFFu;
 }
 
+// tANS.  Table entry of a state = nb | value << 8 | (4 * base) << 16, where nb is the width of the state's
+// field and base the next state before the field is added; bits 4-7 are 0, so that the low five bits of an
+// entry (and of a sum of two) can be used as a field width or offset as they are, and the low byte of a sum
+// of three is the number of bits used.  The next N (2 or 3) symbols; at least 11*N bits are valid in buf.
+template <int N> __device__ __forceinline__ void tans_symbols(Stream &s, uint32_t tbl, uint32_t *e)
+{
+    const uint32_t lo = (uint32_t)s.buf, hi = (uint32_t)(s.buf >> 32);
+    e[0] = lds_load32(tbl + s.x4);
+    uint32_t x4 = (e[0] >> 16) + (__builtin_amdgcn_ubfe(lo, 0u, e[0]) << 2);
+    e[1] = lds_load32(tbl + x4);
+    x4 = (e[1] >> 16) + (__builtin_amdgcn_ubfe(lo, e[0], e[1]) << 2);
+    uint32_t used = e[0] + e[1];
+    if (N == 3) {
+        e[2] = lds_load32(tbl + x4);
+        x4 = (e[2] >> 16) + (__builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(hi, lo, used), 0u, e[2]) << 2);
+        used += e[2];
+    }
+    s.x4 = x4;
+    s.buf >>= (used & 63u);
+    s.state -= used & 0xFFu;
+}
+
+// One tANS symbol at a time, for the ragged end of a chunk.
+__device__ __forceinline__ uint32_t tans_decode1(Stream &s, uint32_t tbl, uint32_t ring_lane)
+{
+    refill(s, ring_lane);
+    const uint32_t e = lds_load32(tbl + s.x4);
+    const uint32_t nb = e & 15u;
+    s.x4 = (e >> 16) + (__builtin_amdgcn_ubfe((uint32_t)s.buf, 0u, nb) << 2);
+    s.buf >>= nb;
+    s.state -= nb;
+    return (e >> 8) & 0xFFu;
+}
+
 // bytes 1 of four entries -> one little-endian word of four symbols
 __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3)
 {
@@ -273,29 +309,29 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
 }
 
 // Symbols [8*HALF, 8*HALF + 8) of a group: three refills, 3 + 3 + 2 symbols.
-template <int HALF>
+template <int HALF, int CODEC>
 __device__ __forceinline__ void decode8(Stream &s, uint32_t tbl, uint32_t ring_lane, uint32_t out[4])
 {
     uint32_t e[8];
     refill33(s, ring_lane);
-    symbols<3>(s, tbl, e);
+    if (CODEC == DC_CODEC_TANS) tans_symbols<3>(s, tbl, e); else symbols<3>(s, tbl, e);
     refill33(s, ring_lane);
-    symbols<3>(s, tbl, e + 3);
+    if (CODEC == DC_CODEC_TANS) tans_symbols<3>(s, tbl, e + 3); else symbols<3>(s, tbl, e + 3);
     refill(s, ring_lane);
-    symbols<2>(s, tbl, e + 6);
+    if (CODEC == DC_CODEC_TANS) tans_symbols<2>(s, tbl, e + 6); else symbols<2>(s, tbl, e + 6);
     out[2 * HALF] = pack4(e[0], e[1], e[2], e[3]);
     out[2 * HALF + 1] = pack4(e[4], e[5], e[6], e[7]);
 }
 
 // One whole group of 16 symbols with the two steps of the placement rule that precede its halves.
-template <bool UNIFORM>
+template <bool UNIFORM, int CODEC = DC_CODEC_HUFFMAN>
 __device__ __forceinline__ void decode16(Stream &s, Region &rg, uint32_t tbl, uint32_t ring_lane, bool has_group,
                                          uint32_t out[4])
 {
     stream_step<UNIFORM>(s, rg, ring_lane);
-    if (has_group) decode8<0>(s, tbl, ring_lane, out);
+    if (has_group) decode8<0, CODEC>(s, tbl, ring_lane, out);
     stream_step<UNIFORM>(s, rg, ring_lane);
-    if (has_group) decode8<1>(s, tbl, ring_lane, out);
+    if (has_group) decode8<1, CODEC>(s, tbl, ring_lane, out);
 }
 
 // One symbol at a time, for the ragged end of a chunk.
@@ -332,7 +368,103 @@ __device__ __forceinline__ void word_to_scaled_f32(uint32_t w, float s, float f[
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-template <int S, int MODE>
+// The tANS table of a chunk (S >= 64: the workgroup's threads are the chunk's).  front: 4 KiB of LDS not yet
+// in use (the rings); table32: the 2048 entries; cumq: 256 words; wave_sum: one word per wave.  The threads
+// read the 256 frequencies, take their prefix sums (value v owns places cum[v] .. cum[v] + q[v] - 1) and mark
+// the first place of every value; then every thread takes 2048/threads consecutive places, finds each
+// place's value, and numbers the place among the places of its value by the order of the states (the places
+// with their 11 bits reversed): place p of a value with places a .. a+q-1 has as many states below it as there are
+// places p' of the value whose reversal is smaller, that is, for every set bit i of p, the places of the value
+// that agree with p below bit i and have bit i clear: (q + M - 1 - ((p - a - 2^i) mod M)) div M of them, M = 2^(i+1).
+// Returns false (for every thread alike) when the frequencies do not add up to 2048; nothing is decoded then.
+template <int S>
+__device__ __forceinline__ bool build_tans_table(const uint8_t *payload8, uint32_t ct, uint32_t lane, uint32_t wave,
+                                                 uint32_t *front, uint32_t *table32, uint32_t *cumq, uint32_t *wave_sum)
+{
+    using G = Geometry<S>;
+    constexpr int WAVES = G::kWaves;
+    constexpr int TPC = G::kThreadsPerChunk;
+    constexpr int SPL = G::kSymbolsPerLane;
+    constexpr int EPT = kTableEntries / TPC;
+    constexpr uint32_t L = kTableEntries;
+    uint16_t *marks = reinterpret_cast<uint16_t *>(front);
+    {
+        uint4 *z = reinterpret_cast<uint4 *>(marks);
+        for (uint32_t i = ct; i < kTableEntries * 2 / 16; i += TPC) z[i] = make_uint4(0, 0, 0, 0);
+    }
+    uint32_t q[SPL], mine = 0;
+#pragma unroll
+    for (int s = 0; s < SPL; s++) {
+        const uint32_t v = ct * SPL + s;
+        const uint8_t *g = payload8 + 3 * (v >> 1); // two 12-bit frequencies in three bytes
+        q[s] = (v & 1u) ? ((uint32_t)g[1] >> 4 | (uint32_t)g[2] << 4) : ((uint32_t)g[0] | ((uint32_t)g[1] & 15u) << 8);
+        mine += q[s];
+    }
+    const uint32_t incl = lanes_prefix_sum<false>(mine);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t cum = incl - mine, total = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; w++) {
+        const uint32_t c = wave_sum[w];
+        if ((uint32_t)w < wave) cum += c;
+        total += c;
+    }
+    if (total != L) return false;
+#pragma unroll
+    for (int s = 0; s < SPL; s++) {
+        const uint32_t v = ct * SPL + s;
+        cumq[v] = cum | q[s] << 16;
+        if (q[s]) {
+            marks[cum] = (uint16_t)(v + 1);
+            // also at the first place of every later wave that the value reaches into
+            for (uint32_t p = (cum / (L / WAVES) + 1) * (L / WAVES); p < cum + q[s]; p += L / WAVES) marks[p] = (uint16_t)(v + 1);
+        }
+        cum += q[s];
+    }
+    __syncthreads();
+    uint32_t w16[EPT / 2];
+    {
+        const uint4 *m4 = reinterpret_cast<const uint4 *>(marks + EPT * ct);
+#pragma unroll
+        for (int i = 0; i < EPT / 8; i++) {
+            const uint4 v = m4[i];
+            w16[4 * i] = v.x; w16[4 * i + 1] = v.y; w16[4 * i + 2] = v.z; w16[4 * i + 3] = v.w;
+        }
+    }
+    uint32_t tail = 0; // last mark among this thread's places
+#pragma unroll
+    for (int i = 0; i < EPT / 2; i++) {
+        const uint32_t lo = w16[i] & 0xFFFFu, hi = w16[i] >> 16;
+        tail = lo ? lo : tail;
+        tail = hi ? hi : tail;
+    }
+    uint32_t cur = lanes_last_nonzero_below<false>(tail);
+    const uint32_t tbl = lds_address(table32);
+#pragma unroll
+    for (int i = 0; i < EPT; i++) {
+        const uint32_t m = (i & 1) ? w16[i / 2] >> 16 : w16[i / 2] & 0xFFFFu;
+        cur = m ? m : cur;
+        const uint32_t v = cur - 1;
+        const uint32_t cq = cumq[v & 255u];
+        const uint32_t a = cq & 0xFFFFu, qv = cq >> 16;
+        const uint32_t p = EPT * ct + i, t = p - a;
+        uint32_t k = qv;
+#pragma unroll
+        for (int b = 0; b < kPeekBits; b++) {
+            const uint32_t M = 2u << b;
+            const uint32_t n = (qv + M - 1 - ((t - (1u << b)) & (M - 1))) >> (b + 1);
+            k += ((p >> b) & 1u) ? n : 0u;
+        }
+        const uint32_t nb = (uint32_t)__builtin_clz(k | 1u) - (31 - kPeekBits);
+        const uint32_t base = ((k << nb) - L) & (L - 1);
+        *(lds_u32 *)(uintptr_t)(tbl + 4 * (__brev(p) >> (32 - kPeekBits))) = nb | (v & 255u) << 8 | base << 18;
+    }
+    __syncthreads();
+    return true;
+}
+
+template <int S, int MODE, int CODEC>
 __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(DecodeArgs a)
 {
     using G = Geometry<S>;
@@ -341,14 +473,18 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr int WAVES = G::kWaves;
     constexpr int TPC = G::kThreadsPerChunk;
     constexpr int SPL = G::kSymbolsPerLane;
-    constexpr uint32_t kHeader = (128 + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
+    static_assert(CODEC == DC_CODEC_HUFFMAN || (S >= 64 && MODE == kModeI8), "tANS: whole workgroups, plain decode");
+    constexpr uint32_t kFront = CODEC == DC_CODEC_TANS ? 384 : 128; // code description at the start of a payload
+    constexpr uint32_t kHeader = (kFront + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
 
     // One block of LDS: the rings (4 KiB a wave, 4 KiB aligned) and then the decode tables.  While
     // the tables are built, before any ring is used, the front part holds the slot markers (one
     // u16 per table slot in code order, 4 KiB a chunk) and the start of the table part holds the
     // first codes of the lengths and the per-wave length counts.
     constexpr int kFrontWords = (WAVES > CPW ? WAVES : CPW) * kRingWords * 64;
-    __shared__ __attribute__((aligned(4096))) uint32_t lds_all[kFrontWords + CPW * kTableEntries / 2];
+    // (tANS: 2048 entries of 32 bits, then 256 words of (first place, frequency) and a word per wave)
+    constexpr int kTableWords = CODEC == DC_CODEC_TANS ? kTableEntries + 256 + 16 : CPW * kTableEntries / 2;
+    __shared__ __attribute__((aligned(4096))) uint32_t lds_all[kFrontWords + kTableWords];
     uint16_t(*lds_table)[kTableEntries] = reinterpret_cast<uint16_t(*)[kTableEntries]>(lds_all + kFrontWords);
     uint32_t(*lds_first)[16] = reinterpret_cast<uint32_t(*)[16]>(lds_all + kFrontWords); // [wave * CPW + sub][length]
     uint32_t(*lds_counts)[4] = reinterpret_cast<uint32_t(*)[4]>(lds_all + kFrontWords + 16 * WAVES * CPW); // [wave]
@@ -408,7 +544,13 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
 
     // The table is only needed where a chunk of the workgroup is Huffman coded; the condition is the
     // same for every thread that is still here, so the barriers inside are reached together.
-    const bool build_table = CPW == 1 ? huff : (bool)__any(huff);
+    const bool build_table = CODEC == DC_CODEC_TANS ? false : CPW == 1 ? huff : (bool)__any(huff);
+    if (CODEC == DC_CODEC_TANS) {
+        uint32_t *table32 = lds_all + kFrontWords;
+        if (!build_tans_table<S>(payload8, ct, lane, wave, lds_all, table32, table32 + kTableEntries,
+                                 table32 + kTableEntries + 256))
+            return;
+    }
 
     // ---- decode table.  Slot p of the table in code order (p = the next 11 stream bits, first bit
     // most significant) belongs to the code that covers p; codes in canonical order cover
@@ -542,9 +684,15 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         const uint64_t room = a.blob_bytes - ent.off - 20;
         rg.max_off = room < 0xFFFFFFE0ull ? (uint32_t)room : 0xFFFFFFE0u;
         rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
-        rg.next_block = payload[(128 + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
+        rg.next_block = payload[(kFront + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
         if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
-        stream_init<UNI>(st, rg, reinterpret_cast<const uint16_t *>(payload8)[64 + ct], ring_lane);
+        stream_init<UNI>(st, rg, reinterpret_cast<const uint16_t *>(payload8)[kFront / 2 + ct], ring_lane);
+        if (CODEC == DC_CODEC_TANS) {
+            // the first state: the stream's first 11 bits (at least 40 bits are valid after the set-up)
+            st.x4 = ((uint32_t)st.buf & (kTableEntries - 1)) << 2;
+            st.buf >>= kPeekBits;
+            st.state -= kPeekBits;
+        }
     }
 
     const uint32_t round_bytes = 16 * S;
@@ -555,7 +703,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos + ct * 16;
         for (uint32_t r = 0; r < full_rounds; r++) {
             uint32_t w[4];
-            decode16<UNI>(st, rg, tbl_addr, ring_lane, true, w);
+            decode16<UNI, CODEC>(st, rg, tbl_addr, ring_lane, true, w);
             store16_stream(d8 + (size_t)r * round_bytes, w[0], w[1], w[2], w[3]);
         }
         if (rem) {
@@ -564,9 +712,11 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
             uint8_t *d = d8 + (size_t)full_rounds * round_bytes;
             stream_step<UNI>(st, rg, ring_lane);
-            for (uint32_t i = 0; i < (n < 8 ? n : 8); i++) d[i] = (uint8_t)decode1(st, tbl_addr, ring_lane);
+            for (uint32_t i = 0; i < (n < 8 ? n : 8); i++)
+                d[i] = (uint8_t)(CODEC == DC_CODEC_TANS ? tans_decode1(st, tbl_addr, ring_lane) : decode1(st, tbl_addr, ring_lane));
             stream_step<UNI>(st, rg, ring_lane);
-            for (uint32_t i = 8; i < n; i++) d[i] = (uint8_t)decode1(st, tbl_addr, ring_lane);
+            for (uint32_t i = 8; i < n; i++)
+                d[i] = (uint8_t)(CODEC == DC_CODEC_TANS ? tans_decode1(st, tbl_addr, ring_lane) : decode1(st, tbl_addr, ring_lane));
         }
         return;
     }
@@ -860,6 +1010,8 @@ bool decode_params_ok(const dc_params *p)
 {
     if (!p) return false;
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
+    if (p->codec == DC_CODEC_TANS) return p->n_streams == 64 || p->n_streams == 128 || p->n_streams == 256;
+    if (p->codec != DC_CODEC_HUFFMAN) return false;
     return p->n_streams == 32 || p->n_streams == 64 || p->n_streams == 128 || p->n_streams == 256;
 }
 
@@ -867,7 +1019,21 @@ template <int S, int MODE> void launch_one(const DecodeArgs &a, hipStream_t stre
 {
     using G = Geometry<S>;
     const uint32_t grid = (uint32_t)((a.n_chunks + G::kChunksPerWave - 1) / G::kChunksPerWave);
-    hipLaunchKernelGGL((dc_decode_kernel<S, MODE>), dim3(grid), dim3(G::kThreads), 0, stream, a);
+    hipLaunchKernelGGL((dc_decode_kernel<S, MODE, DC_CODEC_HUFFMAN>), dim3(grid), dim3(G::kThreads), 0, stream, a);
+}
+
+// tANS payloads: plain decode, S >= 64
+int launch_tans(const DecodeArgs &a, uint32_t S, hipStream_t stream)
+{
+    if (a.n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
+    const uint32_t grid = (uint32_t)a.n_chunks;
+    switch (S) {
+    case 64: hipLaunchKernelGGL((dc_decode_kernel<64, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(64), 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((dc_decode_kernel<128, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(128), 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((dc_decode_kernel<256, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(256), 0, stream, a); break;
+    default: return DC_E_ARG;
+    }
+    return launch_status();
 }
 
 template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream_t stream)
@@ -910,6 +1076,7 @@ extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes
     a.chunk_bytes = params->chunk_bytes;
     a.dst = dst_dev;
     a.dst_cap = dst_cap;
+    if (params->codec == DC_CODEC_TANS) return launch_tans(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
     return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -922,6 +1089,7 @@ int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
     if (!decode_params_ok(params) || !blob_dev || !table_dev || !mats || n_mats == 0 || n_mats > DC_MAX_MATRICES ||
         n_chunks == 0 || blob_bytes < 16)
         return DC_E_ARG;
+    if (params->codec != DC_CODEC_HUFFMAN) return DC_E_ARG; // the fused calls decode Huffman payloads only
     if (!aligned16(blob_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
     a = DecodeArgs{};
     a.blob = blob_dev;

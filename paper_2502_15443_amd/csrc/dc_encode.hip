@@ -549,6 +549,7 @@ bool enc_params_ok(const dc_params *p)
     if (!p) return false;
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
     if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128 && p->n_streams != 256) return false;
+    if (p->codec != DC_CODEC_HUFFMAN) return false; // the device compressor writes Huffman payloads only
     if (p->policy == DC_POLICY_BLOCK_LAST) return p->block_chunks != 0;
     if (p->policy == DC_POLICY_RAW_FRACTION) return p->raw_fraction >= 0.0f && p->raw_fraction <= 1.0f;
     return p->policy == DC_POLICY_ALL_HUFF || p->policy == DC_POLICY_AUTO;

@@ -9,6 +9,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <memory>
 #include <thread>
 #include <vector>
 
@@ -51,6 +52,8 @@ bool params_ok(const dc_params *p)
     if (!p) return false;
     if (p->chunk_bytes < 16 || p->chunk_bytes > DC_MAX_CHUNK_BYTES || p->chunk_bytes % 16) return false;
     if (p->n_streams != 32 && p->n_streams != 64 && p->n_streams != 128 && p->n_streams != 256) return false;
+    if (p->codec != DC_CODEC_HUFFMAN && p->codec != DC_CODEC_TANS) return false;
+    if (p->codec == DC_CODEC_TANS && p->n_streams < 64) return false;
     return true;
 }
 
@@ -168,7 +171,107 @@ constexpr uint32_t kBlock = DC_BLOCK_BYTES;
 constexpr uint32_t kBlockBits = 8 * DC_BLOCK_BYTES;
 
 inline uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }
-inline uint32_t header_bytes(uint32_t S) { return (uint32_t)align_up(128 + 2ull * S + 4ull * (S / set_width(S)), 16); }
+// bytes of the code description at the start of a payload: 256 code lengths, or 256 frequencies of 12 bits
+inline uint32_t front_bytes(uint32_t codec) { return codec == DC_CODEC_TANS ? 384u : 128u; }
+inline uint32_t header_bytes(uint32_t S, uint32_t codec = DC_CODEC_HUFFMAN)
+{
+    return (uint32_t)align_up(front_bytes(codec) + 2ull * S + 4ull * (S / set_width(S)), 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// tANS model (the format text in dc.h: frequencies, states, numbers)
+// ---------------------------------------------------------------------------------------------
+
+constexpr uint32_t kTansBits = DC_TANS_STATE_BITS;
+constexpr uint32_t kTansL = 1u << kTansBits;
+
+struct TansModel {
+    uint16_t q[256];
+    uint16_t cum[257];
+    uint16_t state_of[kTansL]; // state of value v with number q[v] + i at cum[v] + i
+    uint8_t value_of[kTansL];
+    uint16_t number_of[kTansL];
+};
+
+// Frequencies normalised to 2048 by the rule of the format.
+void tans_normalise(const uint32_t cnt[256], uint32_t n, uint16_t q[256])
+{
+    uint32_t sum = 0;
+    for (int v = 0; v < 256; v++) {
+        const uint64_t f = (uint64_t)cnt[v] * kTansL / n;
+        q[v] = cnt[v] == 0 ? 0 : (uint16_t)std::max<uint64_t>(f, 1);
+        sum += q[v];
+    }
+    for (; sum < kTansL; sum++) {
+        int best = -1;
+        for (int v = 0; v < 256; v++)
+            if (cnt[v] && (best < 0 || (uint64_t)cnt[v] * q[best] > (uint64_t)cnt[best] * q[v])) best = v;
+        q[best]++;
+    }
+    for (; sum > kTansL; sum--) {
+        int best = -1;
+        for (int v = 0; v < 256; v++)
+            if (q[v] > 1 && (best < 0 || (uint64_t)cnt[v] * (q[best] - 1u) < (uint64_t)cnt[best] * (q[v] - 1u))) best = v;
+        q[best]--;
+    }
+}
+
+// States, numbers and the encoder's inverse from frequencies that add up to 2048.
+void tans_tables(TansModel &m)
+{
+    m.cum[0] = 0;
+    for (int v = 0; v < 256; v++) m.cum[v + 1] = (uint16_t)(m.cum[v] + m.q[v]);
+    for (int v = 0; v < 256; v++)
+        for (uint32_t p = m.cum[v]; p < m.cum[v + 1]; p++) m.value_of[bit_reverse(p, kTansBits)] = (uint8_t)v;
+    uint16_t next[256];
+    for (int v = 0; v < 256; v++) next[v] = m.q[v];
+    for (uint32_t x = 0; x < kTansL; x++) {
+        const uint8_t v = m.value_of[x];
+        m.number_of[x] = next[v];
+        m.state_of[m.cum[v] + (next[v] - m.q[v])] = (uint16_t)x;
+        next[v]++;
+    }
+}
+
+// One sub-stream coded backwards: field and width of every symbol (in symbol order), the first state, and the
+// stream's bits.  pos lists the positions of the stream's n symbols.
+struct TansStream {
+    std::vector<uint16_t> field;
+    std::vector<uint8_t> width;
+    uint32_t first_state = 0;
+    uint64_t bits = 0;
+};
+
+void tans_code_stream(const uint8_t *src, uint32_t raw, uint32_t S, uint32_t j, const TansModel &m, TansStream &ts)
+{
+    const uint32_t groups = (raw + 15) / 16;
+    uint32_t n = 0;
+    for (uint32_t g = j; g < groups; g += S) n += std::min(raw, 16 * g + 16) - 16 * g;
+    ts.field.resize(n);
+    ts.width.resize(n);
+    ts.bits = 0;
+    ts.first_state = 0;
+    if (n == 0) return;
+    uint32_t X = kTansL, k = n;
+    const uint32_t last_group = j + (groups - 1 - j) / S * S;
+    for (uint32_t g = last_group;; g -= S) {
+        const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16);
+        for (uint32_t p = hi; p-- > lo;) {
+            const uint8_t v = src[p];
+            const uint32_t q = m.q[v];
+            uint32_t nb = 0;
+            while ((X >> nb) >= 2 * q) nb++;
+            k--;
+            ts.field[k] = (uint16_t)(X & ((1u << nb) - 1u));
+            ts.width[k] = (uint8_t)nb;
+            ts.bits += nb;
+            X = kTansL + m.state_of[m.cum[v] + ((X >> nb) - q)];
+        }
+        if (g == j) break;
+    }
+    ts.first_state = X - kTansL;
+    ts.bits += kTansBits;
+}
 
 // Bits of every sub-stream of a chunk under a codebook.
 void stream_bits(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb, uint64_t *bits)
@@ -191,10 +294,10 @@ inline uint32_t blocks_of(uint64_t bits) { return (bytes_of(bits) + kBlock - 1) 
 inline uint32_t head_bytes_of(uint64_t bits) { return bits ? bytes_of(bits) - kBlock * (blocks_of(bits) - 1) : 0; }
 
 // Header, then per stream set the whole blocks, the short first blocks and padding to 16.
-uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
+uint32_t coded_payload_bytes(const uint64_t *bits, uint32_t S, uint32_t codec)
 {
     const uint32_t W = set_width(S);
-    uint64_t pos = header_bytes(S);
+    uint64_t pos = header_bytes(S, codec);
     for (uint32_t s0 = 0; s0 < S; s0 += W) {
         uint64_t area = 0;
         for (uint32_t j = s0; j < s0 + W; j++)
@@ -204,30 +307,43 @@ uint32_t huff_payload_bytes(const uint64_t *bits, uint32_t S)
     return (uint32_t)pos;
 }
 
-// Writes one Huffman payload; `out` has comp_bytes bytes.  Every sub-stream is first coded on its
+// Writes one coded payload; `out` has comp_bytes bytes.  Every sub-stream is first coded on its
 // own (whole blocks; the first one starts with the bytes that the format leaves out) while its position
 // before each step is noted; then, stream set by stream set, the blocks but the first of each stream are
 // placed in the order of the placement rule of the format and the short first blocks follow.
-void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook &cb,
-                        const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
+// cb is the codebook of a Huffman payload, tm the model of a tANS payload.
+void write_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook *cb, const TansModel *tm,
+                   const uint64_t *bits, uint8_t *out, uint32_t comp_bytes)
 {
+    const uint32_t codec = tm ? DC_CODEC_TANS : DC_CODEC_HUFFMAN;
+    const uint32_t front = front_bytes(codec);
     std::memset(out, 0, comp_bytes);
-    for (int v = 0; v < 256; v++) out[v >> 1] |= (uint8_t)(cb.len[v] << (4 * (v & 1)));
+    if (tm) {
+        for (int v = 0; v < 256; v += 2) { // two 12-bit frequencies in three bytes
+            const uint32_t two = tm->q[v] | (uint32_t)tm->q[v + 1] << 12;
+            out[3 * (v / 2)] = (uint8_t)two;
+            out[3 * (v / 2) + 1] = (uint8_t)(two >> 8);
+            out[3 * (v / 2) + 2] = (uint8_t)(two >> 16);
+        }
+    } else {
+        for (int v = 0; v < 256; v++) out[v >> 1] |= (uint8_t)(cb->len[v] << (4 * (v & 1)));
+    }
     const uint32_t groups = (raw + 15) / 16;
     const uint32_t rounds = (groups + S - 1) / S;
     const uint32_t steps = 2 * rounds;
     const uint32_t W = set_width(S);
 
-    std::vector<uint32_t> nb(S), first_block(S + 1, 0);
+    std::vector<uint32_t> nb(S), first_block(S + 1, 0), start(S);
     for (uint32_t j = 0; j < S; j++) {
         nb[j] = blocks_of(bits[j]);
         first_block[j + 1] = first_block[j] + nb[j];
         const uint32_t hb = head_bytes_of(bits[j]);
         const uint16_t n16 = (uint16_t)(nb[j] | (hb ? (hb - 1) << 12 : 0));
-        std::memcpy(out + 128 + 2 * j, &n16, 2);
+        std::memcpy(out + front + 2 * j, &n16, 2);
     }
     std::vector<uint8_t> coded((size_t)first_block[S] * kBlock + 8, 0);
     std::vector<uint32_t> used((size_t)S * (steps + 1), 0); // used[j*(steps+1) + h]: bits before step h
+    TansStream ts;
 
     for (uint32_t j = 0; j < S; j++) {
         uint32_t *w = reinterpret_cast<uint32_t *>(coded.data() + (size_t)first_block[j] * kBlock);
@@ -237,20 +353,32 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
         w += pad / 4;
         uint64_t acc = 0;
         int fill = 8 * (pad % 4);
-        uint32_t total = 8 * pad, h = 0;
+        uint32_t total = 8 * pad, h = 0, k = 0;
+        start[j] = total;
+        auto put = [&](uint32_t value, uint32_t n) {
+            acc |= (uint64_t)value << fill;
+            fill += n;
+            total += n;
+            if (fill >= 32) {
+                *w++ = (uint32_t)acc;
+                acc >>= 32;
+                fill -= 32;
+            }
+        };
+        if (tm) {
+            tans_code_stream(src, raw, S, j, *tm, ts);
+            if (!ts.field.empty()) put(ts.first_state, kTansBits);
+        }
         for (uint32_t g = j; g < groups; g += S) {
             const uint32_t lo = 16 * g, hi = std::min(raw, lo + 16), mid = std::min(hi, lo + 8);
             u[h++] = total;
             for (uint32_t p = lo; p < hi; p++) {
                 if (p == mid) u[h++] = total;
-                const uint8_t v = src[p];
-                acc |= (uint64_t)cb.rev[v] << fill;
-                fill += cb.len[v];
-                total += cb.len[v];
-                if (fill >= 32) {
-                    *w++ = (uint32_t)acc;
-                    acc >>= 32;
-                    fill -= 32;
+                if (tm) {
+                    put(ts.field[k], ts.width[k]);
+                    k++;
+                } else {
+                    put(cb->rev[src[p]], cb->len[src[p]]);
                 }
             }
             if (mid == hi) u[h++] = total;
@@ -259,16 +387,18 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
         if (fill > 0) *w++ = (uint32_t)acc;
     }
 
-    uint32_t pos = header_bytes(S);
+    uint32_t pos = header_bytes(S, codec);
     std::vector<uint32_t> f(W);
     for (uint32_t s0 = 0, w = 0; s0 < S; s0 += W, w++) {
-        std::memcpy(out + 128 + 2 * S + 4 * w, &pos, 4);
+        std::memcpy(out + front + 2 * S + 4 * w, &pos, 4);
         std::fill(f.begin(), f.end(), 0);
         for (uint32_t h = 0; h < steps; h++) {
-            for (int t = (h == 0 ? 4 : 1); t > 0; t--) {
+            for (int t = 0; t < (h == 0 ? 5 : 1); t++) {
                 for (uint32_t i = 0; i < W; i++) {
                     const uint32_t j = s0 + i;
-                    if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < (uint64_t)used[(size_t)j * (steps + 1) + h] + DC_LOOKAHEAD_BITS) {
+                    // the first four times of step 0 come before anything of the stream is read
+                    const uint64_t c = (h == 0 && t < 4) ? start[j] : used[(size_t)j * (steps + 1) + h];
+                    if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < c + DC_LOOKAHEAD_BITS) {
                         if (f[i] > 0) { // block 0 goes to the heads
                             std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
                             pos += kBlock;
@@ -294,7 +424,7 @@ void write_huff_payload(const uint8_t *src, uint32_t raw, uint32_t S, const Code
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.2 (gfx950; canonical Huffman L11, block-interleaved sub-streams, short first blocks)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.3 (gfx950; canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks)"; }
 
 extern "C" const char *dc_strerror(int code)
 {
@@ -444,7 +574,9 @@ extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, ui
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
     const uint64_t nc = (raw_bytes + C - 1) / C;
     // worst Huffman payload: header, 11 bits a byte, one partial block per stream
-    const uint64_t per_chunk = align_up(header_bytes(S) + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + (uint64_t)kBlock * S, 16);
+    // (tANS: 11 bits a byte too, and 11 bits of state per stream)
+    const uint64_t per_chunk =
+        align_up(header_bytes(S, params->codec) + ((uint64_t)C * DC_MAX_CODE_LEN + 7) / 8 + (uint64_t)(kBlock + 2) * S, 16);
     if (max_blob_bytes) *max_blob_bytes = nc * per_chunk + DC_BLOB_TAIL_BYTES;
     if (n_chunks) *n_chunks = nc;
     return DC_OK;
@@ -465,18 +597,32 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
     if (policy == DC_POLICY_RAW_FRACTION && !(params->raw_fraction >= 0.0f && params->raw_fraction <= 1.0f))
         return DC_E_ARG;
 
-    // pass 1: codebook, per-stream bits and Huffman payload size of every chunk
-    std::vector<CodeBook> books(nc);
+    // pass 1: codebook (or frequencies), per-stream bits and coded payload size of every chunk
+    const bool tans = params->codec == DC_CODEC_TANS;
+    std::vector<CodeBook> books(tans ? 0 : nc);
+    std::vector<uint16_t> freqs(tans ? nc * 256 : 0);
     std::vector<uint64_t> bits(nc * S);
     std::vector<uint32_t> huff(nc);
     parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
         uint32_t cnt[256];
+        std::unique_ptr<TansModel> tm(tans ? new TansModel : nullptr);
+        TansStream ts;
         for (uint64_t k = k0; k < k1; k++) {
             const uint32_t raw = chunk_len(raw_bytes, C, k);
             histogram256(src + k * C, raw, cnt);
-            make_codebook(cnt, books[k]);
-            stream_bits(src + k * C, raw, S, books[k], &bits[k * S]);
-            huff[k] = huff_payload_bytes(&bits[k * S], S);
+            if (tans) {
+                tans_normalise(cnt, raw, tm->q);
+                tans_tables(*tm);
+                std::memcpy(&freqs[k * 256], tm->q, sizeof(tm->q));
+                for (uint32_t j = 0; j < S; j++) {
+                    tans_code_stream(src + k * C, raw, S, j, *tm, ts);
+                    bits[k * S + j] = ts.bits;
+                }
+            } else {
+                make_codebook(cnt, books[k]);
+                stream_bits(src + k * C, raw, S, books[k], &bits[k * S]);
+            }
+            huff[k] = coded_payload_bytes(&bits[k * S], S, params->codec);
         }
     });
 
@@ -526,14 +672,19 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
 
     // pass 2: emit
     parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
+        std::unique_ptr<TansModel> tm(tans ? new TansModel : nullptr);
         for (uint64_t k = k0; k < k1; k++) {
             const uint32_t raw = chunk_len(raw_bytes, C, k);
             uint8_t *out = blob + table[k].off;
             if (is_raw[k]) {
                 std::memcpy(out, src + k * C, raw);
                 std::memset(out + raw, 0, table[k].comp_bytes - raw);
+            } else if (tans) {
+                std::memcpy(tm->q, &freqs[k * 256], sizeof(tm->q));
+                tans_tables(*tm);
+                write_payload(src + k * C, raw, S, nullptr, tm.get(), &bits[k * S], out, table[k].comp_bytes);
             } else {
-                write_huff_payload(src + k * C, raw, S, books[k], &bits[k * S], out, table[k].comp_bytes);
+                write_payload(src + k * C, raw, S, &books[k], nullptr, &bits[k * S], out, table[k].comp_bytes);
             }
         }
     });
@@ -542,30 +693,47 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
 
 namespace {
 
-// Checks one Huffman payload completely: header, code completeness, region extents, and that each
-// sub-stream decodes its symbol count from the blocks the placement rule has given it by then.
-bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
+// Checks one coded payload completely: header, code completeness (Huffman) or frequencies that add up
+// (tANS), region extents, and that each sub-stream decodes its symbol count from the blocks the placement
+// rule has given it by then; a tANS stream must also end in state 0.
+bool coded_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S, uint32_t codec)
 {
-    const uint32_t hdr = header_bytes(S);
+    const bool tans = codec == DC_CODEC_TANS;
+    const uint32_t front = front_bytes(codec);
+    const uint32_t hdr = header_bytes(S, codec);
     const uint32_t W = set_width(S), n_sets = S / W;
     if (comp < hdr) return false;
-    uint8_t len[256];
-    uint32_t per_len[16] = {0};
-    int used = 0;
-    for (int v = 0; v < 256; v++) {
-        len[v] = (p[v >> 1] >> (4 * (v & 1))) & 15;
-        if (len[v] > DC_MAX_CODE_LEN) return false;
-        if (len[v]) { per_len[len[v]]++; used++; }
-    }
-    if (used == 0) return false;
-    uint32_t kraft = 0;
-    for (int l = 1; l <= DC_MAX_CODE_LEN; l++) kraft += per_len[l] << (DC_MAX_CODE_LEN - l);
-    if (used == 1) { if (per_len[1] != 1) return false; }
-    else if (kraft != (1u << DC_MAX_CODE_LEN)) return false;
 
-    // length of the code that starts with the next 11 stream bits
-    std::vector<uint8_t> peek_len(1u << DC_MAX_CODE_LEN, 0);
-    {
+    // Huffman: length of the code that starts with the next 11 stream bits
+    std::vector<uint8_t> peek_len;
+    std::unique_ptr<TansModel> tm;
+    if (tans) {
+        tm.reset(new TansModel);
+        uint32_t sum = 0;
+        for (int v = 0; v < 256; v += 2) {
+            const uint32_t two = p[3 * (v / 2)] | (uint32_t)p[3 * (v / 2) + 1] << 8 | (uint32_t)p[3 * (v / 2) + 2] << 16;
+            tm->q[v] = (uint16_t)(two & 0xFFFu);
+            tm->q[v + 1] = (uint16_t)(two >> 12);
+            sum += tm->q[v] + tm->q[v + 1];
+            if (sum > kTansL) return false;
+        }
+        if (sum != kTansL) return false;
+        tans_tables(*tm);
+    } else {
+        uint8_t len[256];
+        uint32_t per_len[16] = {0};
+        int used = 0;
+        for (int v = 0; v < 256; v++) {
+            len[v] = (p[v >> 1] >> (4 * (v & 1))) & 15;
+            if (len[v] > DC_MAX_CODE_LEN) return false;
+            if (len[v]) { per_len[len[v]]++; used++; }
+        }
+        if (used == 0) return false;
+        uint32_t kraft = 0;
+        for (int l = 1; l <= DC_MAX_CODE_LEN; l++) kraft += per_len[l] << (DC_MAX_CODE_LEN - l);
+        if (used == 1) { if (per_len[1] != 1) return false; }
+        else if (kraft != (1u << DC_MAX_CODE_LEN)) return false;
+        peek_len.assign(1u << DC_MAX_CODE_LEN, 0);
         uint32_t next[16], code = 0;
         per_len[0] = 0;
         for (int l = 1; l <= DC_MAX_CODE_LEN; l++) { code = (code + per_len[l - 1]) << 1; next[l] = code; }
@@ -576,7 +744,7 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
             for (uint32_t i = r; i < (1u << DC_MAX_CODE_LEN); i += 1u << l) peek_len[i] = (uint8_t)l;
         }
     }
-    for (uint32_t i = 128 + 2 * S + 4 * n_sets; i < hdr; i++)
+    for (uint32_t i = front + 2 * S + 4 * n_sets; i < hdr; i++)
         if (p[i]) return false;
 
     const uint32_t groups = (raw + 15) / 16;
@@ -584,15 +752,15 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
     uint32_t region = hdr;
     for (uint32_t w = 0; w < n_sets; w++) {
         uint32_t off;
-        std::memcpy(&off, p + 128 + 2 * S + 4 * w, 4);
+        std::memcpy(&off, p + front + 2 * S + 4 * w, 4);
         if (off != region) return false;
-        std::vector<uint32_t> nb(W), hb(W), head_at(W), f(W, 0);
+        std::vector<uint32_t> nb(W), hb(W), head_at(W), f(W, 0), state(W, 0);
         std::vector<uint64_t> bit(W, 0), have(W, 0);
         std::vector<std::vector<uint32_t>> where(W); // payload offset of each block taken
         uint64_t whole = 0, head_bytes = 0;
         for (uint32_t i = 0; i < W; i++) {
             uint16_t n16;
-            std::memcpy(&n16, p + 128 + 2 * (w * W + i), 2);
+            std::memcpy(&n16, p + front + 2 * (w * W + i), 2);
             nb[i] = n16 & 0xFFFu;
             hb[i] = nb[i] ? (n16 >> 12) + 1u : 0;
             if (nb[i] == 0 && n16 != 0) return false;
@@ -614,8 +782,28 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
         }
         const uint32_t heads_begin = region + (uint32_t)(whole * kBlock);
         region += (uint32_t)area;
+        // the next n <= 11 bits of stream i (bits the stream does not have yet read as 0; the caller checks)
+        auto window = [&](uint32_t i, int n) {
+            uint32_t v = 0;
+            for (int b = 0; b < n; b++) {
+                const uint64_t x = bit[i] + b;
+                if (x < have[i]) {
+                    const uint32_t byte = where[i][x / kBlockBits] + (uint32_t)(x % kBlockBits) / 8;
+                    v |= (uint32_t)((p[byte] >> (x & 7)) & 1u) << b;
+                }
+            }
+            return v;
+        };
         for (uint32_t h = 0; h < steps; h++) {
-            for (int t = (h == 0 ? 4 : 1); t > 0; t--)
+            for (int t = 0; t < (h == 0 ? 5 : 1); t++) {
+                if (tans && h == 0 && t == 4) { // the first states are read before the fifth time
+                    for (uint32_t i = 0; i < W; i++) {
+                        if (w * W + i >= groups) continue;
+                        if (bit[i] + kTansBits > have[i]) return false;
+                        state[i] = window(i, kTansBits);
+                        bit[i] += kTansBits;
+                    }
+                }
                 for (uint32_t i = 0; i < W; i++)
                     if (f[i] < nb[i] && (uint64_t)kBlockBits * f[i] < bit[i] + DC_LOOKAHEAD_BITS) {
                         if (f[i] > 0) {
@@ -628,28 +816,29 @@ bool huff_payload_ok(const uint8_t *p, uint32_t comp, uint32_t raw, uint32_t S)
                         have[i] += kBlockBits;
                         f[i]++;
                     }
+            }
             for (uint32_t i = 0; i < W; i++) {
                 const uint32_t g = w * W + i + (h / 2) * S;
                 if (g >= groups) continue;
                 const uint32_t lo = 16 * g + 8 * (h & 1);
                 const uint32_t hi = std::min(raw, lo + 8);
                 for (uint32_t q = lo; q < hi; q++) {
-                    uint32_t window = 0;
-                    for (int b = 0; b < DC_MAX_CODE_LEN; b++) {
-                        const uint64_t x = bit[i] + b;
-                        if (x < have[i]) {
-                            const uint32_t byte = where[i][x / kBlockBits] + (uint32_t)(x % kBlockBits) / 8;
-                            window |= (uint32_t)((p[byte] >> (x & 7)) & 1u) << b;
-                        }
+                    if (tans) {
+                        const uint32_t k = tm->number_of[state[i]];
+                        const int n = (int)kTansBits - (31 - __builtin_clz(k));
+                        if (bit[i] + n > have[i]) return false;
+                        state[i] = (k << n) - kTansL + window(i, n);
+                        bit[i] += n;
+                    } else {
+                        const int l = peek_len[window(i, DC_MAX_CODE_LEN)];
+                        if (l == 0 || bit[i] + l > have[i]) return false;
+                        bit[i] += l;
                     }
-                    const int l = peek_len[window];
-                    if (l == 0 || bit[i] + l > have[i]) return false;
-                    bit[i] += l;
                 }
             }
         }
         for (uint32_t i = 0; i < W; i++)
-            if (f[i] != nb[i] || (bit[i] + 7) / 8 != (uint64_t)kBlock * nb[i]) return false;
+            if (f[i] != nb[i] || (bit[i] + 7) / 8 != (uint64_t)kBlock * nb[i] || state[i] != 0) return false;
         if (pos != heads_begin) return false;
     }
     return region == comp;
@@ -682,7 +871,7 @@ extern "C" int dc_validate(const uint8_t *blob, uint64_t blob_bytes, const dc_ch
             if (ok && k == 0) ok = e.off == 0;
             if (ok) {
                 if (e.raw_bytes_flags & DC_CHUNK_RAW) ok = e.comp_bytes == align_up(raw, 16);
-                else ok = huff_payload_ok(blob + e.off, e.comp_bytes, raw, S);
+                else ok = coded_payload_ok(blob + e.off, e.comp_bytes, raw, S, params->codec);
             }
             if (!ok) {
                 uint64_t cur = first_bad.load();

@@ -120,13 +120,13 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
     16-byte blocks of its streams, all but the first of each, in request order, then the short first
     blocks in stream order: before every half group (8 symbols) of all streams, each stream in turn that
     has blocks left and fewer than 320 placed bits beyond its position takes its next block (its own
-    short first block, or the next of the area); the first such step runs four times.
+    short first block, or the next of the area); the first such step runs five times.
 
     tANS payload: the front of the header is 384 bytes, the 12-bit frequencies of the 256 byte values as one
     little-endian bit string; a stream is the 11 bits of its first state and then, for every symbol, as many
     bits as the state asks for (fields least significant bit first): the symbol is the state's value, and with
     k the state's number and n = 11 - floor(log2 k) the next state is (k << n) - 2048 + the next n bits.  The
-    first state is read after the third and before the fourth run of the first step; the last state is 0.
+    first state is read after the fourth and before the fifth run of the first step; the last state is 0.
     """
     front = 384 if tans else 128
     book: Dict[tuple, int] = {}
@@ -192,6 +192,7 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
         for h in range(2 * rounds):
             step()
             if h == 0:
+                step()
                 step()
                 step()
                 if tans:
