@@ -481,6 +481,30 @@ def main() -> int:
             del b2, t2, l2
         extras["n_streams_sweep"] = sweep_s
 
+        # the container's second coder (tANS, 2048 states; the paper settles on ANS in Section 4.2) on the same
+        # layer: at the headline's shape, and with few streams and big chunks, where its shorter streams count
+        tans_rows = []
+        for c2, s2 in ((C, S), (262144, 64), (262144, 256)):
+            row = {"chunk_bytes": c2, "n_streams": s2}
+            for name, codec in (("huffman", dc.CODEC_HUFFMAN), ("tans", dc.CODEC_TANS)):
+                if codec == dc.CODEC_HUFFMAN and (c2, s2) == (C, S):
+                    row[name] = {"decoded_GBps": round(decoded_gbps, 1), "compression_ratio": round(ratio, 5)}
+                    continue
+                p2 = dc.Params(c2, s2, codec=codec)
+                l2 = build_layer("llama7b", 0, True, p2, dc, synth)
+                b2 = [up(l2["blob"]) for _ in range(nbuf)]
+                t2 = up(l2["table"])
+                ms2, _ = time_launches(
+                    torch, lambda i: dc.decompress_chunks(b2[i % nbuf], l2["blob"].size, t2, len(l2["table"]), p2,
+                                                          dsts[i % nbuf], raw_bytes, stream), 200, 20)
+                good = bool(torch.equal(dsts[(200 + 20 - 1) % nbuf].cpu(), torch.from_numpy(l2["q"].view(np.uint8))))
+                row[name] = {"decoded_GBps": round(raw_bytes / ms2 / 1e6, 1),
+                             "compression_ratio": round(raw_bytes / (l2["blob"].size + l2["table"].nbytes), 5),
+                             "exact": good}
+                del b2, t2, l2
+            tans_rows.append(row)
+        extras["tans_against_huffman"] = tans_rows
+
         # fused paths on the Llama-13B-shaped layer (hidden 5120, FFN 13824, quantised without rescale),
         # one call per matrix as the entry points take one matrix
         l13 = build_layer("llama13b", 0, False, params, dc, synth)

@@ -295,3 +295,111 @@ def test_random_inputs_host_compressor_equals_oracle(seed):
             if not table["raw_bytes_flags"][k] & dc.CHUNK_RAW:
                 o, size, raw = int(table["off"][k]), int(table["comp_bytes"][k]), int(table["raw_bytes_flags"][k])
                 assert pyref.parse_and_decode(blob[o:o + size].tobytes(), raw, S) == data[k * C:k * C + raw].tobytes()
+
+
+# ------------------------------------------------------------------ the second coder (tANS)
+
+def tans(C, S, policy=dc.POLICY_ALL_HUFF, f=0.0, block=0):
+    return dc.Params(C, S, policy, f, block, codec=dc.CODEC_TANS)
+
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_random_inputs_host_tans_compressor_equals_oracle(seed):
+    """The sweep above for tANS blobs: the oracle's blob and table, accepted by the validator, decoded back by
+    the oracle, and on small chunks by the independent Python decoder."""
+    from tests import pyref
+    from tests.helpers import lopsided_bytes
+    r = np.random.default_rng(seed)
+    for it in range(80):
+        S = int(r.choice([64, 128, 256]))
+        C = int(r.choice([16, 48, 512, 4096, 16384, 65536]))
+        n_chunks = int(r.integers(1, 5)) if C >= 16384 else int(r.integers(1, 30))
+        n = (n_chunks - 1) * C + int(r.integers(1, C + 1))
+        kind = int(r.integers(0, 5))
+        if kind == 0:
+            data = weightlike_bytes(n, int(r.integers(1 << 30)))
+        elif kind == 1:
+            data = lopsided_bytes(n, S, int(r.integers(1 << 30)))
+        elif kind == 2:
+            data = r.integers(0, 256, n, dtype=np.uint8)
+        elif kind == 3:
+            data = np.full(n, int(r.integers(256)), np.uint8)
+        else:  # a long tail: many values with a single state
+            pz = 1.0 / np.arange(1, 257) ** float(r.uniform(0.7, 1.8))
+            data = r.permutation(256).astype(np.uint8)[r.choice(256, size=n, p=pz / pz.sum())]
+        policy = int(r.choice([dc.POLICY_ALL_HUFF, dc.POLICY_AUTO, dc.POLICY_RAW_FRACTION, dc.POLICY_BLOCK_LAST]))
+        f = float(r.choice([0.0, 0.3, 0.9, 1.0]))
+        block = int(r.integers(1, 6))
+        p = tans(C, S, policy, f, block)
+        blob, table = dc.compress_chunks(data, p)
+        c = oc.compress(data, C, S, policy, f, block=block, codec=oc.TANS)
+        assert np.array_equal(table, c.table) and np.array_equal(blob, c.blob), (seed, it, S, C, n, policy, f, block)
+        cap, nc = dc.compress_bound(n, p)
+        assert blob.size <= cap and nc == len(table)
+        dc.validate(blob, table, p)
+        assert np.array_equal(oc.decompress(blob, table, C, S, n, codec=oc.TANS), data)
+        if C <= 512:
+            k = int(r.integers(len(table)))
+            if not table["raw_bytes_flags"][k] & dc.CHUNK_RAW:
+                o, size, raw = int(table["off"][k]), int(table["comp_bytes"][k]), int(table["raw_bytes_flags"][k])
+                assert pyref.parse_and_decode(blob[o:o + size].tobytes(), raw, S, tans=True) == data[k * C:k * C + raw].tobytes()
+
+
+def test_validate_catches_corruption_of_tans_payloads():
+    C, S = 4096, 64
+    data = weightlike_bytes(5 * C + 9, 8)
+    p = tans(C, S)
+    blob, table = dc.compress_chunks(data, p)
+    dc.validate(blob, table, p)
+    k = 2
+    o = int(table["off"][k])
+
+    def expect_bad(b, chunk=k):
+        with pytest.raises(dc.DCError) as e:
+            dc.validate(b, table, p)
+        assert e.value.code == -3 and f"chunk {chunk})" in str(e.value)
+
+    b = blob.copy(); b[o] ^= 0x01            # one frequency one off: the sum is no longer 2048
+    expect_bad(b)
+    b = blob.copy(); b[o:o + 384] = 0        # no value at all
+    expect_bad(b)
+    # two frequencies changed so that the sum stays 2048: a different, valid table; the streams then walk other
+    # states and (almost surely) do not end in state 0 or run out of bits
+    bits = int.from_bytes(blob[o:o + 384].tobytes(), "little")
+    q = [(bits >> (12 * v)) & 0xFFF for v in range(256)]
+    hi = max(range(256), key=lambda v: q[v])
+    lo = next(v for v in range(256) if q[v] > 0 and v != hi)
+    q[hi] -= 1
+    q[lo] += 1
+    nbits = sum(x << (12 * v) for v, x in enumerate(q))
+    b = blob.copy(); b[o:o + 384] = np.frombuffer(nbits.to_bytes(384, "little"), np.uint8)
+    expect_bad(b)
+    b = blob.copy(); b[o + 384 + 2 * 5] += 1   # block count of stream 5 one too many
+    expect_bad(b)
+    b = blob.copy(); b[o + 384 + 2 * S] ^= 0x10  # area not right after the header
+    expect_bad(b)
+    # a flipped stream bit: caught when the walk has not found its way back to the right states before the stream
+    # ends (a field of many bits sets most of the next state, so walks do meet again) or runs out of bits
+    hdr = (384 + 2 * S + 4 + 15) // 16 * 16
+    caught = 0
+    r = np.random.default_rng(2)
+    for _ in range(40):
+        b = blob.copy()
+        b[o + hdr + int(r.integers(int(table["comp_bytes"][k]) - hdr - 16))] ^= 1 << int(r.integers(8))
+        try:
+            dc.validate(b, table, p)
+        except dc.DCError:
+            caught += 1
+    assert caught >= 10
+    # a Huffman blob is not a tANS blob
+    hb, ht = dc.compress_chunks(data, dc.Params(C, S))
+    with pytest.raises(dc.DCError):
+        dc.validate(hb, ht, p)
+
+
+def test_tans_argument_errors():
+    data = weightlike_bytes(4096, 1)
+    for bad in (dc.Params(4096, 32, codec=dc.CODEC_TANS), dc.Params(4096, 64, codec=2)):
+        with pytest.raises(dc.DCError) as e:
+            dc.compress_chunks(data, bad)
+        assert e.value.code == -1

@@ -226,8 +226,9 @@ def test_stream_bits_against_the_information_in_the_symbols(sigma):
 
 
 def test_flipped_bits_are_noticed():
-    """A stream must end in the state the encoder started from; a flipped stream bit sends the walk elsewhere.
-    Most flips are caught by that (or run the stream out of its blocks); none may crash the decoder."""
+    """A stream must end in the state the encoder started from; a flipped stream bit sends the walk elsewhere,
+    and unless it finds its way back before the stream ends (a wide field sets most of the next state, so walks
+    do meet again) the end state shows it, or the stream runs out of its blocks.  None may crash the decoder."""
     raw, S = 20000, 32
     data = gaussian_bytes(raw, 9.0, 4)
     payload = oc.encode_chunk(data, S, codec=oc.TANS)
