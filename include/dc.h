@@ -8,8 +8,9 @@
  * about to be used, into a caller-owned decompression buffer; a speed-adaptive
  * share of the chunks is stored raw.  The lossless coder is a per-chunk
  * canonical Huffman code over the 256 byte values (code length <= 11) with S
- * symbol-interleaved sub-bitstreams per chunk, stored block-interleaved; the
- * layout is given below.
+ * symbol-interleaved sub-bitstreams per chunk, stored block-interleaved; a
+ * tabled ANS coder with 2048 states can take its place in the same container
+ * (dc_params.codec).  The layout is given below.
  *
  * Conventions for every entry point
  *   - extern "C", plain pointers and sizes.  "_host" pointers are ordinary
@@ -249,6 +250,8 @@ int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, uint64_t *max
  *   table_host  out: one dc_chunk per chunk, table_cap entries available
  *   n_chunks    out: entries used (on DC_E_CAP: entries required)
  * The result is a function of the input and params alone (not of the thread count).
+ * params->codec chooses the coder of the chunks that are not raw; "Huffman" in the names of the
+ * policies then reads "coded".
  */
 int dc_compress_chunks(const int8_t *src_host, uint64_t raw_bytes, const dc_params *params,
                        uint8_t *blob_host, uint64_t blob_cap, uint64_t *blob_bytes, dc_chunk *table_host,
@@ -279,7 +282,8 @@ int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_p
 
 /*
  * Host-side check of a table and blob against the stored format: offsets, sizes, alignment, code
- * lengths forming a complete code, sub-stream extents, and that every sub-stream holds its symbols.
+ * lengths forming a complete code (tANS: frequencies adding up to 2048), sub-stream extents, and that
+ * every sub-stream holds its symbols (tANS: and ends in state 0).
  * Returns DC_OK or DC_E_FORMAT (first offending chunk index in *bad_chunk when not NULL).
  */
 int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *table_host,
@@ -297,6 +301,8 @@ int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *t
  * A part of a blob (a layer of a model, say) is decoded by passing table_dev + k0 and the number of
  * chunks wanted with the same blob: offsets in the table count from blob_dev, and chunk k0 + i then
  * decodes to dst_dev + i * chunk_bytes.
+ * params->codec names the coder of the blob's coded chunks; DC_CODEC_TANS needs n_streams >= 64
+ * (DC_E_ARG otherwise).  A tANS chunk whose frequencies do not add up to 2048 is left undecoded.
  */
 int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                          uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
