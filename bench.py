@@ -351,6 +351,8 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=int(os.environ.get("DC_BENCH_STREAMS", "256")),
                     help="sub-streams per chunk (32, 64, 128 or 256)")
     ap.add_argument("--chunk", type=int, default=65536)
+    ap.add_argument("--codec", choices=("huffman", "tans"), default="huffman",
+                    help="coder of the timed launches (the headline is Huffman; tans times the second coder instead)")
     ap.add_argument("--tile", type=int, default=1,
                     help="decode this many copies of the layer in one launch (input-size scaling; not the headline)")
     ap.add_argument("--full-model", type=int, default=0, metavar="LAYERS",
@@ -362,6 +364,8 @@ def main() -> int:
                     help="skip the side timings of the headline launch (timed alone, same buffers, two streams), "
                          "so that a profiler sees the timed launches only")
     args = ap.parse_args()
+    if args.codec == "tans":
+        args.no_extras = True  # the side measurements (fused calls, device compressor) take Huffman blobs
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; decode shards by chunk range with no exchange step, "
               "but no multi-GPU path is built. Run with --gpus 1.", file=sys.stderr)
@@ -381,7 +385,7 @@ def main() -> int:
                           [(65536, 64), (65536, 256), (16384, 64), (262144, 64), (262144, 256)])
     stream = torch.cuda.current_stream().cuda_stream
     S, C = args.streams, args.chunk
-    params = dc.Params(C, S)
+    params = dc.Params(C, S, codec=dc.CODEC_TANS if args.codec == "tans" else dc.CODEC_HUFFMAN)
 
     layer = build_layer("llama7b", 0, True, params, dc, synth)
     blob, table, q = layer["blob"], layer["table"], layer["q"]
@@ -421,7 +425,7 @@ def main() -> int:
     achieved = algo_bytes / ms / 1e6
 
     traffic = None
-    if S in MEASURED_TRAFFIC_KIB and args.tile == 1 and C == 65536:
+    if S in MEASURED_TRAFFIC_KIB and args.tile == 1 and C == 65536 and args.codec == "huffman":
         f_kib, w_kib = MEASURED_TRAFFIC_KIB[S]
         traffic = int((2.0 * f_kib + 1.0 * w_kib) * 1024)
 
@@ -439,12 +443,14 @@ def main() -> int:
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": "llama7b decoder layer, 7 matrices, compression-aware INT8 (s=a^0.5), 64 KiB chunks, "
-                               "all chunks Huffman coded", "raw_bytes": raw_bytes, "chunk_bytes": C,
+                               + ("all chunks Huffman coded" if args.codec == "huffman" else "all chunks tANS coded"),
+                   "raw_bytes": raw_bytes, "chunk_bytes": C,
                    "n_streams": S, "n_chunks": n_chunks, "blob_bytes": int(blob.size),
                    "compression_ratio": round(ratio, 5), "buffers_rotated": nbuf},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": f"dc_decode_kernel<{S},int8>", "algorithmic_bytes_per_launch": int(algo_bytes),
+                     "kernel": f"dc_decode_kernel<{S},int8" + (",tANS>" if args.codec == "tans" else ">"),
+                     "algorithmic_bytes_per_launch": int(algo_bytes),
                      "avg_launch_ms": round(ms, 5)},
         "wall_ms_per_step": round(wall_ms, 5),
         "roofline_limited_decoded_gbps": round(HBM_PEAK_GBPS / (1 + 1 / ratio), 1),
@@ -618,7 +624,7 @@ def main() -> int:
         t0 = time.perf_counter()
         reps = 0
         while True:
-            ref = oc.decompress(blob, table[:n_sample], C, S, sample_raw, threads=threads)
+            ref = oc.decompress(blob, table[:n_sample], C, S, sample_raw, threads=threads, codec=params.codec)
             reps += 1
             if time.perf_counter() - t0 > 1.5 and reps >= 3:
                 break
@@ -628,10 +634,10 @@ def main() -> int:
         n_small = min(128, layer["slices"][0]["n_chunks"])  # inside the first matrix, whose blob the library made alone
         small_raw = min(raw_bytes, n_small * C)
         t0 = time.perf_counter()
-        oc.decompress(blob, table[:n_small], C, S, small_raw, threads=1)
+        oc.decompress(blob, table[:n_small], C, S, small_raw, threads=1, codec=params.codec)
         one_thread = small_raw / (time.perf_counter() - t0) / 1e9
         t0 = time.perf_counter()
-        enc = oc.compress(q[:small_raw], C, S, threads=threads)
+        enc = oc.compress(q[:small_raw], C, S, threads=threads, codec=params.codec)
         encode = small_raw / (time.perf_counter() - t0) / 1e9
         assert np.array_equal(enc.blob[:-64], blob[:int(table["off"][n_small - 1]) + int(table["comp_bytes"][n_small - 1])])
         out["cpu_baseline"] = {"value": round(sample_raw / dt / 1e9, 3), "unit": "GB/s", "cores": threads,
