@@ -145,9 +145,9 @@ extern "C" {
 /* the coder of the chunks that are not raw (Section 4.2 of the paper compares entropy coders) */
 #define DC_CODEC_HUFFMAN 0 /* canonical Huffman, code length <= 11 */
 #define DC_CODEC_TANS 1    /* tabled asymmetric numeral systems, 2048 states; n_streams 64, 128 or 256;
-                              decoded by dc_decompress_chunks, written by dc_compress_chunks, checked by
-                              dc_validate; the fused calls and dc_compress_chunks_dev take Huffman blobs only
-                              (DC_E_ARG otherwise) */
+                              decoded by every dc_decompress_* call, written by dc_compress_chunks, checked
+                              by dc_validate; dc_compress_chunks_dev writes Huffman blobs only (DC_E_ARG
+                              otherwise) */
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */

@@ -473,7 +473,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr int WAVES = G::kWaves;
     constexpr int TPC = G::kThreadsPerChunk;
     constexpr int SPL = G::kSymbolsPerLane;
-    static_assert(CODEC == DC_CODEC_HUFFMAN || (S >= 64 && MODE == kModeI8), "tANS: whole workgroups, plain decode");
+    static_assert(CODEC == DC_CODEC_HUFFMAN || S >= 64, "tANS: the workgroup's threads are the chunk's");
     constexpr uint32_t kFront = CODEC == DC_CODEC_TANS ? 384 : 128; // code description at the start of a payload
     constexpr uint32_t kHeader = (kFront + 2 * S + 4 * (S / Geometry<S>::kLanesPerChunk) + 15) / 16 * 16;
 
@@ -545,7 +545,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     // The table is only needed where a chunk of the workgroup is Huffman coded; the condition is the
     // same for every thread that is still here, so the barriers inside are reached together.
     const bool build_table = CODEC == DC_CODEC_TANS ? false : CPW == 1 ? huff : (bool)__any(huff);
-    if (CODEC == DC_CODEC_TANS) {
+    if (CODEC == DC_CODEC_TANS && huff) { // (one chunk per workgroup: the same for all of its threads)
         uint32_t *table32 = lds_all + kFrontWords;
         if (!build_tans_table<S>(payload8, ct, lane, wave, lds_all, table32, table32 + kTableEntries,
                                  table32 + kTableEntries + 256))
@@ -749,7 +749,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const float s_a = mat.row_scale[row_a < mat.rows ? row_a : 0], s_b = mat.row_scale[row_b < mat.rows ? row_b : 0];
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
-                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
+                decode16<UNI, CODEC>(st, rg, tbl_addr, ring_lane, whole, w);
             } else if (whole) {
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
@@ -793,7 +793,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const bool whole = raw >= start + 16;
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
-                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
+                decode16<UNI, CODEC>(st, rg, tbl_addr, ring_lane, whole, w);
             } else if (whole) {
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
@@ -833,7 +833,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const bool whole = raw >= start + 16;
             uint32_t w[4] = {0, 0, 0, 0};
             if (huff) {
-                decode16<UNI>(st, rg, tbl_addr, ring_lane, whole, w);
+                decode16<UNI, CODEC>(st, rg, tbl_addr, ring_lane, whole, w);
             } else if (whole) {
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
@@ -1022,22 +1022,23 @@ template <int S, int MODE> void launch_one(const DecodeArgs &a, hipStream_t stre
     hipLaunchKernelGGL((dc_decode_kernel<S, MODE, DC_CODEC_HUFFMAN>), dim3(grid), dim3(G::kThreads), 0, stream, a);
 }
 
-// tANS payloads: plain decode, S >= 64
-int launch_tans(const DecodeArgs &a, uint32_t S, hipStream_t stream)
+// tANS payloads: S >= 64, one chunk per workgroup
+template <int MODE> int launch_tans(const DecodeArgs &a, uint32_t S, hipStream_t stream)
 {
     if (a.n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
     const uint32_t grid = (uint32_t)a.n_chunks;
     switch (S) {
-    case 64: hipLaunchKernelGGL((dc_decode_kernel<64, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(64), 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((dc_decode_kernel<128, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(128), 0, stream, a); break;
-    case 256: hipLaunchKernelGGL((dc_decode_kernel<256, kModeI8, DC_CODEC_TANS>), dim3(grid), dim3(256), 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((dc_decode_kernel<64, MODE, DC_CODEC_TANS>), dim3(grid), dim3(64), 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((dc_decode_kernel<128, MODE, DC_CODEC_TANS>), dim3(grid), dim3(128), 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((dc_decode_kernel<256, MODE, DC_CODEC_TANS>), dim3(grid), dim3(256), 0, stream, a); break;
     default: return DC_E_ARG;
     }
     return launch_status();
 }
 
-template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream_t stream)
+template <int MODE> int launch_decode(const DecodeArgs &a, uint32_t S, hipStream_t stream, uint32_t codec = DC_CODEC_HUFFMAN)
 {
+    if (codec == DC_CODEC_TANS) return launch_tans<MODE>(a, S, stream);
     if (a.n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
     switch (S) {
     case 32: launch_one<32, MODE>(a, stream); break;
@@ -1076,8 +1077,7 @@ extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes
     a.chunk_bytes = params->chunk_bytes;
     a.dst = dst_dev;
     a.dst_cap = dst_cap;
-    if (params->codec == DC_CODEC_TANS) return launch_tans(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
-    return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
+    return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream), params->codec);
 }
 
 namespace {
@@ -1089,7 +1089,6 @@ int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
     if (!decode_params_ok(params) || !blob_dev || !table_dev || !mats || n_mats == 0 || n_mats > DC_MAX_MATRICES ||
         n_chunks == 0 || blob_bytes < 16)
         return DC_E_ARG;
-    if (params->codec != DC_CODEC_HUFFMAN) return DC_E_ARG; // the fused calls decode Huffman payloads only
     if (!aligned16(blob_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
     a = DecodeArgs{};
     a.blob = blob_dev;
@@ -1140,7 +1139,7 @@ extern "C" int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_
     DecodeArgs a;
     const int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, kModeBf16, a);
     if (rc != DC_OK) return rc;
-    return launch_decode<kModeBf16>(a, params->n_streams, static_cast<hipStream_t>(hip_stream));
+    return launch_decode<kModeBf16>(a, params->n_streams, static_cast<hipStream_t>(hip_stream), params->codec);
 }
 
 namespace {
@@ -1161,7 +1160,7 @@ int gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipLaunchKernelGGL(dc_gemv_zero_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
-    rc = launch_decode<MODE>(a, params->n_streams, stream);
+    rc = launch_decode<MODE>(a, params->n_streams, stream, params->codec);
     if (rc != DC_OK) return rc;
     hipLaunchKernelGGL(dc_gemv_finish_kernel<MODE == kModeGemvW8A8>, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
     return launch_status();

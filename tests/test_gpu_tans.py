@@ -1,5 +1,6 @@
-"""GPU parity of the tANS coder: dc_decompress_chunks on tANS blobs against the CPU oracle, bit for bit; the
-library's host compressor against the oracle's blob; what the calls that take Huffman blobs only say."""
+"""GPU parity of the tANS coder: the decode calls on tANS blobs against the CPU oracle (bytes, bf16 values and the
+W8A8 product bit for bit); the library's host compressor against the oracle's blob; what the device compressor,
+which writes Huffman blobs only, says."""
 import numpy as np
 import pytest
 
@@ -116,16 +117,47 @@ def test_corrupt_payloads_stay_inside_the_buffers(S):
         assert (out[k * C:(k + 1) * C] == 0x5A).all()  # frequencies that do not add up: nothing is written
 
 
+@pytest.mark.parametrize("S", [64, 128, 256])
+@pytest.mark.parametrize("rows,cols,C,policy", [(192, 1024, 16384, dc.POLICY_ALL_HUFF), (77, 1040, 4096, dc.POLICY_RAW_FRACTION),
+                                                (1031, 4096, 65536, dc.POLICY_ALL_HUFF)])
+def test_fused_calls_on_tans_blobs(S, rows, cols, C, policy):
+    """Dequantisation to bf16 and both batch-1 products fused into the tANS decode: the same bars as on Huffman
+    blobs (bf16 and the W8A8 product bit for bit, the bf16-activation product within the stated tolerance)."""
+    import oracle.quant as oq
+    import synth
+    from tests.helpers import oracle_matrix
+    print(f"case tans fused S={S} rows={rows} cols={cols} C={C} policy={policy}", flush=True)
+    q, scale = oracle_matrix(rows, cols, synth.matrix_seed(3, 2), True)
+    n = rows * cols
+    p = tans(C, S, policy, 0.4)
+    c = oc.compress(q, C, S, policy, 0.4, codec=oc.TANS, threads=8)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    out16 = torch.full((n + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols, out16, n, stream())
+    x = synth.gen_activation_bf16(cols, 99)
+    y32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols,
+                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, stream())
+    xq = np.random.default_rng(S).integers(-127, 128, cols).astype(np.int8)
+    sx = np.float32(0.021)
+    z32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols, torch.from_numpy(xq).cuda(),
+                            float(sx), z32, None, stream())
+    torch.cuda.synchronize()
+    got = out16.cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[:n].reshape(rows, cols), oq.dequant_bf16(q, scale)) and (got[n:] == 0x5A5A).all()
+    y, y_ref = y32.cpu().numpy(), oq.gemv_ref(q, scale, x)
+    rms = float(np.sqrt(np.mean(y_ref ** 2)))
+    assert (y[rows:] == 7.0).all() and (np.abs(y[:rows] - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
+    z = z32.cpu().numpy()
+    assert (z[rows:] == 7.0).all()
+    assert np.array_equal(z[:rows].view(np.uint32), oq.gemv_w8a8(q, scale, xq, sx).view(np.uint32))
+
+
 def test_calls_that_take_huffman_blobs_only_say_so():
     C, S, n = 16384, 64, 4 * 16384
     data = weightlike_bytes(n, 3)
     p = tans(C, S)
-    blob, table = dc.compress_chunks(data, p)
-    blob_d, table_d = dev(blob), dev(table)
-    scale = torch.ones(64, dtype=torch.float32, device="cuda")
-    out16 = torch.zeros(n, dtype=torch.int16, device="cuda")
-    with pytest.raises(dc.DCError):
-        dc.decompress_dequant_bf16(blob_d, blob.size, table_d, len(table), p, scale, 64, 1024, out16, n, stream())
     with pytest.raises(dc.DCError):
         dc.compress_chunks_dev_workspace(n, p)
     with pytest.raises(dc.DCError):
