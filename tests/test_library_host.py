@@ -403,3 +403,42 @@ def test_tans_argument_errors():
         with pytest.raises(dc.DCError) as e:
             dc.compress_chunks(data, bad)
         assert e.value.code == -1
+
+
+@pytest.mark.parametrize("codec", [dc.CODEC_HUFFMAN, dc.CODEC_TANS])
+def test_what_the_validator_accepts_the_oracle_decodes(codec):
+    """Damaged blobs and tables (flipped bits, overwritten header bytes, changed table fields, truncation): the
+    validator rejects most; whatever it accepts, the oracle's decoder, which checks the format on its own, decodes
+    without complaint (a flip in bits that nothing reads, or a table field that still describes the blob)."""
+    r = np.random.default_rng(40 + codec)
+    accepted = rejected = 0
+    for it in range(250):
+        S = int(r.choice([64, 128, 256]))
+        C = int(r.choice([512, 4096, 16384]))
+        n = max(1, int(r.integers(1, 6)) * C - int(r.integers(0, C)))
+        data = weightlike_bytes(n, int(r.integers(1 << 30)))
+        p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, float(r.choice([0, 0.3])), codec=codec)
+        blob, table = dc.compress_chunks(data, p)
+        b, t = blob.copy(), table.copy()
+        what = int(r.integers(0, 4))
+        if what == 0:
+            for _ in range(int(r.integers(1, 4))):
+                b[r.integers(b.size)] ^= 1 << int(r.integers(8))
+        elif what == 1:
+            k = int(r.integers(len(t)))
+            b[int(t["off"][k]) + int(r.integers(0, min(700, int(t["comp_bytes"][k]))))] = int(r.integers(256))
+        elif what == 2:
+            k = int(r.integers(len(t)))
+            f = str(r.choice(["off", "comp_bytes", "raw_bytes_flags"]))
+            t[f][k] = int(t[f][k]) ^ (1 << int(r.integers(0, 24)))
+        else:
+            b = b[:max(1, b.size - int(r.integers(1, 100)))].copy()
+        try:
+            dc.validate(b, t, p)
+        except dc.DCError:
+            rejected += 1
+            continue
+        accepted += 1
+        sizes = (t["raw_bytes_flags"] & 0x7FFFFFFF).astype(np.int64)
+        oc.decompress(b, t, C, S, int((len(t) - 1) * C + sizes[-1]), codec=codec)
+    assert rejected > 150 and accepted > 0
