@@ -46,11 +46,11 @@ def compress_concat(qs, params):
     return np.concatenate(blobs), np.concatenate(tables)
 
 
-def check_sampled_chunks_with_oracle(blob, table, C, S, flat, ks):
+def check_sampled_chunks_with_oracle(blob, table, C, S, flat, ks, codec=oc.HUFFMAN):
     for k in ks:
         t = table[k:k + 1].copy()
         raw = int(t["raw_bytes_flags"][0] & 0x7FFFFFFF)
-        ref = oc.decompress(blob, t, C, S, raw)
+        ref = oc.decompress(blob, t, C, S, raw, codec=codec)
         assert np.array_equal(ref, flat[k * C:k * C + raw]), k
 
 
@@ -83,6 +83,23 @@ def test_config2_llama7b_layer_one_launch(S):
     check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, 255, 256, 1711, 3087])
     # one matrix compressed by the oracle: same bytes, same ratio
     c = oc.compress(layer[0][1], C, S, threads=8)
+    b0, t0 = dc.compress_chunks(layer[0][1], p)
+    assert np.array_equal(b0, c.blob) and np.array_equal(t0, c.table)
+
+
+@pytest.mark.parametrize("C,S", [(65536, 256), (262144, 64)])
+def test_config2_llama7b_layer_tans_coded(C, S):
+    """The same layer through the second coder, in the launches `bench.py` times for it."""
+    print(f"case config 2 tANS C={C} S={S}", flush=True)
+    layer = oracle_layer("llama7b", 0, True)
+    p = dc.Params(C, S, codec=dc.CODEC_TANS)
+    blob, table = compress_concat([q for _, q, _ in layer], p)
+    flat = np.concatenate([q.reshape(-1) for _, q, _ in layer]).view(np.uint8)
+    assert len(table) == 202375168 // C
+    out = gpu_decode(blob, table, p, flat.size)
+    assert np.array_equal(out, flat)
+    check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, len(table) // 3, len(table) - 1], codec=oc.TANS)
+    c = oc.compress(layer[0][1], C, S, threads=8, codec=oc.TANS)
     b0, t0 = dc.compress_chunks(layer[0][1], p)
     assert np.array_equal(b0, c.blob) and np.array_equal(t0, c.table)
 
