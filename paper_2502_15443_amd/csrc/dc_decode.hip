@@ -14,6 +14,11 @@
 // read front to back exactly once); the block goes into the ring one step later, so the per-symbol
 // loop never waits on memory.  A lane packs 16 decoded bytes and writes them with one 128-bit
 // store; the lanes of a chunk write S*16 contiguous bytes per round.
+//
+// The container's second coder (tANS, 2048 states; Section 4.2 of the paper settles on ANS) runs through the
+// same kernel with another table and another symbol step: the table holds one 32-bit entry per state
+// (build_tans_table), the lane carries the state, and a symbol costs one table read and the state's field
+// of stream bits (tans_symbols).  Rings, block placement, refills, stores and the fused epilogues are shared.
 #include <hip/hip_runtime.h>
 
 #include "dc.h"
