@@ -160,6 +160,10 @@ def test_calls_that_take_huffman_blobs_only_say_so():
     p = tans(C, S)
     with pytest.raises(dc.DCError):
         dc.compress_chunks_dev_workspace(n, p)
+    blob, table = dc.compress_chunks(data, p)
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dc.DCError):  # 32 sub-streams are half a wavefront: Huffman only
+        dc.decompress_chunks(dev(blob), blob.size, dev(table), len(table), dc.Params(C, 32, codec=dc.CODEC_TANS), dst, n, stream())
     with pytest.raises(dc.DCError):
         dc.compress_chunks(data, dc.Params(C, 32, codec=dc.CODEC_TANS))  # tANS needs whole wavefronts of streams
     torch.cuda.synchronize()
