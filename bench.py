@@ -611,7 +611,20 @@ def main() -> int:
         dc.compress_chunks(q, params)
         extras["compress_on_host"] = {"GBps": round(raw_bytes / (time.perf_counter() - t0) / 1e9, 3),
                                       "threads": os.cpu_count()}
-        del q_d, blob_c, table_c, ws_c
+        del blob_c, table_c, ws_c
+        # the same with the second coder
+        pt = dc.Params(C, S, codec=dc.CODEC_TANS)
+        cap_t, nc_t = dc.compress_bound(raw_bytes, pt)
+        blob_t = torch.empty(cap_t, dtype=torch.uint8, device="cuda")
+        table_t = torch.empty(nc_t * 16, dtype=torch.uint8, device="cuda")
+        ws_tn = dc.compress_chunks_dev_workspace(raw_bytes, pt)
+        ws_t = torch.empty(ws_tn, dtype=torch.uint8, device="cuda")
+        tms, _ = time_launches(
+            torch, lambda i: dc.compress_chunks_dev(q_d, raw_bytes, pt, blob_t, cap_t, table_t, nc_t, ws_t, ws_tn,
+                                                    res_c, stream), 20, 3)
+        extras["compress_on_gpu_tans"] = {"GBps": round(raw_bytes / tms / 1e6, 1), "ms": round(tms, 4),
+                                          "blob_bytes": int(res_c.cpu()[0]), "workspace_bytes": ws_tn}
+        del q_d, blob_t, table_t, ws_t
         extras["layer_streaming"] = layer_streaming(torch, dc, synth, params)
         out["extras"] = extras
 

@@ -144,10 +144,9 @@ extern "C" {
 
 /* the coder of the chunks that are not raw (Section 4.2 of the paper compares entropy coders) */
 #define DC_CODEC_HUFFMAN 0 /* canonical Huffman, code length <= 11 */
-#define DC_CODEC_TANS 1    /* tabled asymmetric numeral systems, 2048 states; n_streams 64, 128 or 256;
-                              decoded by every dc_decompress_* call, written by dc_compress_chunks, checked
-                              by dc_validate; dc_compress_chunks_dev writes Huffman blobs only (DC_E_ARG
-                              otherwise) */
+#define DC_CODEC_TANS 1    /* tabled asymmetric numeral systems, 2048 states; n_streams 64, 128 or 256
+                              (DC_E_ARG otherwise); decoded by every dc_decompress_* call, written by
+                              dc_compress_chunks and dc_compress_chunks_dev, checked by dc_validate */
 
 /* which chunks are stored raw (Section 3.3, "Speed Adaptive Partial Compression") */
 #define DC_POLICY_ALL_HUFF 0     /* every chunk Huffman coded, even if that enlarges it */
@@ -268,6 +267,9 @@ int dc_compress_chunks(const int8_t *src_host, uint64_t raw_bytes, const dc_para
  *   table_dev       out, table_cap >= number of chunks entries
  *   workspace_dev   scratch of at least dc_compress_chunks_dev_workspace() bytes, 16-byte aligned,
  *                   owned by the caller; may be reused once the call's work on the stream is done
+ *                   (about 260 + 4 n_streams bytes per chunk; with DC_CODEC_TANS two more bytes per
+ *                   input byte, because a tANS sub-stream is coded from its end and written from its
+ *                   start)
  *   result_dev      out, two u64 in device memory: [0] = blob bytes (needed, when [1] != 0),
  *                   [1] = 0, or DC_E_CAP as a 64-bit value when blob_cap was too small (then the
  *                   blob is incomplete, the table is still written)

@@ -35,10 +35,10 @@ def dev_compress(data: np.ndarray, params, blob_cap=None):
     return blob_d[:cap].cpu().numpy(), table_d.cpu().numpy().view(dc.CHUNK_DTYPE), int(r[0]), int(r[1])
 
 
-def check_equal_to_oracle(data, C, S, policy=oc.ALL_HUFF, block=0, f=0.0):
-    p = dc.Params(C, S, policy, f, block)
+def check_equal_to_oracle(data, C, S, policy=oc.ALL_HUFF, block=0, f=0.0, codec=oc.HUFFMAN):
+    p = dc.Params(C, S, policy, f, block, codec=codec)
     blob, table, used, status = dev_compress(data, p)
-    c = oc.compress(data, C, S, policy, f, block=block, threads=8)
+    c = oc.compress(data, C, S, policy, f, block=block, threads=8, codec=codec)
     assert status == 0 and used == c.blob.size
     assert np.array_equal(table, c.table)
     assert np.array_equal(blob[:used], c.blob)
@@ -138,3 +138,61 @@ def test_largest_chunk_size_both_ways(S):
                          len(table), dc.Params(C, S), dst, n, st)
     torch.cuda.synchronize()
     assert np.array_equal(dst.cpu().numpy(), data)
+
+
+# ------------------------------------------------------------------ the second coder (tANS)
+
+@pytest.mark.parametrize("S", [64, 128, 256])
+@pytest.mark.parametrize("n,C", [(3 * 65536, 65536), (5 * 16384 + 777, 16384), (7 * 4096 + 4095, 4096), (100, 65536),
+                                 (1, 4096), (2 * 262144 + 12345, 262144), (1048576 + 5, 1048576)])
+def test_device_tans_blob_equals_oracle_blob(S, n, C):
+    """Frequencies normalised by the format's rule, states, every sub-stream coded backwards and written forwards
+    in placement order: one right answer, the oracle's."""
+    print(f"case dev tANS compress S={S} n={n} C={C}", flush=True)
+    check_equal_to_oracle(weightlike_bytes(n, 300 + n % 911 + S), C, S, codec=oc.TANS)
+
+
+@pytest.mark.parametrize("S", [64, 256])
+def test_device_tans_compress_degenerate_cases_and_policies(S):
+    """One value (no field bits), two values, uniform bytes, a long tail (many values raised to one state, so the
+    surplus is taken back from the frequent ones), lopsided streams; and the raw-chunk policies."""
+    print(f"case dev tANS compress degenerate S={S}", flush=True)
+    C = 4096
+    r = np.random.default_rng(1)
+    skew = np.clip(np.rint(r.standard_cauchy(C) * 2), -127, 127).astype(np.int8).view(np.uint8)
+    pz = 1.0 / np.arange(1, 257) ** 0.8
+    tail = r.permutation(256).astype(np.uint8)[r.choice(256, size=C, p=pz / pz.sum())]
+    data = np.concatenate([np.zeros(C, np.uint8), np.full(C, 0x81, np.uint8), r.integers(0, 256, C, dtype=np.uint8),
+                           np.tile(np.array([3, 250], np.uint8), C // 2), np.arange(C, dtype=np.uint32).astype(np.uint8),
+                           skew, tail, lopsided_bytes(C, S, 5), np.array([7], np.uint8)])
+    for policy in (oc.ALL_HUFF, oc.AUTO):
+        check_equal_to_oracle(data, C, S, policy, codec=oc.TANS)
+    check_equal_to_oracle(data, C, S, oc.BLOCK_LAST, block=3, codec=oc.TANS)
+    check_equal_to_oracle(data, C, S, oc.RAW_FRACTION, f=0.4, codec=oc.TANS)
+
+
+def test_device_tans_compress_config2_matrix_and_round_trip():
+    """gate_proj of the Llama-7B-shaped layer: the host compressor's tANS blob, accepted by the validator, decoded
+    back on the GPU."""
+    q, _ = oracle_matrix(11008, 4096, synth.matrix_seed(0, 4), True)
+    C, S = 65536, 256
+    p = dc.Params(C, S, codec=dc.CODEC_TANS)
+    blob, table, used, status = dev_compress(q, p)
+    hb, ht = dc.compress_chunks(q, p)
+    assert status == 0 and used == hb.size and np.array_equal(table, ht) and np.array_equal(blob[:used], hb)
+    dc.validate(blob[:used], table, p)
+    st = torch.cuda.current_stream().cuda_stream
+    dst = torch.zeros(q.size, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(torch.from_numpy(blob[:used].copy()).cuda(), used, torch.from_numpy(table.view(np.uint8).copy()).cuda(),
+                         len(table), p, dst, q.size, st)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), q.view(np.uint8).ravel())
+
+
+def test_device_tans_compress_reports_small_blob():
+    data = weightlike_bytes(8 * 16384, 5)
+    p = dc.Params(16384, 64, codec=dc.CODEC_TANS)
+    full, _, used, status = dev_compress(data, p)
+    assert status == 0
+    blob, table, need, status = dev_compress(data, p, blob_cap=used - 16)
+    assert status == E_CAP_U64 and need == used

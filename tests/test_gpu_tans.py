@@ -1,6 +1,6 @@
 """GPU parity of the tANS coder: the decode calls on tANS blobs against the CPU oracle (bytes, bf16 values and the
-W8A8 product bit for bit); the library's host compressor against the oracle's blob; what the device compressor,
-which writes Huffman blobs only, says."""
+W8A8 product bit for bit); the library's host compressor against the oracle's blob (the device compressor's is in
+tests/test_gpu_compress.py); what the calls say to 32 sub-streams."""
 import numpy as np
 import pytest
 
@@ -154,12 +154,12 @@ def test_fused_calls_on_tans_blobs(S, rows, cols, C, policy):
     assert np.array_equal(z[:rows].view(np.uint32), oq.gemv_w8a8(q, scale, xq, sx).view(np.uint32))
 
 
-def test_calls_that_take_huffman_blobs_only_say_so():
+def test_32_sub_streams_are_refused():
     C, S, n = 16384, 64, 4 * 16384
     data = weightlike_bytes(n, 3)
     p = tans(C, S)
     with pytest.raises(dc.DCError):
-        dc.compress_chunks_dev_workspace(n, p)
+        dc.compress_chunks_dev_workspace(n, dc.Params(C, 32, codec=dc.CODEC_TANS))
     blob, table = dc.compress_chunks(data, p)
     dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
     with pytest.raises(dc.DCError):  # 32 sub-streams are half a wavefront: Huffman only
@@ -198,3 +198,6 @@ def test_random_valid_inputs(seed):
         blob, table = dc.compress_chunks(data, p)
         assert np.array_equal(blob, c.blob) and np.array_equal(table, c.table)
         assert np.array_equal(gpu_decode(c.blob, c.table, p, n), data)
+        from tests.test_gpu_compress import dev_compress
+        dblob, dtable, used, status = dev_compress(data, p)
+        assert status == 0 and used == c.blob.size and np.array_equal(dtable, c.table) and np.array_equal(dblob[:used], c.blob)
