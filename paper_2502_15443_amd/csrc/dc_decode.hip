@@ -178,8 +178,21 @@ __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring
 // has blocks left and fewer than DC_LOOKAHEAD_BITS bits beyond its position 8*pad), and buf and next
 // are loaded.  (The step at the head of the decode loop is the fifth time; a tANS stream has read its
 // first state by then.)
+// What stream_fetch has asked memory for and stream_start puts into the ring.
+struct StreamFetch {
+    u32x4_align4 v; // the 20 bytes around the head of the stream
+    uint32_t v4;
+    uint32_t shift; // bytes to shift them down by
+    uint32_t pad;   // bytes that block 0 lacks
+    bool has_head;
+    u32x4 b[3];     // up to three further blocks
+    bool got[3];
+};
+
+// First half of the set-up: loads only, so that it can run before the decode table is built (the rings share
+// their LDS with the scratch of the table build).
 template <bool UNIFORM>
-__device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t field, uint32_t ring_lane)
+__device__ __forceinline__ void stream_fetch(Stream &s, Region &rg, uint32_t field, StreamFetch &f)
 {
     // header field of the stream: blocks in all, and the bytes of block 0 less one
     const uint32_t nb = field & 0xFFFu;
@@ -195,30 +208,38 @@ __device__ __forceinline__ void stream_init(Stream &s, Region &rg, uint32_t fiel
     s.nb10 = nb << 10;
     s.tk10 = 0;
     s.pend = 0;
+    f.pad = pad;
+    f.has_head = nb != 0;
+    f.shift = 0;
     if (nb) {
         uint32_t at = (rg.next_block + whole_total) * kBlockBytes + (heads_incl - hb) - pad; // the header lies before it
         at = at < rg.max_off ? at : rg.max_off;
         const uint8_t *p = rg.payload8 + (at & ~3u);
-        const u32x4_align4 v = *reinterpret_cast<const u32x4_align4 *>(p);
-        const uint32_t v4 = *reinterpret_cast<const uint32_t *>(p + 16);
-        const uint32_t shift = at & 3u;
-        const u32x4 b0 = {__builtin_amdgcn_alignbyte(v[1], v[0], shift), __builtin_amdgcn_alignbyte(v[2], v[1], shift),
-                          __builtin_amdgcn_alignbyte(v[3], v[2], shift), __builtin_amdgcn_alignbyte(v4, v[3], shift)};
-        push_block(0, b0, ring_lane);
+        f.v = *reinterpret_cast<const u32x4_align4 *>(p);
+        f.v4 = *reinterpret_cast<const uint32_t *>(p + 16);
+        f.shift = at & 3u;
         s.tk10 = 1024;
     }
-    u32x4 b[3];
-    bool got[3];
 #pragma unroll
     for (int t = 0; t < 3; t++) {
-        got[t] = s.tk10 < s.nb10 && s.tk10 < ((8u * pad + DC_LOOKAHEAD_BITS) << 3); // 128 f < c + look-ahead, times 8
-        take_blocks<UNIFORM>(s, rg, got[t], b[t]);
+        f.got[t] = s.tk10 < s.nb10 && s.tk10 < ((8u * pad + DC_LOOKAHEAD_BITS) << 3); // 128 f < c + look-ahead, times 8
+        take_blocks<UNIFORM>(s, rg, f.got[t], f.b[t]);
+    }
+}
+
+// Second half: block 0 shifted into place and the further blocks go into the ring, and buf and next are loaded.
+__device__ __forceinline__ void stream_start(Stream &s, const StreamFetch &f, uint32_t ring_lane)
+{
+    if (f.has_head) {
+        const u32x4 b0 = {__builtin_amdgcn_alignbyte(f.v[1], f.v[0], f.shift), __builtin_amdgcn_alignbyte(f.v[2], f.v[1], f.shift),
+                          __builtin_amdgcn_alignbyte(f.v[3], f.v[2], f.shift), __builtin_amdgcn_alignbyte(f.v4, f.v[3], f.shift)};
+        push_block(0, b0, ring_lane);
     }
 #pragma unroll
     for (int t = 0; t < 3; t++)
-        if (got[t]) push_block((t + 1) << 10, b[t], ring_lane);
+        if (f.got[t]) push_block((t + 1) << 10, f.b[t], ring_lane);
     // the stream begins `pad` bytes into block 0
-    const uint32_t skip = pad >> 2, bits = 8u * (pad & 3u);
+    const uint32_t skip = f.pad >> 2, bits = 8u * (f.pad & 3u);
     const uint32_t lo = ring_word(skip << 8, ring_lane);
     const uint32_t hi = ring_word((skip + 1) << 8, ring_lane);
     s.buf = ((uint64_t)lo | ((uint64_t)hi << 32)) >> bits;
@@ -549,6 +570,30 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
 
     // The table is only needed where a chunk of the workgroup is Huffman coded; the condition is the
     // same for every thread that is still here, so the barriers inside are reached together.
+    // ---- the code lengths of the header are asked for first, so that they travel while the sub-streams are set up
+    uint32_t nib_word = 0;
+    if (CODEC == DC_CODEC_HUFFMAN && huff) {
+        if (SPL == 8) nib_word = payload[ct];
+        else if (SPL == 4) nib_word = reinterpret_cast<const uint16_t *>(payload8)[ct];
+        else if (SPL == 2) nib_word = payload8[ct];
+        else nib_word = payload8[ct >> 1];
+    }
+
+    // ---- sub-stream set-up, first half: the loads (all lanes of a stream set are here together or not at all)
+    Region rg;
+    Stream st;
+    StreamFetch sf;
+    if (huff) {
+        rg.payload8 = payload8;
+        // a 20-byte load may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
+        const uint64_t room = a.blob_bytes - ent.off - 20;
+        rg.max_off = room < 0xFFFFFFE0ull ? (uint32_t)room : 0xFFFFFFE0u;
+        rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
+        rg.next_block = payload[(kFront + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
+        if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
+        stream_fetch<UNI>(st, rg, reinterpret_cast<const uint16_t *>(payload8)[kFront / 2 + ct], sf);
+    }
+
     const bool build_table = CODEC == DC_CODEC_TANS ? false : CPW == 1 ? huff : (bool)__any(huff);
     if (CODEC == DC_CODEC_TANS && huff) { // (one chunk per workgroup: the same for all of its threads)
         uint32_t *table32 = lds_all + kFrontWords;
@@ -571,14 +616,8 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             uint4 *z = reinterpret_cast<uint4 *>(marks);
             for (uint32_t i = ct; i < kTableEntries * 2 / 16; i += TPC) z[i] = make_uint4(0, 0, 0, 0);
         }
-        // this thread's SPL code lengths, values v = ct*SPL + s
-        uint32_t nib = 0;
-        if (huff) {
-            if (SPL == 8) nib = payload[ct];
-            else if (SPL == 4) nib = reinterpret_cast<const uint16_t *>(payload8)[ct];
-            else if (SPL == 2) nib = payload8[ct];
-            else nib = (payload8[ct >> 1] >> (4 * (ct & 1))) & 15u;
-        }
+        // this thread's SPL code lengths, values v = ct*SPL + s (asked for above, with the rest of the header)
+        const uint32_t nib = SPL == 1 ? (nib_word >> (4 * (ct & 1))) & 15u : nib_word;
         // counts per length, packed three 10-bit fields a register: length l in reg (l-1)/3
         uint32_t mine[4] = {0, 0, 0, 0};
         uint32_t len_of[SPL];
@@ -680,18 +719,9 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         __syncthreads();
     }
 
-    // ---- sub-stream set-up: all lanes of a stream set are here together or not at all
-    Region rg;
-    Stream st;
+    // ---- sub-stream set-up, second half: the ring is free now
     if (huff) {
-        rg.payload8 = payload8;
-        // a 20-byte load may begin in the last bytes of the payload; the blob goes on for DC_BLOB_TAIL_BYTES
-        const uint64_t room = a.blob_bytes - ent.off - 20;
-        rg.max_off = room < 0xFFFFFFE0ull ? (uint32_t)room : 0xFFFFFFE0u;
-        rg.lanes = CPW == 1 ? ~0ull : (sub ? 0xFFFFFFFF00000000ull : 0x00000000FFFFFFFFull);
-        rg.next_block = payload[(kFront + 2 * S) / 4 + (CPW == 1 ? wave : 0)] / kBlockBytes;
-        if (UNI) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
-        stream_init<UNI>(st, rg, reinterpret_cast<const uint16_t *>(payload8)[kFront / 2 + ct], ring_lane);
+        stream_start(st, sf, ring_lane);
         if (CODEC == DC_CODEC_TANS) {
             // the first state: the stream's first 11 bits (at least 40 bits are valid after the set-up)
             st.x4 = ((uint32_t)st.buf & (kTableEntries - 1)) << 2;
