@@ -334,17 +334,20 @@ __device__ __forceinline__ uint32_t pack4(uint32_t e0, uint32_t e1, uint32_t e2,
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
-// Symbols [8*HALF, 8*HALF + 8) of a group: three refills, 3 + 3 + 2 symbols.
+// Symbols [8*HALF, 8*HALF + 8) of a group: 3 + 2 + 3 symbols.  Only the first batch can meet an empty buffer
+// (the batch before it, the last of the half group before, may have used all 33 bits it had) and needs the second
+// refill; the two symbols leave at least 10 of the 32 bits their refill guarantees, so one refill gives the
+// last three their 33.
 template <int HALF, int CODEC>
 __device__ __forceinline__ void decode8(Stream &s, uint32_t tbl, uint32_t ring_lane, uint32_t out[4])
 {
     uint32_t e[8];
     refill33(s, ring_lane);
     if (CODEC == DC_CODEC_TANS) tans_symbols<3>(s, tbl, e); else symbols<3>(s, tbl, e);
-    refill33(s, ring_lane);
-    if (CODEC == DC_CODEC_TANS) tans_symbols<3>(s, tbl, e + 3); else symbols<3>(s, tbl, e + 3);
     refill(s, ring_lane);
-    if (CODEC == DC_CODEC_TANS) tans_symbols<2>(s, tbl, e + 6); else symbols<2>(s, tbl, e + 6);
+    if (CODEC == DC_CODEC_TANS) tans_symbols<2>(s, tbl, e + 3); else symbols<2>(s, tbl, e + 3);
+    refill(s, ring_lane);
+    if (CODEC == DC_CODEC_TANS) tans_symbols<3>(s, tbl, e + 5); else symbols<3>(s, tbl, e + 5);
     out[2 * HALF] = pack4(e[0], e[1], e[2], e[3]);
     out[2 * HALF + 1] = pack4(e[4], e[5], e[6], e[7]);
 }
