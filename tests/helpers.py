@@ -55,7 +55,7 @@ def lopsided_bytes(n: int, S: int, seed: int) -> np.ndarray:
 
 def empty_buffer_before_three_codes(data: np.ndarray, S: int):
     """Walk of a decoder that keeps a 64-bit buffer per sub-stream, refills it by 32 bits whenever at most 32
-    bits are valid, and decodes each half group of 8 symbols as 3 + 3 + 2 codes: the places (lane, group,
+    bits are valid, and decodes each half group of 8 symbols as 3 + 2 + 3 codes: the places (lane, group,
     half, first symbol of the batch) where a batch of three 11-bit codes (33 bits) begins on a buffer that the
     batch before it emptied completely, so that one refill leaves 32 bits.  Code lengths from the oracle."""
     raw = data.size
@@ -71,7 +71,7 @@ def empty_buffer_before_three_codes(data: np.ndarray, S: int):
                 break
             for half in (0, 1):
                 h = gl[8 * half:8 * half + 8]
-                for lo, hi in ((0, 3), (3, 6), (6, 8)):
+                for lo, hi in ((0, 3), (3, 5), (5, 8)):
                     if avail <= 32:
                         if avail == 0 and int(h[lo:hi].sum()) == 33:
                             hits.append((j, gi, half, lo))
