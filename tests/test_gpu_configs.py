@@ -10,7 +10,7 @@ import oracle.codec as oc
 import oracle.quant as oq
 import paper_2502_15443_amd as dc
 import synth
-from tests.helpers import oracle_matrix
+from tests.helpers import oracle_matrix, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -217,3 +217,101 @@ def test_config5_whole_layer_in_one_fused_call():
         dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, bad, stream())
     with pytest.raises(dc.DCError):
         dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g[:-1], stream())
+
+
+@pytest.mark.parametrize("codec", [oc.HUFFMAN, oc.TANS])
+def test_offsets_beyond_4_gib_in_blob_and_destination(codec):
+    """64-bit arithmetic of the launch: 4104 chunks of the largest chunk size (1 MiB) decode into 4.3 GB, from
+    a blob whose payloads lie on both sides of the 4 GiB mark.  The table refers to nine payloads the oracle
+    wrote (two of them raw, the last one ragged) over and over — the kernel takes every entry on its own —
+    and every decoded chunk is compared on the device."""
+    C, S = 1 << 20, 256
+    n_chunks, tail = 4104, 12345
+    print(f"case beyond 4 GiB codec={codec}", flush=True)
+    data = weightlike_bytes(8 * C + tail, 9090 + codec)
+    mask = np.zeros(9, np.uint8)
+    mask[[2, 5]] = 1
+    c = oc.compress(data, C, S, oc.RAW_MASK, mask=mask, threads=8, codec=codec)
+    assert c.n_chunks == 9 and int(((c.table["raw_bytes_flags"] >> 31) & 1).sum()) == 2
+    high = (1 << 32) + 4096
+    blob_bytes = high + c.blob.size
+    blob_d = torch.zeros(blob_bytes, dtype=torch.uint8, device="cuda")
+    table = np.zeros(n_chunks, dtype=c.table.dtype)
+    place = {}
+    low_end = 0
+    for r in range(9):
+        off, size = int(c.table["off"][r]), int(c.table["comp_bytes"][r])
+        padded = (size + 15) // 16 * 16
+        base = low_end if r % 2 == 0 else high + off
+        if r % 2 == 0:
+            low_end += padded
+        blob_d[base:base + size] = torch.from_numpy(c.blob[off:off + size].copy()).cuda()
+        place[r] = base
+    for k in range(n_chunks):
+        r = 8 if k == n_chunks - 1 else k % 8
+        table[k] = (place[r], c.table["comp_bytes"][r], c.table["raw_bytes_flags"][r])
+    n = (n_chunks - 1) * C + tail
+    assert n > 1 << 32 and max(place.values()) > 1 << 32
+    table_d = dev(table.view(np.uint8))
+    dst = torch.full((n + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, blob_bytes, table_d, n_chunks, dc.Params(C, S, codec=codec), dst, n, stream())
+    torch.cuda.synchronize()
+    src_d = torch.from_numpy(data).cuda()
+    rows = dst[:(n_chunks - 1) * C].view(n_chunks - 1, C)
+    for r in range(8):
+        assert bool((rows[r::8] == src_d[r * C:(r + 1) * C]).all()), f"payload {r}"
+    assert torch.equal(dst[(n_chunks - 1) * C:n], src_d[8 * C:])
+    assert bool((dst[n:] == 0x5A).all())
+
+
+def test_fused_calls_on_a_matrix_beyond_4_gib():
+    """The fused epilogues on a 524 800 x 8192 matrix (4.3 G weights, 8.6 GB of bf16): 4100 chunks of 1 MiB
+    whose table refers to eight payloads of the oracle in turn, so the weights repeat every 1024 rows while
+    the row scales do not.  Dequantised rows are compared with the oracle on sampled chunks (first, around the
+    element 2^32, last); the bf16 product against the fp64 reference and the integer product bit for bit, on
+    every row (the references are those of the 1024 distinct rows times each row's scale)."""
+    C, S = 1 << 20, 256
+    n_chunks, cols = 4100, 8192
+    rows, rows_per_chunk = n_chunks * C // cols, C // cols
+    print(f"case fused beyond 4 GiB rows={rows} cols={cols}", flush=True)
+    data = weightlike_bytes(8 * C, 9191)
+    data[data == 0x80] = 0x81            # int8 weights never hold -128
+    c = oc.compress(data, C, S, threads=8)
+    table = np.zeros(n_chunks, dtype=c.table.dtype)
+    for k in range(n_chunks):
+        table[k] = c.table[k % 8]
+    q8 = data.view(np.int8).reshape(8 * rows_per_chunk, cols)
+    scale = (np.random.default_rng(5).random(rows, dtype=np.float32) + np.float32(0.5)) * np.float32(0.01)
+    blob_d, table_d, scale_d = dev(c.blob), dev(table.view(np.uint8)), torch.from_numpy(scale).cuda()
+    p = dc.Params(C, S)
+    n = rows * cols
+    assert n > 1 << 32
+
+    out16 = torch.zeros(n, dtype=torch.int16, device="cuda")
+    dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, n_chunks, p, scale_d, rows, cols, out16, n, stream())
+    torch.cuda.synchronize()
+    for k in (0, 1, (1 << 32) // C - 1, (1 << 32) // C, (1 << 32) // C + 3, n_chunks - 1):
+        r0 = k * rows_per_chunk
+        got = out16[k * C:(k + 1) * C].cpu().numpy().view(np.uint16).reshape(rows_per_chunk, cols)
+        qk = q8[(k % 8) * rows_per_chunk:(k % 8 + 1) * rows_per_chunk]
+        assert np.array_equal(got, oq.dequant_bf16(qk, scale[r0:r0 + rows_per_chunk])), f"chunk {k}"
+    del out16
+
+    x = synth.gen_activation_bf16(cols, 321)
+    y32 = torch.full((rows + 16,), 7.0, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv(blob_d, c.blob.size, table_d, n_chunks, p, scale_d, rows, cols,
+                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, stream())
+    xq, sx = oq.quantise_vector(np.random.default_rng(6).standard_normal(cols).astype(np.float32))
+    z32 = torch.full((rows + 16,), 7.0, dtype=torch.float32, device="cuda")
+    dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, n_chunks, p, scale_d, rows, cols,
+                            torch.from_numpy(xq).cuda(), float(sx), z32, None, stream())
+    torch.cuda.synchronize()
+    which = np.arange(rows) % q8.shape[0]
+    y_ref = oq.gemv_ref(q8, np.ones(q8.shape[0], np.float32), x)[which] * scale.astype(np.float64)
+    y = y32.cpu().numpy()
+    err = np.abs(y[:rows].astype(np.float64) - y_ref)
+    assert (err <= 1e-2 * np.abs(y_ref) + 1e-2 * float(np.sqrt(np.mean(y_ref ** 2)))).all() and (y[rows:] == 7.0).all()
+    acc = oq.gemv_w8a8_acc(q8, xq)[which]
+    z_ref = (acc.astype(np.float32) * scale) * np.float32(sx)
+    z = z32.cpu().numpy()
+    assert np.array_equal(z[:rows].view(np.uint32), z_ref.view(np.uint32)) and (z[rows:] == 7.0).all()
