@@ -196,3 +196,51 @@ def test_device_tans_compress_reports_small_blob():
     assert status == 0
     blob, table, need, status = dev_compress(data, p, blob_cap=used - 16)
     assert status == E_CAP_U64 and need == used
+
+
+@pytest.mark.parametrize("codec", [oc.HUFFMAN, oc.TANS])
+def test_device_compress_of_more_than_4_gib(codec):
+    """64-bit arithmetic of the compression kernels: 5000 chunks of 1 MiB, the same 8 MiB of weight-like bytes
+    over and over, so the oracle's payloads of the eight distinct chunks tell what every chunk's payload and
+    table entry must be (a chunk is coded alone); offsets are their running sum.  Checked: every table entry,
+    the payload bytes of sampled chunks on both sides of the 4 GiB mark of the source and of the blob, the
+    blob size, and the device decode of the whole blob against the source, on the device."""
+    C, S, period, n_chunks = 1 << 20, 256, 8, 5000
+    print(f"case dev compress beyond 4 GiB codec={codec}", flush=True)
+    data = weightlike_bytes(period * C, 9292 + codec)
+    c = oc.compress(data, C, S, threads=8, codec=codec)
+    step = np.diff(np.append(c.table["off"], c.blob.size - 64)).astype(np.uint64)  # payloads, padded to 16
+    n = n_chunks * C
+    p = dc.Params(C, S, codec=codec)
+    st = torch.cuda.current_stream().cuda_stream
+    src = torch.from_numpy(data).cuda().repeat(n_chunks // period + 1)[:n].contiguous()
+    cap, nc = dc.compress_bound(n, p)
+    assert nc == n_chunks and n > 1 << 32
+    blob_d = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    table_d = torch.zeros(nc * 16, dtype=torch.uint8, device="cuda")
+    ws_bytes = dc.compress_chunks_dev_workspace(n, p)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    res = torch.zeros(2, dtype=torch.int64, device="cuda")
+    dc.compress_chunks_dev(src, n, p, blob_d, cap, table_d, nc, ws, ws_bytes, res, st)
+    torch.cuda.synchronize()
+    used, status = (int(v) for v in res.cpu().numpy().view(np.uint64))
+    table = table_d.cpu().numpy().view(dc.CHUNK_DTYPE)
+    which = np.arange(n_chunks) % period
+    want_off = np.concatenate([[0], np.cumsum(step[which])]).astype(np.uint64)
+    assert status == 0 and used == int(want_off[-1]) + 64
+    assert np.array_equal(table["off"], want_off[:-1])
+    assert np.array_equal(table["comp_bytes"], c.table["comp_bytes"][which])
+    assert np.array_equal(table["raw_bytes_flags"], c.table["raw_bytes_flags"][which])
+    assert used > 1 << 32
+    k_blob = int(np.searchsorted(want_off, np.uint64(1 << 32)))  # first chunk whose payload starts beyond 4 GiB
+    for k in {0, 1, (1 << 32) // C - 1, (1 << 32) // C, k_blob - 1, k_blob, n_chunks - 1}:
+        r, size = int(which[k]), int(c.table["comp_bytes"][which[k]])
+        o = int(c.table["off"][r])
+        got = blob_d[int(want_off[k]):int(want_off[k]) + size].cpu().numpy()
+        assert np.array_equal(got, c.blob[o:o + size]), f"payload of chunk {k}"
+    assert not blob_d[used - 64:used].any()
+    del ws
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, used, table_d, nc, p, dst, n, st)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
