@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 def dev(a):
-    return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1).copy()).cuda()
 
 
 def draw_case(r):
@@ -118,3 +118,35 @@ def test_random_valid_inputs_all_entry_points(seed):
         assert (z[rows:] == 7.0).all()
         assert np.array_equal(z[:rows].view(np.uint32), oq.gemv_w8a8(q, scale, xq, sx).view(np.uint32))
     assert fused >= 30
+
+
+@pytest.mark.parametrize("codec", [dc.CODEC_HUFFMAN, dc.CODEC_TANS])
+def test_damaged_blobs_that_still_validate_decode_as_the_oracle_decodes_them(codec):
+    """Flipped payload bits that dc_validate lets through (a flip in padding, or one that turns a stream into
+    another stream of the same size) give a blob that is valid by the format, so it has one right decode:
+    the device and the oracle must agree on it byte for byte, although it is no longer the input."""
+    r = np.random.default_rng(70 + codec)
+    st = torch.cuda.current_stream().cuda_stream
+    accepted = changed = 0
+    for it in range(400):
+        S = int(r.choice([64, 128, 256]))
+        C = int(r.choice([512, 4096, 16384]))
+        n = max(1, int(r.integers(1, 6)) * C - int(r.integers(0, C)))
+        data = weightlike_bytes(n, int(r.integers(1 << 30)))
+        p = dc.Params(C, S, dc.POLICY_RAW_FRACTION, float(r.choice([0, 0.3])), codec=codec)
+        blob, table = dc.compress_chunks(data, p)
+        b = blob.copy()
+        for _ in range(int(r.integers(1, 4))):
+            b[r.integers(b.size - 64)] ^= 1 << int(r.integers(8))
+        try:
+            dc.validate(b, table, p)
+        except dc.DCError:
+            continue
+        accepted += 1
+        want = oc.decompress(b, table, C, S, n, codec=codec)
+        changed += not np.array_equal(want, data)
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        dc.decompress_chunks(dev(b), b.size, dev(table.view(np.uint8)), len(table), p, dst, n, st)
+        torch.cuda.synchronize()
+        assert np.array_equal(dst.cpu().numpy(), want), f"case {it} S={S} C={C} n={n}"
+    assert accepted >= 15 and changed >= 5
