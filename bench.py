@@ -592,6 +592,27 @@ def main() -> int:
             f = r["raw_fraction"]
             r["model_GBps"] = round(1.0 / ((1 - f) / d0 + f / d1), 1)
         extras["raw_fraction_sweep"] = sweep
+        # The paper's own rule (Section 3.3: of every block of N chunks only the last is compressed) beside the
+        # gain-ranked rule at the same share of raw chunks, 1 - 1/N
+        pareto = []
+        for n_block in (2, 4, 5):
+            row = {"block_chunks": n_block, "raw_fraction": round(1 - 1 / n_block, 4)}
+            for name, pf in (("positional", dc.Params(C, S, dc.POLICY_BLOCK_LAST, 0.0, n_block)),
+                             ("gain_ranked", dc.Params(C, S, dc.POLICY_RAW_FRACTION, 1 - 1 / n_block))):
+                lf = build_layer("llama7b", 0, True, pf, dc, synth)
+                bd = [up(lf["blob"]) for _ in range(nbuf)]
+                td = up(lf["table"])
+                nb, nc = lf["q"].size, len(lf["table"])
+                fms, _ = time_launches(
+                    torch, lambda i: dc.decompress_chunks(bd[i % nbuf], lf["blob"].size, td, nc, pf, dsts[i % nbuf], nb,
+                                                          stream), 50, 5)
+                good = bool(torch.equal(dsts[(50 + 5 - 1) % nbuf][:nb].cpu(), torch.from_numpy(lf["q"].view(np.uint8))))
+                is_raw = (lf["table"]["raw_bytes_flags"] >> 31) & 1
+                row[name] = {"compression_ratio": round(nb / (lf["blob"].size + lf["table"].nbytes), 5),
+                             "decoded_GBps": round(nb / fms / 1e6, 1), "raw_chunks": int(is_raw.sum()), "exact": good}
+                del bd, td
+            pareto.append(row)
+        extras["positional_rule_against_gain_ranked"] = pareto
         # compression of the same layer on the GPU (Section 4.2 reports compression speed as well)
         q_d = up(q)
         cap_c, nc_c = dc.compress_bound(raw_bytes, params)
