@@ -138,7 +138,7 @@ extern "C" {
 #define DC_MAX_CHUNK_BYTES (1u << 20)
 #define DC_BLOB_TAIL_BYTES 64
 #define DC_BLOCK_BYTES 16
-#define DC_LOOKAHEAD_BITS 320
+#define DC_LOOKAHEAD_BITS 392
 #define DC_MAX_MATRICES 16
 #define DC_TANS_STATE_BITS 11
 

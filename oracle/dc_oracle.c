@@ -56,13 +56,13 @@
  * symbols 8*(h%2) .. 8*(h%2)+7 of group number h/2 of every stream.  With c[j]
  * the stream bits used by the symbols of stream j before step h and f[j] the
  * blocks of stream j placed so far: at a step, for j ascending over the set, if
- * f[j] < nb[j] and 128*f[j] - c[j] < 320 then the stream takes block f[j] and
+ * f[j] < nb[j] and 128*f[j] - c[j] < 392 then the stream takes block f[j] and
  * f[j] grows by one: block 0 is the stream's head, any other block is the next
  * one in the area.  Step 0 is carried out five times, every later step once.
  * (c[j] counts from the start of block 0: it is 8*pad[j] before the first
  * symbol, which is why a stream may need a fourth block before it starts.  For
  * a Huffman payload the fifth time changes nothing: c[j] is what it was, and a
- * fifth block would have to start less than 320 bits beyond a position of at
+ * fifth block would have to start less than 392 bits beyond a position of at
  * most 120.  In a tANS payload the first state is read between the fourth and
  * the fifth time.)
  *
@@ -246,7 +246,7 @@ uint32_t orc_stream_symbols(uint32_t raw_bytes, uint32_t S, uint32_t j)
 static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 #define ORC_BLOCK 16u        /* bytes of a block */
-#define ORC_LOOKAHEAD 320u   /* bits a stream keeps placed beyond its position */
+#define ORC_LOOKAHEAD 392u   /* bits a stream keeps placed beyond its position */
 
 /* Streams of a set, number of sets, header size. */
 static uint32_t set_width(uint32_t S) { return S < 64 ? S : 64; }

@@ -106,9 +106,9 @@ struct Stream {
     uint32_t next;  // the word that follows buf
     uint32_t tk10;  // 1024 * (blocks asked for so far, f of the placement rule)
     uint32_t nb10;  // 1024 * (blocks of the stream)
-    uint32_t pend;  // != 0: blk holds the block asked for at the last step, not yet in the ring
-    uint32_t x4;    // tANS: 4 * state = byte offset of the state's table entry
-    u32x4 blk;
+    uint32_t npend[2]; // -1024: blk[p] holds a block asked for at the last step of parity p, not yet in the ring; else 0
+    uint32_t x4;      // tANS: 4 * state = byte offset of the state's table entry
+    u32x4 blk[2];     // a block travels for two steps: asked for at step h, put into the ring at step h + 2
 };
 
 // What the lanes of one stream set share: where the block region of the set's area stands.
@@ -154,20 +154,42 @@ __device__ __forceinline__ void take_blocks(Stream &s, Region &rg, bool want, u3
     if (UNIFORM) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
 }
 
-// One step of the placement rule (before every half group): the block asked for at the step before
-// goes into the ring, then the lanes short of look-ahead ask for their next block.  With
+// The same inside the decode loop: every lane loads; a lane without `want` loads, and drops, a block that a
+// lane below it asks for, or the one after the last asked for (the address is inside the payload in any case).
+// A load that is always issued lets the wait for an earlier load be exact (it counts the loads issued
+// since), so a block can stay in flight across the next step's load.  npend = -1024 where the lane asked.
+template <bool UNIFORM>
+__device__ __forceinline__ void take_blocks_all_load(Stream &s, Region &rg, bool want, u32x4 &dst, uint32_t &npend)
+{
+    const uint64_t m = __ballot(want) & rg.lanes;
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    uint32_t off = (rg.next_block + rank) * kBlockBytes;
+    const uint32_t limit = rg.max_off & ~15u;
+    off = off < limit ? off : limit;
+    dst = *reinterpret_cast<const u32x4 *>(rg.payload8 + off);
+    npend = want ? 0xFFFFFC00u : 0u;
+    s.tk10 -= npend;
+    rg.next_block += (uint32_t)__popcll(m);
+    if (UNIFORM) rg.next_block = __builtin_amdgcn_readfirstlane(rg.next_block);
+}
+
+// One step of the placement rule (before every half group; P = the step's parity): the block asked for two
+// steps before goes into the ring, then the lanes short of look-ahead ask for their next block.  With
 // used = 32*(words taken) - 32 - avail stream bits used so far, the rule's
 // 128*f - used < DC_LOOKAHEAD_BITS reads, times 8, tk10 + 9*avail < state + 8*(DC_LOOKAHEAD_BITS - 32).
-template <bool UNIFORM>
+// Why two steps are safe: before its decision at a step a stream has at least DC_LOOKAHEAD_BITS - 88 bits
+// placed beyond its position, at least DC_LOOKAHEAD_BITS - 48 if it asked at the step before; the blocks
+// asked for at this step and the one before are the only ones not in the ring, so at least
+// DC_LOOKAHEAD_BITS - 176 = 216 bits are, and half a group reads at most 88 + 96 + 31 = 215 bits ahead.
+template <bool UNIFORM, int P>
 __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring_lane)
 {
-    if (s.pend) push_block(s.tk10 - 1024, s.blk, ring_lane);
+    if (s.npend[P]) push_block(s.tk10 - 1024 + s.npend[1 - P], s.blk[P], ring_lane);
     const uint32_t avail = s.state & 0xFFu;
     const int32_t short_of = (int32_t)(s.tk10 + 9u * avail) - (int32_t)(s.state + 8u * (DC_LOOKAHEAD_BITS - 32));
     const int32_t left = (int32_t)s.tk10 - (int32_t)s.nb10;
     const bool want = (short_of > left ? short_of : left) < 0; // both negative
-    take_blocks<UNIFORM>(s, rg, want, s.blk);
-    s.pend = want;
+    take_blocks_all_load<UNIFORM>(s, rg, want, s.blk[P], s.npend[P]);
 }
 
 // Start of a sub-stream.  Block 0 of a stream is short: its first pad = 16 - hb bytes do not exist and
@@ -207,7 +229,7 @@ __device__ __forceinline__ void stream_fetch(Stream &s, Region &rg, uint32_t fie
     }
     s.nb10 = nb << 10;
     s.tk10 = 0;
-    s.pend = 0;
+    s.npend[0] = s.npend[1] = 0;
     f.pad = pad;
     f.has_head = nb != 0;
     f.shift = 0;
@@ -357,9 +379,9 @@ template <bool UNIFORM, int CODEC = DC_CODEC_HUFFMAN>
 __device__ __forceinline__ void decode16(Stream &s, Region &rg, uint32_t tbl, uint32_t ring_lane, bool has_group,
                                          uint32_t out[4])
 {
-    stream_step<UNIFORM>(s, rg, ring_lane);
+    stream_step<UNIFORM, 0>(s, rg, ring_lane);
     if (has_group) decode8<0, CODEC>(s, tbl, ring_lane, out);
-    stream_step<UNIFORM>(s, rg, ring_lane);
+    stream_step<UNIFORM, 1>(s, rg, ring_lane);
     if (has_group) decode8<1, CODEC>(s, tbl, ring_lane, out);
 }
 
@@ -749,10 +771,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             const uint32_t start = ct * 16;
             const uint32_t n = rem > start ? (rem - start < 16 ? rem - start : 16) : 0;
             uint8_t *d = d8 + (size_t)full_rounds * round_bytes;
-            stream_step<UNI>(st, rg, ring_lane);
+            stream_step<UNI, 0>(st, rg, ring_lane);
             for (uint32_t i = 0; i < (n < 8 ? n : 8); i++)
                 d[i] = (uint8_t)(CODEC == DC_CODEC_TANS ? tans_decode1(st, tbl_addr, ring_lane) : decode1(st, tbl_addr, ring_lane));
-            stream_step<UNI>(st, rg, ring_lane);
+            stream_step<UNI, 1>(st, rg, ring_lane);
             for (uint32_t i = 8; i < n; i++)
                 d[i] = (uint8_t)(CODEC == DC_CODEC_TANS ? tans_decode1(st, tbl_addr, ring_lane) : decode1(st, tbl_addr, ring_lane));
         }

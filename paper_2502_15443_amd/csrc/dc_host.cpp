@@ -424,7 +424,7 @@ void write_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook 
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.3 (gfx950; canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.4 (gfx950; canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks)"; }
 
 extern "C" const char *dc_strerror(int code)
 {

@@ -119,7 +119,7 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
     front do not exist; positions count from where that block would start).  An area holds the
     16-byte blocks of its streams, all but the first of each, in request order, then the short first
     blocks in stream order: before every half group (8 symbols) of all streams, each stream in turn that
-    has blocks left and fewer than 320 placed bits beyond its position takes its next block (its own
+    has blocks left and fewer than 392 placed bits beyond its position takes its next block (its own
     short first block, or the next of the area); the first such step runs five times.
 
     tANS payload: the front of the header is 384 bytes, the 12-bit frequencies of the 256 byte values as one
@@ -171,7 +171,7 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
             nonlocal pos
             for i in range(W):
                 j = w * W + i
-                if len(data[i]) < 16 * nb[j] and 8 * len(data[i]) - bit[i] < 320:
+                if len(data[i]) < 16 * nb[j] and 8 * len(data[i]) - bit[i] < 392:
                     if len(data[i]) > 0:
                         data[i] += payload[pos:pos + 16]
                         pos += 16

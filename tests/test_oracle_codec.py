@@ -190,7 +190,7 @@ def test_round_trip_and_independent_decoder_ragged(raw, S):
 def test_lopsided_streams_round_trip_and_lookahead(raw, S):
     """Sub-streams that use the code very unevenly (some all long codes, most all short): round trip
     through the oracle and the independent decoder, and the placement rule keeps every stream between
-    320 and 448 placed bits ahead of its position (or has placed all of its blocks) after every step.
+    392 and 520 placed bits ahead of its position (or has placed all of its blocks) after every step.
     Positions count from where the short first block of a stream would start."""
     from tests.helpers import lopsided_bytes
     data = lopsided_bytes(raw, S, raw + S)
@@ -207,9 +207,9 @@ def test_lopsided_streams_round_trip_and_lookahead(raw, S):
         f, used = 0, 8 * (15 - (field[j] >> 12))
         for h in range(2 * rounds):
             for _ in range(5 if h == 0 else 1):
-                if f < nb[j] and 128 * f - used < 320:
+                if f < nb[j] and 128 * f - used < 392:
                     f += 1
-            assert f == nb[j] or 320 <= 128 * f - used < 448, (j, h)
+            assert f == nb[j] or 392 <= 128 * f - used < 520, (j, h)
             g = j + (h // 2) * S
             if g < groups:
                 lo = 16 * g + 8 * (h % 2)
@@ -301,9 +301,8 @@ def test_short_first_blocks_follow_the_whole_blocks_in_stream_order(raw, S):
 
 def test_first_blocks_of_a_region_are_the_streams_in_turn():
     """Step 0 runs five times (the fifth changes nothing for a Huffman payload).  The first block a stream takes is
-    its short one, so the region opens with block 1 of every stream in stream order, then block 2; block 3
-    follows only for the streams whose first block lacks more than 8 bytes (3 blocks are then fewer than 320
-    bits ahead)."""
+    its short one, so the region opens with block 1 of every stream in stream order, then block 2, then block 3
+    (three blocks are at most 384 bits ahead of the first position, fewer than 392; four are at least 392)."""
     raw, S = 16384, 32
     data = gaussian_bytes(raw, 20.0, 5)
     payload = oc.encode_chunk(data, S)
@@ -315,12 +314,12 @@ def test_first_blocks_of_a_region_are_the_streams_in_turn():
     pos = header_bytes(S)
     for blk in (1, 2, 3):
         for j in range(S):
-            if blk == 3 and not 128 * 3 - 8 * (16 - firsts[j]) < 320:
-                continue
             lo = firsts[j] + 16 * (blk - 1)
             assert payload[pos:pos + 16].tobytes() == streams[j][lo:lo + 16], (blk, j)
             pos += 16
     assert any(f < 8 for f in firsts) and any(f >= 8 for f in firsts)
+    # no stream takes a fifth block at step 0: the next block of the region is the first one asked for later
+    assert all(128 * 4 - 8 * (16 - f) >= 392 for f in firsts)
 
 
 def test_single_value_chunk_closed_form():
