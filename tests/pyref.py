@@ -107,7 +107,7 @@ def tans_state_table(q: Sequence[int]):
     return table
 
 
-def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False) -> bytes:
+def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False, flight: int = 0) -> bytes:
     """Decode one Huffman (or, with `tans`, tANS) payload by walking bits, from the written format alone.
 
     header: 128 bytes of 4-bit code lengths (value v in nibble v&1 of byte v>>1), then S little-endian
@@ -127,6 +127,12 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
     bits as the state asks for (fields least significant bit first): the symbol is the state's value, and with
     k the state's number and n = 11 - floor(log2 k) the next state is (k << n) - 2048 + the next n bits.  The
     first state is read after the fourth and before the fifth run of the first step; the last state is 0.
+
+    flight > 0 checks what a decoder may rely on that gets a block `flight` steps after the step that took it
+    (the blocks of the first four runs are there when decoding starts): at the start of every half group a
+    stream has 215 bits beyond its position among the blocks that have arrived, or all of its blocks have.
+    (215 = the 88 bits half a group can use, the 96 a decoder may hold in registers beyond them, 31 of rounding
+    to whole words.)
     """
     front = 384 if tans else 128
     book: Dict[tuple, int] = {}
@@ -164,6 +170,8 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
             at += first_bytes[w * W + i]
         assert at <= len(payload), "area runs past the payload"
         data = [bytearray() for _ in range(W)]  # blocks of each stream, in order
+        taken_at = [[] for _ in range(W)]       # the step at which each block was taken (-flight: before decoding)
+        now = -flight
         # the position starts behind the bytes that the first block lacks
         bit = [8 * (16 - first_bytes[w * W + i]) if nb[w * W + i] else 0 for i in range(W)]
 
@@ -172,6 +180,7 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
             for i in range(W):
                 j = w * W + i
                 if len(data[i]) < 16 * nb[j] and 8 * len(data[i]) - bit[i] < 392:
+                    taken_at[i].append(now)
                     if len(data[i]) > 0:
                         data[i] += payload[pos:pos + 16]
                         pos += 16
@@ -199,7 +208,13 @@ def parse_and_decode(payload: bytes, raw_bytes: int, S: int, tans: bool = False)
                     for i in range(W):
                         if w * W + i < groups:
                             state[i] = take(i, 11)
+                now = 0
                 step()
+            if flight:
+                for i in range(W):
+                    arrived = sum(1 for t in taken_at[i] if t <= h - flight)
+                    assert arrived == nb[w * W + i] or bit[i] + 215 <= 128 * arrived, (w * W + i, h, bit[i], arrived)
+            now = h + 1
             for i in range(W):
                 g = w * W + i + (h // 2) * S
                 if g >= groups:

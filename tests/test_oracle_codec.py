@@ -488,3 +488,25 @@ def test_layer_sizes_of_the_papers_speed_table():
     import synth
     for kind, hidden, ffn in (("llama7b", 4096, 11008), ("llama13b", 5120, 13824)):
         assert sum(m.rows * m.cols for m in synth.layer_specs(kind)) == 4 * hidden ** 2 + 3 * hidden * ffn
+
+
+@pytest.mark.parametrize("codec", [oc.HUFFMAN, oc.TANS])
+@pytest.mark.parametrize("raw,S", [(65536, 64), (40000, 128), (65536, 256), (5000, 64)])
+def test_the_rule_covers_two_steps_of_flight_for_a_block(raw, S, codec):
+    """What a decoder may rely on that receives a block two steps after the step that took it (the device
+    kernel does): the independent decoder checks, at every half group of every stream, that 215 bits beyond
+    the position lie in blocks taken at least two steps before (88 bits the half group can use, 96 a decoder
+    holds in registers beyond them, 31 of rounding to words), or that the stream's blocks are all there.
+    Streams of the longest codes are the hard case; with three steps of flight the same check fails on them,
+    so the look-ahead of the rule is not more than the two steps need by a whole step."""
+    from tests.helpers import lopsided_bytes, weightlike_bytes
+    tans = codec == oc.TANS
+    for data in (lopsided_bytes(raw, S, raw + S), weightlike_bytes(raw, 5),
+                 np.random.default_rng(raw).integers(0, 256, raw, dtype=np.uint8)):
+        payload = oc.encode_chunk(data, S, codec=codec).tobytes()
+        assert pyref.parse_and_decode(payload, raw, S, tans=tans, flight=2) == data.tobytes()
+        assert pyref.parse_and_decode(payload, raw, S, tans=tans, flight=1) == data.tobytes()
+    if raw >= 40000:
+        payload = oc.encode_chunk(lopsided_bytes(raw, S, raw + S), S, codec=codec).tobytes()
+        with pytest.raises(AssertionError):
+            pyref.parse_and_decode(payload, raw, S, tans=tans, flight=3)
