@@ -176,7 +176,7 @@ __device__ __forceinline__ void take_blocks_all_load(Stream &s, Region &rg, bool
 // One step of the placement rule (before every half group; P = the step's parity): the block asked for two
 // steps before goes into the ring, then the lanes short of look-ahead ask for their next block.  With
 // used = 32*(words taken) - 32 - avail stream bits used so far, the rule's
-// 128*f - used < DC_LOOKAHEAD_BITS reads, times 8, tk10 + 9*avail < state + 8*(DC_LOOKAHEAD_BITS - 32).
+// 128*f - used < DC_LOOKAHEAD_BITS reads, times 8, tk10 < state + 8*(DC_LOOKAHEAD_BITS - 32) - 9*avail.
 // Why two steps are safe: before its decision at a step a stream has at least DC_LOOKAHEAD_BITS - 88 bits
 // placed beyond its position, at least DC_LOOKAHEAD_BITS - 48 if it asked at the step before; the blocks
 // asked for at this step and the one before are the only ones not in the ring, so at least
@@ -186,9 +186,9 @@ __device__ __forceinline__ void stream_step(Stream &s, Region &rg, uint32_t ring
 {
     if (s.npend[P]) push_block(s.tk10 - 1024 + s.npend[1 - P], s.blk[P], ring_lane);
     const uint32_t avail = s.state & 0xFFu;
-    const int32_t short_of = (int32_t)(s.tk10 + 9u * avail) - (int32_t)(s.state + 8u * (DC_LOOKAHEAD_BITS - 32));
-    const int32_t left = (int32_t)s.tk10 - (int32_t)s.nb10;
-    const bool want = (short_of > left ? short_of : left) < 0; // both negative
+    // tk10 below both bounds: the look-ahead's (at least 2368, so no wrap) and the stream's blocks
+    const uint32_t bound = s.state + 8u * (DC_LOOKAHEAD_BITS - 32) + (uint32_t)__mul24((int)avail, -9);
+    const bool want = s.tk10 < (bound < s.nb10 ? bound : s.nb10);
     take_blocks_all_load<UNIFORM>(s, rg, want, s.blk[P], s.npend[P]);
 }
 
