@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the decode kernel on the headline workload, from the rocprofv3 counter runs
 # summarised under profiles/ (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the
 # same counter reads for the plain copy kernel: FETCH_SIZE x 2.000, WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_KIB = {256: (74467.6, 197632.0), 128: (73533.3, 197632.0), 64: (73076.4, 197632.0)}
+MEASURED_TRAFFIC_KIB = {256: (74467.8, 197632.0), 128: (73533.3, 197632.0), 64: (73076.4, 197632.0)}
 
 
 _QUANTISED = {}
