@@ -11,8 +11,8 @@
 // 11 stream bits).  Per wavefront the LDS holds a ring of 16 stream words per lane.  Before every
 // half group of 8 symbols the lanes that are short of look-ahead each take the next block of the
 // wavefront's region (consecutive lanes, consecutive blocks: one coalesced load, and the region is
-// read front to back exactly once); the block goes into the ring one step later, so the per-symbol
-// loop never waits on memory.  A lane packs 16 decoded bytes and writes them with one 128-bit
+// read front to back exactly once); the block goes into the ring two steps later (the look-ahead of
+// DC_LOOKAHEAD_BITS bits in the format allows for it), so the per-symbol loop does not wait on memory.  A lane packs 16 decoded bytes and writes them with one 128-bit
 // store; the lanes of a chunk write S*16 contiguous bytes per round.
 //
 // The container's second coder (tANS, 2048 states; Section 4.2 of the paper settles on ANS) runs through the
