@@ -283,6 +283,23 @@ int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_p
                            void *hip_stream);
 
 /*
+ * dc_compress_chunks_dev for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): the workspace is a fixed array of
+ * DC_STATIC_SCRATCH_BYTES in device memory that belongs to the library (one per GPU, held until the
+ * process ends), and the call allocates nothing.  Same arguments, results and errors as
+ * dc_compress_chunks_dev without the workspace; an input whose workspace
+ * (dc_compress_chunks_dev_workspace) exceeds DC_STATIC_SCRATCH_BYTES is refused with DC_E_CAP before
+ * anything is enqueued (with the default coder and n_streams = 256 the array serves about 13 000 chunks,
+ * 850 MB of weights in 64 KiB chunks; with DC_CODEC_TANS about 8 MB of input).  Every call on a GPU
+ * uses that GPU's one array: calls whose work overlaps on the same GPU (two streams, two threads) race
+ * and must be serialised by the caller.  Nothing in the array has to be cleared between calls.
+ */
+#define DC_STATIC_SCRATCH_BYTES (16u << 20)
+int dc_compress_chunks_dev_static(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
+                                  uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap,
+                                  uint64_t *result_dev, void *hip_stream);
+
+/*
  * Host-side check of a table and blob against the stored format: offsets, sizes, alignment, code
  * lengths forming a complete code (tANS: frequencies adding up to 2048), sub-stream extents, and that
  * every sub-stream holds its symbols (tANS: and ends in state 0).

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     POLICY_RAW_MASK,
     POLICY_BLOCK_LAST,
     CHUNK_RAW,
+    STATIC_SCRATCH_BYTES,
     lib_path,
     version,
     set_num_threads,
@@ -26,6 +27,7 @@ from .binding import (  # noqa: F401
     compress_chunks,
     compress_chunks_dev,
     compress_chunks_dev_workspace,
+    compress_chunks_dev_static,
     validate,
     decompress_chunks,
     decompress_dequant_bf16,

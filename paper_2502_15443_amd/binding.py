@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_PKG, "libdc_mi355x.so")
 POLICY_ALL_HUFF, POLICY_AUTO, POLICY_RAW_FRACTION, POLICY_RAW_MASK, POLICY_BLOCK_LAST = 0, 1, 2, 3, 4
 CODEC_HUFFMAN, CODEC_TANS = 0, 1
 CHUNK_RAW = 0x80000000
+STATIC_SCRATCH_BYTES = 16 << 20
 CHUNK_DTYPE = np.dtype([("off", "<u8"), ("comp_bytes", "<u4"), ("raw_bytes_flags", "<u4")])
 
 
@@ -82,7 +83,7 @@ def lib_path() -> str:
 def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(
-            f"{_LIB_PATH} is missing: build it with `python -m paper_2502_15443_amd.build` "
+            f"{_LIB_PATH} is missing: build it with `python paper_2502_15443_amd/build.py` "
             "(there is no fallback path)")
     # Device memory and streams come from PyTorch, so the library must run on the HIP runtime that
     # PyTorch loaded: bring PyTorch in first so that the shared runtime is resolved to its copy.
@@ -114,6 +115,8 @@ def _load():
     L.dc_compress_chunks_dev_workspace.argtypes = [u64, pp, pu64]
     L.dc_compress_chunks_dev.restype = i32
     L.dc_compress_chunks_dev.argtypes = [vp, u64, pp, vp, u64, vp, u64, vp, u64, vp, vp]
+    L.dc_compress_chunks_dev_static.restype = i32
+    L.dc_compress_chunks_dev_static.argtypes = [vp, u64, pp, vp, u64, vp, u64, vp, vp]
     L.dc_validate.restype = i32
     L.dc_validate.argtypes = [vp, u64, vp, u64, pp, pu64]
     L.dc_decompress_chunks.restype = i32
@@ -243,6 +246,14 @@ def compress_chunks_dev(src_dev, raw_bytes: int, params: Params, blob_dev, blob_
     _check(_L.dc_compress_chunks_dev(_dev(src_dev), raw_bytes, C.byref(cp), _dev(blob_dev), blob_cap, _dev(table_dev),
                                      table_cap, _dev(workspace_dev), workspace_bytes, _dev(result_dev), stream),
            "dc_compress_chunks_dev")
+
+
+def compress_chunks_dev_static(src_dev, raw_bytes: int, params: Params, blob_dev, blob_cap: int, table_dev,
+                               table_cap: int, result_dev, stream: int = 0) -> None:
+    cp = params._c()
+    _check(_L.dc_compress_chunks_dev_static(_dev(src_dev), raw_bytes, C.byref(cp), _dev(blob_dev), blob_cap,
+                                            _dev(table_dev), table_cap, _dev(result_dev), stream),
+           "dc_compress_chunks_dev_static")
 
 
 def validate(blob: np.ndarray, table: np.ndarray, params: Params) -> None:

@@ -13,6 +13,8 @@
 // The stored format is in include/dc.h.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "dc.h"
 #include "dc_device.h"
 
@@ -875,10 +877,13 @@ extern "C" int dc_compress_chunks_dev_workspace(uint64_t raw_bytes, const dc_par
     return DC_OK;
 }
 
-extern "C" int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
-                                      uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap,
-                                      void *workspace_dev, uint64_t workspace_bytes, uint64_t *result_dev,
-                                      void *hip_stream)
+namespace {
+
+// The three launches of the compression, with the workspace (code lengths, sub-stream sizes and payload
+// sizes between them) wherever the caller of this function has it.
+int compress_chunks_on_stream(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params, uint8_t *blob_dev,
+                              uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap, void *workspace_dev,
+                              uint64_t workspace_bytes, uint64_t *result_dev, void *hip_stream)
 {
     uint64_t need = 0;
     if (dc_compress_chunks_dev_workspace(raw_bytes, params, &need) != DC_OK) return DC_E_ARG;
@@ -929,4 +934,64 @@ extern "C" int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes,
     default: launch_emit<256>(a, stream); break;
     }
     return dc_launch_status();
+}
+
+} // namespace
+
+extern "C" int dc_compress_chunks_dev(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
+                                      uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev, uint64_t table_cap,
+                                      void *workspace_dev, uint64_t workspace_bytes, uint64_t *result_dev,
+                                      void *hip_stream)
+{
+    return compress_chunks_on_stream(src_dev, raw_bytes, params, blob_dev, blob_cap, table_dev, table_cap, workspace_dev,
+                                     workspace_bytes, result_dev, hip_stream);
+}
+
+// ---- the same call for callers that cannot allocate: the workspace is a fixed array in device memory
+
+// Workspace of dc_compress_chunks_dev_static.  One copy per GPU that runs the library, held until the
+// process ends.  In host code this name only stands for the array: its address on the current device comes
+// from hipGetSymbolAddress (static_scratch below), and only that address is handed to kernels.
+static __device__ __align__(256) uint8_t scratch[DC_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_of_device[kMaxDevices]; // address of `scratch` on every device that has asked for it
+
+// Address of the workspace array on the current device (looked up once per device), or null with the HIP
+// status noted for dc_last_hip_error().
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        dc_launch_status();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_of_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            dc_launch_status();
+            return nullptr;
+        }
+        g_scratch_of_device[dev] = p;
+    }
+    return g_scratch_of_device[dev];
+}
+
+} // namespace
+
+extern "C" int dc_compress_chunks_dev_static(const int8_t *src_dev, uint64_t raw_bytes, const dc_params *params,
+                                             uint8_t *blob_dev, uint64_t blob_cap, dc_chunk *table_dev,
+                                             uint64_t table_cap, uint64_t *result_dev, void *hip_stream)
+{
+    uint64_t need = 0;
+    if (dc_compress_chunks_dev_workspace(raw_bytes, params, &need) != DC_OK) return DC_E_ARG;
+    if (need > DC_STATIC_SCRATCH_BYTES) return DC_E_CAP; // the input is beyond what the fixed workspace serves
+    void *ws = static_scratch();
+    if (!ws) return DC_E_HIP;
+    return compress_chunks_on_stream(src_dev, raw_bytes, params, blob_dev, blob_cap, table_dev, table_cap, ws,
+                                     DC_STATIC_SCRATCH_BYTES, result_dev, hip_stream);
 }
