@@ -231,10 +231,13 @@ def layer_streaming(torch, dc, synth, params, n_layers=8, reps=10):
     mats = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales[j], x_bf16_dev=xs[j], y_accum_dev=ys[j])
             for j, sl in enumerate(lay["slices"])]
 
+    ws_bytes = dc.decompress_gemv_workspace(len(lay["table"]))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
     def fused(main):
         for i in range(n_layers):
             dc.decompress_gemv_layer(blobs[i % 2], lay["blob"].size, table, len(lay["table"]), params, mats,
-                                     main.cuda_stream)
+                                     ws, ws_bytes, main.cuda_stream)
 
     f_ms = wall(fused)
     # the replayed launches must have produced what the eager calls produce
@@ -532,10 +535,13 @@ def main() -> int:
               for sl in l13["slices"]]
         ys = [torch.empty(sl["rows"], dtype=torch.float32, device="cuda") for sl in l13["slices"]]
 
+        ws13_bytes = dc.decompress_gemv_workspace(len(l13["table"]))
+        ws13 = torch.empty(ws13_bytes, dtype=torch.uint8, device="cuda")
+
         def gemv(i):
             for j, sl in enumerate(l13["slices"]):
                 dc.decompress_gemv(b13[i % 2], blob13, t13.data_ptr() + 16 * sl["k0"], sl["n_chunks"], params,
-                                   scales_d[j], sl["rows"], sl["cols"], xs[j], ys[j], None, stream)
+                                   scales_d[j], sl["rows"], sl["cols"], xs[j], ys[j], None, ws13, ws13_bytes, stream)
 
         gms, _ = time_launches(torch, gemv, 30, 3)
         # the same through the whole-layer calls: one launch over all 4840 chunks
@@ -553,8 +559,8 @@ def main() -> int:
         mats_g = [dc.Matrix(sl["k0"], sl["rows"], sl["cols"], scales_d[j], x_bf16_dev=xs[j], y_accum_dev=ys[j])
                   for j, sl in enumerate(l13["slices"])]
         glms, _ = time_launches(
-            torch, lambda i: dc.decompress_gemv_layer(b13[i % 2], blob13, t13, len(l13["table"]), params, mats_g, stream),
-            30, 3)
+            torch, lambda i: dc.decompress_gemv_layer(b13[i % 2], blob13, t13, len(l13["table"]), params, mats_g,
+                                                      ws13, ws13_bytes, stream), 30, 3)
         del layer16
         extras["fused_llama13b_layer"] = {
             "whole_layer_call": {"dequant_bf16_int8_GBps": round(raw13 / dlms / 1e6, 1),

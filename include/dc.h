@@ -183,7 +183,7 @@ typedef struct {
     uint16_t *dst_bf16_dev;       /* dequant: bf16 [rows][cols], 16-byte aligned */
     uint64_t dst_cap_elems;       /* dequant: capacity of dst_bf16_dev in elements */
     const uint16_t *x_bf16_dev;   /* gemv: cols bf16 activations, 16-byte aligned; cols <= 16384 */
-    float *y_accum_dev;           /* gemv: rows fp32 results (zeroed by the call) */
+    float *y_accum_dev;           /* gemv: rows fp32 results */
     uint16_t *y_bf16_dev;         /* gemv: rows bf16 results, may be NULL */
     const int8_t *x_i8_dev;       /* gemv_w8a8: cols int8 activations, 16-byte aligned; cols <= 16384 */
     float x_scale;                /* gemv_w8a8: scale of the activations (activation = x_i8 * x_scale) */
@@ -342,28 +342,42 @@ int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob_bytes, con
 /*
  * Decompression fused with the batch-1 product of Eq. 1, Y = X' W'^T for one activation row:
  *   y_i = row_scale[i] * sum_j q_ij * x_j,   x given as bf16, accumulated in fp32.
- * Nothing decoded is written to memory.  y_accum_dev (rows fp32 values) is zeroed by the call on the
- * stream and receives the result; y_bf16_dev (rows bf16 values, may be NULL) receives it rounded to
- * bf16.  cols must be a multiple of 16 and at most 16384.
+ * Nothing decoded is written to memory.  y_f32_dev (rows fp32 values) receives the result; y_bf16_dev
+ * (rows bf16 values, may be NULL) receives it rounded to bf16.  cols must be a multiple of 16 and at
+ * most 16384.
+ *   workspace_dev, workspace_bytes   scratch of at least dc_decompress_gemv_workspace(n_chunks) bytes
+ *                                    (256 per chunk), 4-byte aligned, owned by the caller; its contents
+ *                                    before the call do not matter and it may be reused once the call's
+ *                                    work on the stream is done
+ * Two launches: the decode kernel leaves in the workspace one partial sum per chunk and row the chunk
+ * touches, added up inside the chunk in a fixed order, and a second kernel adds a row's partial sums in
+ * chunk order and scales them.  No atomic operation is involved, so a call returns the same bits every
+ * time it runs on the same input.  That holds while a chunk touches at most min(n_streams, 64) rows
+ * (chunk_bytes / cols rows if cols divides chunk_bytes, else ceil(chunk_bytes / cols) + 1); for
+ * flatter matrices the call falls back to three launches that add with fp32 atomics on y_f32_dev (the
+ * workspace is then not used and may be NULL), and results are reproducible to rounding only.
+ * Errors: DC_E_ARG, DC_E_CAP (workspace too small), DC_E_HIP.
  */
+int dc_decompress_gemv_workspace(uint64_t n_chunks, uint64_t *workspace_bytes);
 int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                        uint64_t n_chunks, const dc_params *params, const float *row_scale_dev,
-                       uint32_t rows, uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev,
-                       uint16_t *y_bf16_dev, void *hip_stream);
+                       uint32_t rows, uint32_t cols, const uint16_t *x_bf16_dev, float *y_f32_dev,
+                       uint16_t *y_bf16_dev, void *workspace_dev, uint64_t workspace_bytes, void *hip_stream);
 
 /*
  * The two fused calls for all matrices of a layer at once (Section 3.3 lets the decompression
  * granularity be a layer; one launch over all chunks keeps the GPU filled where a single matrix
  * cannot).  mats_host: n_mats <= DC_MAX_MATRICES descriptors in table order; the chunk counts of the
- * matrices must add up to n_chunks.  Same arithmetic, outputs and errors as the single-matrix calls,
- * which are these calls with one matrix.
+ * matrices must add up to n_chunks.  Same arithmetic, outputs, workspace and errors as the single-matrix
+ * calls, which are these calls with one matrix (the ordered product needs every matrix to meet the
+ * condition on rows per chunk).
  */
 int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                                      uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
                                      uint32_t n_mats, void *hip_stream);
 int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                              uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
-                             uint32_t n_mats, void *hip_stream);
+                             uint32_t n_mats, void *workspace_dev, uint64_t workspace_bytes, void *hip_stream);
 
 /*
  * Decompression fused with the batch-1 product in the paper's own arithmetic: weights and activations

@@ -32,6 +32,7 @@ from .binding import (  # noqa: F401
     decompress_chunks,
     decompress_dequant_bf16,
     decompress_gemv,
+    decompress_gemv_workspace,
     decompress_dequant_bf16_layer,
     decompress_gemv_layer,
     Matrix,

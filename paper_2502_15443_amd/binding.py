@@ -124,12 +124,14 @@ def _load():
     L.dc_decompress_dequant_bf16.restype = i32
     L.dc_decompress_dequant_bf16.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, u64, vp]
     L.dc_decompress_gemv.restype = i32
-    L.dc_decompress_gemv.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, vp, vp, vp]
+    L.dc_decompress_gemv.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, vp, vp, vp, u64, vp]
+    L.dc_decompress_gemv_workspace.restype = i32
+    L.dc_decompress_gemv_workspace.argtypes = [u64, pu64]
     pm = C.POINTER(_CMatrix)
     L.dc_decompress_dequant_bf16_layer.restype = i32
     L.dc_decompress_dequant_bf16_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
     L.dc_decompress_gemv_layer.restype = i32
-    L.dc_decompress_gemv_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp]
+    L.dc_decompress_gemv_layer.argtypes = [vp, u64, vp, u64, pp, pm, u32, vp, u64, vp]
     L.dc_gemv_i8.restype = i32
     L.dc_gemv_i8.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
     L.dc_decompress_gemv_w8a8.restype = i32
@@ -282,12 +284,19 @@ def decompress_dequant_bf16(blob_dev, blob_bytes: int, table_dev, n_chunks: int,
                                          stream), "dc_decompress_dequant_bf16")
 
 
+def decompress_gemv_workspace(n_chunks: int) -> int:
+    n = C.c_uint64(0)
+    _check(_L.dc_decompress_gemv_workspace(n_chunks, C.byref(n)), "dc_decompress_gemv_workspace")
+    return int(n.value)
+
+
 def decompress_gemv(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, row_scale_dev,
-                    rows: int, cols: int, x_bf16_dev, y_accum_dev, y_bf16_dev=None, stream: int = 0) -> None:
+                    rows: int, cols: int, x_bf16_dev, y_f32_dev, y_bf16_dev, workspace_dev, workspace_bytes: int,
+                    stream: int = 0) -> None:
     cp = params._c()
     _check(_L.dc_decompress_gemv(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
-                                 _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_accum_dev),
-                                 _dev(y_bf16_dev), stream), "dc_decompress_gemv")
+                                 _dev(row_scale_dev), rows, cols, _dev(x_bf16_dev), _dev(y_f32_dev),
+                                 _dev(y_bf16_dev), _dev(workspace_dev), workspace_bytes, stream), "dc_decompress_gemv")
 
 
 def _matrices(mats):
@@ -308,11 +317,12 @@ def decompress_dequant_bf16_layer(blob_dev, blob_bytes: int, table_dev, n_chunks
 
 
 def decompress_gemv_layer(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, mats,
-                          stream: int = 0) -> None:
+                          workspace_dev, workspace_bytes: int, stream: int = 0) -> None:
     cp = params._c()
     arr = _matrices(mats)
     _check(_L.dc_decompress_gemv_layer(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp), arr,
-                                       len(mats), stream), "dc_decompress_gemv_layer")
+                                       len(mats), _dev(workspace_dev), workspace_bytes, stream),
+           "dc_decompress_gemv_layer")
 
 
 def gemv_i8(q_dev, row_scale_dev, rows: int, cols: int, x_bf16_dev, y_f32_dev, y_bf16_dev=None, stream: int = 0) -> None:

@@ -33,7 +33,11 @@ constexpr int kTableEntries = 1 << kPeekBits;
 constexpr int kRingWords = 16;                 // per lane
 constexpr uint32_t kBlockBytes = DC_BLOCK_BYTES; // bitstream fetch granule
 
-enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2, kModeGemvW8A8 = 3 };
+// kModeGemv adds the partial sums in a fixed order (per wave in registers, per chunk through LDS, per row in
+// dc_gemv_ordered_finish_kernel); kModeGemvAtomic is the same product with one atomic per run of lanes, for
+// shapes with more rows to a chunk than a wave has lanes.
+enum Mode { kModeI8 = 0, kModeBf16 = 1, kModeGemv = 2, kModeGemvW8A8 = 3, kModeGemvAtomic = 4 };
+constexpr uint32_t kPartialSlots = 64; // fp32 partial sums a chunk leaves in the workspace of the ordered product
 
 template <int S> struct Geometry {
     static constexpr int kLanesPerChunk = S < 64 ? S : 64;       // lanes of one wave that serve a chunk
@@ -66,6 +70,8 @@ struct DecodeArgs {
     // kModeI8: all chunks decode into one buffer of dst_cap bytes
     void *dst;
     uint64_t dst_cap;
+    // kModeGemv: kPartialSlots sums per chunk (slot r: the chunk's share of the r-th row it touches)
+    float *partial;
     // fused modes: the matrices, in table order
     uint32_t n_mats;
     MatrixArgs mats[DC_MAX_MATRICES];
@@ -94,6 +100,37 @@ template <bool HALVES, typename T> __device__ __forceinline__ void lanes_add_by_
     uint32_t above = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, 0x130, 0xF, 0xF, false);
     if (HALVES && (threadIdx.x & 31u) == 31u) above = 0xFFFFFFFFu;
     if (key != 0xFFFFFFFFu && above != key) atomicAdd(y + key, val);
+}
+
+// The same sums, kept in the wave: the sum of every run goes to the lane whose number is the run's `slot`
+// (slot < 64, the same for all lanes of a run), where it is added to `mine`.  Runs are taken in lane order and
+// each lane adds at most one value per call, so the result does not depend on timing.
+template <bool HALVES> __device__ __forceinline__ void lanes_add_runs_to_slots(float &mine, uint32_t key, uint32_t slot, float val)
+{
+#define DC_SEG_STEP(CTRL, MASK)                                                                              \
+    {                                                                                                        \
+        const uint32_t k2 = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, CTRL, MASK, 0xF, false);     \
+        const float v2 = __uint_as_float(dpp_or_zero<CTRL, MASK>(__float_as_uint(val)));                     \
+        val += k2 == key ? v2 : 0.0f;                                                                        \
+    }
+    DC_SEG_STEP(0x111, 0xF)
+    DC_SEG_STEP(0x112, 0xF)
+    DC_SEG_STEP(0x114, 0xF)
+    DC_SEG_STEP(0x118, 0xF)
+    DC_SEG_STEP(0x142, 0xA)
+    if (!HALVES) DC_SEG_STEP(0x143, 0xC)
+#undef DC_SEG_STEP
+    uint32_t above = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)key, 0x130, 0xF, 0xF, false);
+    if (HALVES && (threadIdx.x & 31u) == 31u) above = 0xFFFFFFFFu;
+    uint64_t ends = __ballot(key != 0xFFFFFFFFu && above != key); // the last lane of every run
+    const uint32_t lane = threadIdx.x & 63u;
+    while (ends) {
+        const uint32_t from = (uint32_t)__builtin_ctzll(ends);
+        const uint32_t to = (uint32_t)__builtin_amdgcn_readlane((int)slot, from) & 63u;
+        const float v = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(val), from));
+        mine += lane == to ? v : 0.0f;
+        ends &= ends - 1;
+    }
 }
 
 // One sub-stream as its lane sees it.  Stream words travel memory -> blk -> LDS ring -> next -> buf.
@@ -841,13 +878,25 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         return;
     }
 
-    if (MODE == kModeGemv) {
-        // Partial dot products of the int8 values with x; the row scale is applied once per row by
-        // dc_gemv_finish_kernel.  A lane keeps the sum of its groups of
-        // one row; when some lane of the wave moves to another row, the wave adds its sums to y, one
-        // atomic per row it holds.
+    if (MODE == kModeGemv || MODE == kModeGemvAtomic) {
+        // Partial dot products of the int8 values with x; the row scale is applied once per row by the finish
+        // kernel.  A lane keeps the sum of its groups of one row; when some lane of the wave moves to another
+        // row, the wave sums its lanes by row.  kModeGemvAtomic: one atomic on y per row the wave holds.
+        // kModeGemv: the sum of the r-th row the chunk touches goes to lane r of the wave (of the chunk's half
+        // of it when S = 32), which keeps the wave's total for that row; at the end the waves' totals are
+        // added in wave order through LDS and the chunk leaves one sum per row in the workspace.  Every
+        // addition then has a fixed place in a fixed order, so the result is the same bits at every run.
+        const uint32_t first_row = (uint32_t)(dst_pos / cols);
+        float mine = 0.0f; // kModeGemv: this wave's sum for row first_row + cl
         uint32_t cur_row = 0xFFFFFFFFu;
         float acc = 0.0f;
+        auto flush = [&]() {
+            const uint32_t key = cur_row < mat.rows ? cur_row : 0xFFFFFFFFu;
+            if (MODE == kModeGemvAtomic) lanes_add_by_key<CPW == 2, float>(mat.y_accum, key, acc);
+            else lanes_add_runs_to_slots<CPW == 2>(mine, key, (cur_row - first_row) % LPC + sub * LPC, acc);
+            acc = 0.0f;
+            cur_row = 0xFFFFFFFFu;
+        };
         for (uint32_t r = 0; r < rounds; r++) {
             const uint32_t start = r * round_bytes + ct * 16;
             const bool whole = raw >= start + 16;
@@ -858,11 +907,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 const u32x4 v = load16_stream(payload8 + start);
                 w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
             }
-            if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) {
-                lanes_add_by_key<CPW == 2, float>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
-                acc = 0.0f;
-                cur_row = 0xFFFFFFFFu;
-            }
+            if (__any(whole && row != cur_row && cur_row != 0xFFFFFFFFu)) flush();
             if (whole) {
                 cur_row = row;
                 const uint4 *xp = reinterpret_cast<const uint4 *>(mat.x_bf16 + col);
@@ -879,7 +924,22 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             col += round_bytes;
             while (col >= cols) { col -= cols; row++; }
         }
-        lanes_add_by_key<CPW == 2, float>(mat.y_accum, cur_row < mat.rows ? cur_row : 0xFFFFFFFFu, acc);
+        flush();
+        if (MODE == kModeGemv) {
+            float total = mine;
+            if (WAVES > 1) {
+                // a wave's ring is its own, and the wave has read the last of it: the totals go there
+                lds_all[wave * (kRingWords * 64) + lane] = __float_as_uint(mine);
+                __syncthreads();
+                if (wave == 0) {
+                    total = 0.0f;
+#pragma unroll
+                    for (int v = 0; v < WAVES; v++) total += __uint_as_float(lds_all[v * (kRingWords * 64) + lane]);
+                }
+            }
+            const uint32_t last_row = (uint32_t)((dst_pos + raw - 1) / cols);
+            if (wave == 0 && cl <= last_row - first_row) a.partial[k * kPartialSlots + cl] = total;
+        }
     }
 
     if (MODE == kModeGemvW8A8) {
@@ -921,6 +981,8 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
 // Blocks of 256 rows of the matrices of a fused GEMV call, matrix after matrix.
 struct RowBlocks {
     uint32_t n_mats;
+    uint32_t chunk_bytes;
+    const float *partial; // the ordered product: kPartialSlots sums per chunk
     uint32_t first_block[DC_MAX_MATRICES + 1];
     MatrixArgs mats[DC_MAX_MATRICES];
 };
@@ -946,6 +1008,30 @@ template <bool W8A8> __global__ __launch_bounds__(256) void dc_gemv_finish_kerne
         float y;
         if (W8A8) y = ((float)reinterpret_cast<const int32_t *>(m.y_accum)[i] * m.row_scale[i]) * m.x_scale;
         else y = m.row_scale[i] * m.y_accum[i];
+        m.y_accum[i] = y;
+        if (m.y_bf16) m.y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
+    }
+}
+
+// The ordered product: y_i = scale_i * (sum over the chunks that hold a part of row i, in chunk order, of the
+// chunk's sum for the row).  Chunk c of a matrix holds bytes [c*C, c*C + C) of it and keeps the sum of the r-th
+// row it touches, row (c*C) div cols + r, in slot r.
+__global__ __launch_bounds__(256) void dc_gemv_ordered_finish_kernel(RowBlocks rb)
+{
+    uint32_t mi = 0;
+    for (uint32_t i = 1; i < rb.n_mats; i++)
+        if (blockIdx.x >= rb.first_block[i]) mi = i;
+    const MatrixArgs &m = rb.mats[mi];
+    const uint32_t i = (blockIdx.x - rb.first_block[mi]) * 256 + threadIdx.x;
+    if (i < m.rows) {
+        const uint64_t C = rb.chunk_bytes;
+        const uint64_t begin = (uint64_t)i * m.cols, last = begin + m.cols - 1;
+        float sum = 0.0f;
+        for (uint64_t c = begin / C; c <= last / C; c++) {
+            const uint64_t first_row = c * C / m.cols;
+            sum += rb.partial[(m.first_chunk + c) * kPartialSlots + (i - first_row)];
+        }
+        const float y = m.row_scale[i] * sum;
         m.y_accum[i] = y;
         if (m.y_bf16) m.y_bf16[i] = (uint16_t)(bf16x2(y, 0.0f) & 0xFFFFu);
     }
@@ -1204,23 +1290,47 @@ extern "C" int dc_decompress_dequant_bf16_layer(const uint8_t *blob_dev, uint64_
 
 namespace {
 
+// Rows a chunk of chunk_bytes bytes can touch in a matrix with rows of `cols` bytes whose first chunk starts a row.
+uint64_t rows_touched_by_a_chunk(uint32_t chunk_bytes, uint32_t cols)
+{
+    if (chunk_bytes % cols == 0) return chunk_bytes / cols;
+    return (chunk_bytes + cols - 1) / cols + 1;
+}
+
 // zero y, decode with the product fused in, scale y: three launches
 template <int MODE>
 int gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev, uint64_t n_chunks,
-               const dc_params *params, const dc_matrix *mats_host, uint32_t n_mats, void *hip_stream)
+               const dc_params *params, const dc_matrix *mats_host, uint32_t n_mats, void *workspace_dev,
+               uint64_t workspace_bytes, void *hip_stream)
 {
     DecodeArgs a;
     int rc = fused_args(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, MODE, a);
     if (rc != DC_OK) return rc;
     RowBlocks rb = {};
     rb.n_mats = n_mats;
+    rb.chunk_bytes = params->chunk_bytes;
+    bool ordered = MODE == kModeGemv;
     for (uint32_t i = 0; i < n_mats; i++) {
         rb.mats[i] = a.mats[i];
         rb.first_block[i + 1] = rb.first_block[i] + (a.mats[i].rows + 255) / 256;
+        // the ordered product keeps a row's sum in the lane of the row's number inside the chunk
+        if (rows_touched_by_a_chunk(params->chunk_bytes, a.mats[i].cols) > (params->n_streams < 64 ? params->n_streams : 64))
+            ordered = false;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (ordered) {
+        // decode leaves one sum per chunk and row in the workspace, the finish kernel adds them in chunk order
+        if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 3u)) return DC_E_ARG;
+        if (workspace_bytes / (kPartialSlots * sizeof(float)) < n_chunks) return DC_E_CAP;
+        a.partial = static_cast<float *>(workspace_dev);
+        rb.partial = a.partial;
+        rc = launch_decode<kModeGemv>(a, params->n_streams, stream, params->codec);
+        if (rc != DC_OK) return rc;
+        hipLaunchKernelGGL(dc_gemv_ordered_finish_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
+        return launch_status();
+    }
     hipLaunchKernelGGL(dc_gemv_zero_kernel, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
-    rc = launch_decode<MODE>(a, params->n_streams, stream, params->codec);
+    rc = launch_decode<MODE == kModeGemv ? kModeGemvAtomic : MODE>(a, params->n_streams, stream, params->codec);
     if (rc != DC_OK) return rc;
     hipLaunchKernelGGL(dc_gemv_finish_kernel<MODE == kModeGemvW8A8>, dim3(rb.first_block[n_mats]), dim3(256), 0, stream, rb);
     return launch_status();
@@ -1228,18 +1338,27 @@ int gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
 
 } // namespace
 
+extern "C" int dc_decompress_gemv_workspace(uint64_t n_chunks, uint64_t *workspace_bytes)
+{
+    if (!workspace_bytes || n_chunks == 0 || n_chunks > 0x7FFFFFFFull) return DC_E_ARG;
+    *workspace_bytes = n_chunks * kPartialSlots * sizeof(float);
+    return DC_OK;
+}
+
 extern "C" int dc_decompress_gemv_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                                         uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
-                                        uint32_t n_mats, void *hip_stream)
+                                        uint32_t n_mats, void *workspace_dev, uint64_t workspace_bytes, void *hip_stream)
 {
-    return gemv_layer<kModeGemv>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, hip_stream);
+    return gemv_layer<kModeGemv>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, workspace_dev,
+                                 workspace_bytes, hip_stream);
 }
 
 extern "C" int dc_decompress_gemv_w8a8_layer(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                                              uint64_t n_chunks, const dc_params *params, const dc_matrix *mats_host,
                                              uint32_t n_mats, void *hip_stream)
 {
-    return gemv_layer<kModeGemvW8A8>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, hip_stream);
+    return gemv_layer<kModeGemvW8A8>(blob_dev, blob_bytes, table_dev, n_chunks, params, mats_host, n_mats, nullptr, 0,
+                                     hip_stream);
 }
 
 extern "C" int dc_decompress_gemv_w8a8(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
@@ -1274,17 +1393,18 @@ extern "C" int dc_decompress_dequant_bf16(const uint8_t *blob_dev, uint64_t blob
 
 extern "C" int dc_decompress_gemv(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
                                   uint64_t n_chunks, const dc_params *params, const float *row_scale_dev, uint32_t rows,
-                                  uint32_t cols, const uint16_t *x_bf16_dev, float *y_accum_dev, uint16_t *y_bf16_dev,
-                                  void *hip_stream)
+                                  uint32_t cols, const uint16_t *x_bf16_dev, float *y_f32_dev, uint16_t *y_bf16_dev,
+                                  void *workspace_dev, uint64_t workspace_bytes, void *hip_stream)
 {
     dc_matrix m = {};
     m.rows = rows;
     m.cols = cols;
     m.row_scale_dev = row_scale_dev;
     m.x_bf16_dev = x_bf16_dev;
-    m.y_accum_dev = y_accum_dev;
+    m.y_accum_dev = y_f32_dev;
     m.y_bf16_dev = y_bf16_dev;
-    return dc_decompress_gemv_layer(blob_dev, blob_bytes, table_dev, n_chunks, params, &m, 1, hip_stream);
+    return dc_decompress_gemv_layer(blob_dev, blob_bytes, table_dev, n_chunks, params, &m, 1, workspace_dev,
+                                    workspace_bytes, hip_stream);
 }
 
 extern "C" const char *dc_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }

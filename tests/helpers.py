@@ -21,6 +21,17 @@ def oracle_matrix(rows: int, cols: int, seed: int, rescale: bool):
     return oq.prune(q), scale
 
 
+def gemv_workspace(n_chunks: int):
+    """(device tensor, size in bytes) for the workspace argument of the fused product calls, filled with
+    all-ones bytes (fp32 NaN), so that a partial sum that is read without having been written shows."""
+    import torch
+
+    import paper_2502_15443_amd as dc
+
+    n = dc.decompress_gemv_workspace(n_chunks)
+    return torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda"), n
+
+
 def weightlike_bytes(n: int, seed: int) -> np.ndarray:
     """Byte string with chunk-to-chunk varying spread, so chunks differ in gain."""
     r = np.random.default_rng(seed)

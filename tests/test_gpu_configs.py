@@ -10,7 +10,7 @@ import oracle.codec as oc
 import oracle.quant as oq
 import paper_2502_15443_amd as dc
 import synth
-from tests.helpers import oracle_matrix, weightlike_bytes
+from tests.helpers import gemv_workspace, oracle_matrix, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -157,7 +157,8 @@ def test_config5_llama13b_fused_paths(index):
     x_d = torch.from_numpy(x.view(np.int16)).cuda()
     y32 = torch.empty(m.rows, dtype=torch.float32, device="cuda")
     y16 = torch.empty(m.rows, dtype=torch.int16, device="cuda")
-    dc.decompress_gemv(blob_d, blob.size, table_d, len(table), p, scale_d, m.rows, m.cols, x_d, y32, y16, stream())
+    dc.decompress_gemv(blob_d, blob.size, table_d, len(table), p, scale_d, m.rows, m.cols, x_d, y32, y16,
+                       *gemv_workspace(len(table)), stream())
     out16 = torch.empty(q.size, dtype=torch.int16, device="cuda")
     dc.decompress_dequant_bf16(blob_d, blob.size, table_d, len(table), p, scale_d, m.rows, m.cols, out16, q.size,
                                stream())
@@ -197,7 +198,7 @@ def test_config5_whole_layer_in_one_fused_call():
         keep.append((m, q, scale, x, y32, y16, o16))
         k0 += q.size // C
     assert k0 == len(table) == 4840
-    dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g, stream())
+    dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g, *gemv_workspace(len(table)), stream())
     dc.decompress_dequant_bf16_layer(blob_d, blob.size, table_d, len(table), p, mats_b, stream())
     torch.cuda.synchronize()
     for m, q, scale, x, y32, y16, o16 in keep:
@@ -214,9 +215,10 @@ def test_config5_whole_layer_in_one_fused_call():
     bad = [dc.Matrix(mm.first_chunk + 1, mm.rows, mm.cols, mm.row_scale_dev, x_bf16_dev=mm.x_bf16_dev,
                      y_accum_dev=mm.y_accum_dev) for mm in mats_g]
     with pytest.raises(dc.DCError):
-        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, bad, stream())
+        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, bad, *gemv_workspace(len(table)), stream())
     with pytest.raises(dc.DCError):
-        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g[:-1], stream())
+        dc.decompress_gemv_layer(blob_d, blob.size, table_d, len(table), p, mats_g[:-1], *gemv_workspace(len(table)),
+                                 stream())
 
 
 @pytest.mark.parametrize("codec", [oc.HUFFMAN, oc.TANS])
@@ -300,7 +302,7 @@ def test_fused_calls_on_a_matrix_beyond_4_gib():
     x = synth.gen_activation_bf16(cols, 321)
     y32 = torch.full((rows + 16,), 7.0, dtype=torch.float32, device="cuda")
     dc.decompress_gemv(blob_d, c.blob.size, table_d, n_chunks, p, scale_d, rows, cols,
-                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, stream())
+                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, *gemv_workspace(n_chunks), stream())
     xq, sx = oq.quantise_vector(np.random.default_rng(6).standard_normal(cols).astype(np.float32))
     z32 = torch.full((rows + 16,), 7.0, dtype=torch.float32, device="cuda")
     dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, n_chunks, p, scale_d, rows, cols,

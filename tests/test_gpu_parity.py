@@ -10,7 +10,7 @@ import oracle.codec as oc
 import oracle.quant as oq
 import paper_2502_15443_amd as dc
 import synth
-from tests.helpers import lopsided_bytes, oracle_matrix, weightlike_bytes
+from tests.helpers import gemv_workspace, lopsided_bytes, oracle_matrix, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -199,7 +199,7 @@ def test_corrupt_payloads_and_table_entries_stay_inside_the_buffers(S):
     x = synth.gen_activation_bf16(cols, 3)
     x_d = torch.from_numpy(x.view(np.int16)).cuda()
     y32 = torch.full((rows + 64,), 7.0, dtype=torch.float32, device="cuda")
-    dc.decompress_gemv(blob_d, blob.size, table_d, 12, p, scale_d, rows, cols, x_d, y32, None, stream())
+    dc.decompress_gemv(blob_d, blob.size, table_d, 12, p, scale_d, rows, cols, x_d, y32, None, *gemv_workspace(12), stream())
     torch.cuda.synchronize()
     y = y32.cpu().numpy()
     assert (y[rows:] == 7.0).all()
@@ -278,7 +278,8 @@ def gemv_check(y, y_ref):
 
 @pytest.mark.parametrize("S", [32, 64, 128, 256])
 @pytest.mark.parametrize("rows,cols,C,f", [(160, 1024, 16384, 0.0), (50, 5120, 65536, 0.0), (37, 13824, 65536, 0.3),
-                                           (64, 2752, 16384, 0.5)])
+                                           (64, 2752, 16384, 0.5), (24, 8192, 4096, 0.2), (5, 16384, 1024, 0.0),
+                                           (2048, 64, 16384, 0.3), (640, 256, 16384, 0.0), (512, 512, 16384, 0.0)])
 def test_gemv_within_tolerance(S, rows, cols, C, f):
     print(f"case gemv S={S} {rows}x{cols} C={C} f={f}", flush=True)
     seed = synth.matrix_seed(2, 5)
@@ -291,13 +292,54 @@ def test_gemv_within_tolerance(S, rows, cols, C, f):
     y32 = torch.full((rows,), 7.0, dtype=torch.float32, device="cuda")  # the call must zero it itself
     y16 = torch.zeros(rows, dtype=torch.int16, device="cuda")
     dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, x_d, y32, y16,
-                       stream())
+                       *gemv_workspace(c.n_chunks), stream())
     torch.cuda.synchronize()
     norm_err = gemv_check(y32.cpu().numpy(), y_ref)
     assert norm_err < 1e-4  # fp32 accumulation: far inside the 1e-2 bar
     y16f = oq.bf16_to_f64(y16.cpu().numpy().view(np.uint16))
     gemv_check(y16f, y_ref)
     assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
+
+
+@pytest.mark.parametrize("S", [32, 64, 128, 256])
+@pytest.mark.parametrize("codec", [oc.HUFFMAN, oc.TANS])
+@pytest.mark.parametrize("rows,cols,C,f", [(50, 5120, 65536, 0.0), (37, 13824, 65536, 0.3), (24, 8192, 4096, 0.2),
+                                           (512, 512, 16384, 0.0)])
+def test_gemv_same_bits_at_every_run(S, codec, rows, cols, C, f):
+    """The fused product adds in a fixed order (a chunk touches at most min(S, 64) rows in these shapes), so
+    two runs give the same fp32 bits whatever the workspace held before, and what they give is the sum of
+    the workspace's partial sums taken row by row in chunk order."""
+    if codec == oc.TANS and S == 32:
+        pytest.skip("the tANS payload needs at least 64 sub-streams")
+    print(f"case gemv bits S={S} codec={codec} {rows}x{cols} C={C} f={f}", flush=True)
+    seed = synth.matrix_seed(4, 1)
+    q, scale = oracle_matrix(rows, cols, seed, False)
+    c = oc.compress(q, C, S, oc.RAW_FRACTION, f, codec=codec)
+    x = synth.gen_activation_bf16(cols, seed)
+    blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
+    x_d = torch.from_numpy(x.view(np.int16)).cuda()
+    p = dc.Params(C, S, codec=codec)
+    runs = []
+    for fill in (0xFF, 0x00, 0x3C):
+        ws, ws_bytes = gemv_workspace(c.n_chunks)
+        ws.fill_(fill)
+        y32 = torch.full((rows + 3,), 7.0, dtype=torch.float32, device="cuda")
+        dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols, x_d, y32, None, ws, ws_bytes,
+                           stream())
+        torch.cuda.synchronize()
+        runs.append((y32.cpu().numpy(), ws.cpu().numpy().view(np.float32).reshape(c.n_chunks, 64)))
+    (y0, part), (y1, _), (y2, _) = runs
+    assert (y0[rows:] == 7.0).all()
+    assert np.array_equal(y0.view(np.uint32), y1.view(np.uint32)) and np.array_equal(y0.view(np.uint32), y2.view(np.uint32))
+    gemv_check(y0[:rows], oq.gemv_ref(q, scale, x))
+    # the second launch, redone on the host from the partial sums the first one left
+    want = np.zeros(rows, np.float32)
+    for i in range(rows):
+        total = np.float32(0.0)
+        for k in range(i * cols // C, ((i + 1) * cols - 1) // C + 1):
+            total = np.float32(total + part[k, i - k * C // cols])
+        want[i] = np.float32(scale[i] * total)
+    assert np.array_equal(want.view(np.uint32), y0[:rows].view(np.uint32))
 
 
 @pytest.mark.parametrize("S", [32, 64, 128, 256])

@@ -9,7 +9,7 @@ import oracle.codec as oc
 import oracle.quant as oq
 import paper_2502_15443_amd as dc
 import synth
-from tests.helpers import lopsided_bytes, weightlike_bytes
+from tests.helpers import gemv_workspace, lopsided_bytes, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -100,7 +100,7 @@ def test_random_valid_inputs_all_entry_points(seed):
         x = synth.gen_activation_bf16(cols, seed * 1000 + it)
         y32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
         dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols,
-                           torch.from_numpy(x.view(np.int16)).cuda(), y32, None, st)
+                           torch.from_numpy(x.view(np.int16)).cuda(), y32, None, *gemv_workspace(c.n_chunks), st)
         torch.cuda.synchronize()
         y = y32.cpu().numpy()
         y_ref = oq.gemv_ref(q, scale, x)

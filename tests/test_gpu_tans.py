@@ -6,7 +6,7 @@ import pytest
 
 import oracle.codec as oc
 import paper_2502_15443_amd as dc
-from tests.helpers import lopsided_bytes, weightlike_bytes
+from tests.helpers import gemv_workspace, lopsided_bytes, weightlike_bytes
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -137,7 +137,7 @@ def test_fused_calls_on_tans_blobs(S, rows, cols, C, policy):
     x = synth.gen_activation_bf16(cols, 99)
     y32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
     dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, p, scale_d, rows, cols,
-                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, stream())
+                       torch.from_numpy(x.view(np.int16)).cuda(), y32, None, *gemv_workspace(c.n_chunks), stream())
     xq = np.random.default_rng(S).integers(-127, 128, cols).astype(np.int8)
     sx = np.float32(0.021)
     z32 = torch.full((rows + 8,), 7.0, dtype=torch.float32, device="cuda")
