@@ -36,7 +36,27 @@
  *     chunk k decodes to bytes [k*chunk_bytes, k*chunk_bytes + raw_bytes) of the
  *     destination; only the last chunk may be shorter than chunk_bytes.
  *   blob                 the payloads back to back in chunk order, followed by DC_BLOB_TAIL_BYTES
- *                        zero bytes; blob_bytes counts them
+ *                        closing bytes; blob_bytes counts them.  The closing bytes are 48 zero bytes
+ *                        and the 16-byte trailer, which says how the blob is to be read:
+ *                          u32 DC_TRAILER_MAGIC ("DCBF")
+ *                          u16 DC_FORMAT_ID          u16 DC_LOOKAHEAD_BITS of that format
+ *                          u32 chunk_bytes
+ *                          u16 n_streams             u16 codec
+ *                        Blobs written with the same parameters can be put one after the other
+ *                        (table offsets moved accordingly): the last trailer closes the whole.
+ *   format id            DC_FORMAT_ID names this text as a whole.  Part of it is not of the method
+ *                        but of the decode kernel it was written with, and changes the bytes of a
+ *                        coded payload when it changes: DC_LOOKAHEAD_BITS and the five times of step 0
+ *                        (how far ahead of its position a stream's blocks are placed: the kernel
+ *                        keeps a block in flight for two steps), steps of half a group of 8 symbols
+ *                        (the kernel's unit between two refills of its ring), DC_BLOCK_BYTES (one
+ *                        128-bit load) and stream sets of 64 (one wavefront).  Earlier formats
+ *                        (look-ahead 320, sub-streams padded to whole blocks, no trailer) had none
+ *                        of this written into the blob; a blob without the trailer of this format
+ *                        is refused, never decoded: dc_validate and every dc_decompress_* call
+ *                        return DC_E_FORMAT when params->format is not DC_FORMAT_ID, dc_validate also
+ *                        when the trailer in the blob differs from what params say, and the decode
+ *                        kernels leave every chunk undecoded then.
  *   raw payload          the bytes, zero padded to a multiple of 16
  *   Huffman payload
  *       [0,128)          4-bit code length of byte value v in nibble (v & 1) of
@@ -130,7 +150,8 @@ extern "C" {
 #define DC_OK 0
 #define DC_E_ARG (-1)    /* bad argument: null pointer, misalignment, unsupported parameter */
 #define DC_E_CAP (-2)    /* an output buffer is too small; required sizes are written back where stated */
-#define DC_E_FORMAT (-3) /* dc_validate: table or payload violates the stored format */
+#define DC_E_FORMAT (-3) /* the blob is of another format than this library reads (params->format, trailer);
+                            dc_validate: table or payload violates the stored format */
 #define DC_E_HIP (-4)    /* a HIP runtime call failed (launch error, no device) */
 
 #define DC_CHUNK_RAW 0x80000000u
@@ -139,6 +160,9 @@ extern "C" {
 #define DC_BLOB_TAIL_BYTES 64
 #define DC_BLOCK_BYTES 16
 #define DC_LOOKAHEAD_BITS 392
+#define DC_FORMAT_ID 5
+#define DC_TRAILER_BYTES 16
+#define DC_TRAILER_MAGIC 0x46424344u /* the bytes 'D' 'C' 'B' 'F' */
 #define DC_MAX_MATRICES 16
 #define DC_TANS_STATE_BITS 11
 
@@ -171,6 +195,8 @@ typedef struct {
                                floor((double)raw_fraction * n_chunks + 0.5) of this 32-bit value */
     uint32_t block_chunks;  /* DC_POLICY_BLOCK_LAST: chunks per block, >= 1 */
     uint32_t codec;         /* DC_CODEC_*: the coder of the chunks that are not raw */
+    uint32_t format;        /* id of the stored format of the blob that is written or read: DC_FORMAT_ID;
+                               any other value is refused with DC_E_FORMAT */
     const uint8_t *raw_mask; /* DC_POLICY_RAW_MASK: host array of n_chunks bytes, else NULL */
 } dc_params;
 
@@ -300,10 +326,21 @@ int dc_compress_chunks_dev_static(const int8_t *src_dev, uint64_t raw_bytes, con
                                   uint64_t *result_dev, void *hip_stream);
 
 /*
- * Host-side check of a table and blob against the stored format: offsets, sizes, alignment, code
+ * Reads the trailer of a blob (its last DC_TRAILER_BYTES bytes, in host memory) into params_out:
+ * format, chunk_bytes, n_streams and codec; the other fields are set to 0.  DC_E_FORMAT when the bytes
+ * are not a trailer (no magic number) or name a format this library does not read; DC_E_ARG for null
+ * pointers.  For a caller who gets a blob from elsewhere and must know how to decode it.
+ */
+int dc_blob_trailer(const uint8_t *trailer_host, dc_params *params_out);
+
+/*
+ * Host-side check of a table and blob against the stored format: the trailer against params, offsets, sizes, alignment, code
  * lengths forming a complete code (tANS: frequencies adding up to 2048), sub-stream extents, and that
  * every sub-stream holds its symbols (tANS: and ends in state 0).
- * Returns DC_OK or DC_E_FORMAT (first offending chunk index in *bad_chunk when not NULL).
+ * Payloads must lie in the blob in chunk order without overlapping; bytes between them (the closing
+ * bytes of blobs that were put one after the other) are not looked at, and the table may be a part of a
+ * larger one (a layer of a model).  Returns DC_OK or DC_E_FORMAT (first offending chunk index in
+ * *bad_chunk when not NULL; n_chunks when it is the trailer that does not fit params).
  */
 int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *table_host,
                 uint64_t n_chunks, const dc_params *params, uint64_t *bad_chunk);
@@ -312,7 +349,9 @@ int dc_validate(const uint8_t *blob_host, uint64_t blob_bytes, const dc_chunk *t
  * GPU decompression into the decompression buffer (Section 3.3, "Inference Process" and
  * "Throughput Analysis": compressed chunks resident in GPU memory are decompressed by the GPU into
  * a buffer in GPU memory from which inference reads the weights).  One kernel launch.
- *   blob_dev, blob_bytes   the blob, 16-byte aligned
+ *   blob_dev, blob_bytes   the blob, 16-byte aligned, up to and with its closing bytes (blob_bytes a
+ *                          multiple of 16); a launch whose blob does not end in the trailer that params
+ *                          describe decodes nothing
  *   table_dev, n_chunks    chunk table in device memory
  *   dst_dev, dst_cap       destination, 16-byte aligned; needs (n_chunks-1)*chunk_bytes + last chunk's
  *                          raw_bytes bytes; the host checks dst_cap >= (n_chunks-1)*chunk_bytes + 1 and

@@ -88,6 +88,10 @@ def lib():
             L.orc_decompress.argtypes = [vp, C.c_uint64, vp, C.c_uint64, C.c_uint64, C.c_uint32,
                                          C.c_uint32, vp]
             L.orc_decompress.restype = C.c_int
+            L.orc_close_blob.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int]
+            L.orc_close_blob.restype = C.c_int
+            L.orc_check_trailer.argtypes = [vp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int]
+            L.orc_check_trailer.restype = C.c_int
             _lib = L
     return _lib
 
@@ -241,6 +245,8 @@ def compress(data, chunk_bytes: int, n_streams: int, policy: int = ALL_HUFF, raw
     blob = np.zeros(total, dtype=np.uint8)
     _run_ranges(lambda a, b: L.orc_emit_codec(_ptr(src), n, chunk_bytes, n_streams, codec, _ptr(table), a, b,
                                               _ptr(blob)), nc, threads)
+    if L.orc_close_blob(_ptr(blob), total, chunk_bytes, n_streams, codec) != 0:
+        raise ValueError("orc_close_blob failed")
     return Compressed(blob, table, n, chunk_bytes, n_streams, codec)
 
 

@@ -19,8 +19,9 @@
  *     u64 off          payload offset in the blob, multiple of 16
  *     u32 comp_bytes   payload size including padding, multiple of 16
  *     u32 raw_bytes | RAW<<31
- *   blob              the payloads back to back in chunk order, then 64 zero
- *                     bytes
+ *   blob              the payloads back to back in chunk order, then 64
+ *                     closing bytes: 48 zeros and a trailer of 16 bytes that
+ *                     names the format and the parameters (orc_close_blob)
  *   raw payload       raw_bytes bytes, zero padded to 16
  *   Huffman payload
  *     [0,128)          code length of byte value v in nibble (v&1) of byte v>>1
@@ -80,6 +81,10 @@
 
 #define ORC_RAW_FLAG 0x80000000u
 #define ORC_BLOB_TAIL 64
+/* format 5 of the container: sub-streams cut to bytes with a short first block, look-ahead of 392
+ * bits, and a trailer in the blob's closing bytes that says so */
+#define ORC_FORMAT 5
+#define ORC_LOOKAHEAD_IN_TRAILER 392
 
 enum { ORC_ALL_HUFF = 0, ORC_AUTO = 1, ORC_RAW_FRACTION = 2, ORC_RAW_MASK = 3, ORC_BLOCK_LAST = 4 };
 
@@ -946,7 +951,7 @@ int orc_select_raw(const uint32_t *huff_bytes, uint64_t n, uint32_t C, uint64_t 
 }
 
 /* Offsets and sizes of every payload, laid out back to back.  Returns the blob size, which
- * includes the 64 zero bytes that close the blob. */
+ * includes the 64 bytes that close the blob (orc_close_blob writes them). */
 uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t n, uint32_t C,
                     uint64_t n_chunks, orc_chunk *table)
 {
@@ -964,6 +969,48 @@ uint64_t orc_layout(const uint32_t *huff_bytes, const uint8_t *is_raw, uint64_t 
         off += table[k].comp_bytes;
     }
     return off + ORC_BLOB_TAIL;
+}
+
+/*
+ * The blob's closing bytes: 48 zero bytes, then the trailer of 16 bytes, little endian:
+ *   bytes 0-3  'D' 'C' 'B' 'F'
+ *   bytes 4-5  format id (5)            bytes 6-7   look-ahead bits of the placement rule (392)
+ *   bytes 8-11 chunk size C
+ *   bytes 12-13 sub-streams S           bytes 14-15 coder (0 Huffman, 1 tANS)
+ * A reader that finds anything else at the end of a blob must not decode it.
+ */
+static void put_le(uint8_t *at, uint64_t v, int bytes)
+{
+    for (int i = 0; i < bytes; i++)
+        at[i] = (uint8_t)(v >> (8 * i));
+}
+
+static void make_trailer(uint32_t C, uint32_t S, int codec, uint8_t *t)
+{
+    t[0] = 'D'; t[1] = 'C'; t[2] = 'B'; t[3] = 'F';
+    put_le(t + 4, ORC_FORMAT, 2);
+    put_le(t + 6, ORC_LOOKAHEAD_IN_TRAILER, 2);
+    put_le(t + 8, C, 4);
+    put_le(t + 12, S, 2);
+    put_le(t + 14, (uint64_t)codec, 2);
+}
+
+int orc_close_blob(uint8_t *blob, uint64_t blob_bytes, uint32_t C, uint32_t S, int codec)
+{
+    if (blob_bytes < ORC_BLOB_TAIL)
+        return ORC_E_ARG;
+    memset(blob + blob_bytes - ORC_BLOB_TAIL, 0, ORC_BLOB_TAIL);
+    make_trailer(C, S, codec, blob + blob_bytes - 16);
+    return ORC_OK;
+}
+
+int orc_check_trailer(const uint8_t *blob, uint64_t blob_bytes, uint32_t C, uint32_t S, int codec)
+{
+    uint8_t want[16];
+    if (blob_bytes < ORC_BLOB_TAIL)
+        return ORC_E_FORMAT;
+    make_trailer(C, S, codec, want);
+    return memcmp(blob + blob_bytes - 16, want, 16) == 0 ? ORC_OK : ORC_E_FORMAT;
 }
 
 /* Write the payloads of chunks k0 <= k < k1 at the offsets the table gives. */
@@ -997,6 +1044,8 @@ int orc_emit(const uint8_t *src, uint64_t n, uint32_t C, uint32_t S, const orc_c
 int orc_decompress_codec(const uint8_t *blob, uint64_t blob_bytes, const orc_chunk *table, uint64_t k0,
                          uint64_t k1, uint32_t C, uint32_t S, int codec, uint8_t *dst)
 {
+    if (orc_check_trailer(blob, blob_bytes, C, S, codec) != ORC_OK)
+        return ORC_E_FORMAT;
     for (uint64_t k = k0; k < k1; k++) {
         uint32_t raw = table[k].raw_bytes_flags & ~ORC_RAW_FLAG;
         if (raw == 0 || raw > C)

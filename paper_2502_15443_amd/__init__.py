@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     CHUNK_DTYPE,
     CODEC_HUFFMAN,
     CODEC_TANS,
+    FORMAT_ID,
     POLICY_ALL_HUFF,
     POLICY_AUTO,
     POLICY_RAW_FRACTION,
@@ -29,6 +30,7 @@ from .binding import (  # noqa: F401
     compress_chunks_dev_workspace,
     compress_chunks_dev_static,
     validate,
+    blob_trailer,
     decompress_chunks,
     decompress_dequant_bf16,
     decompress_gemv,

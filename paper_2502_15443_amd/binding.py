@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "libdc_mi355x.so")
 
 POLICY_ALL_HUFF, POLICY_AUTO, POLICY_RAW_FRACTION, POLICY_RAW_MASK, POLICY_BLOCK_LAST = 0, 1, 2, 3, 4
 CODEC_HUFFMAN, CODEC_TANS = 0, 1
+FORMAT_ID = 5  # DC_FORMAT_ID of include/dc.h
 CHUNK_RAW = 0x80000000
 STATIC_SCRATCH_BYTES = 16 << 20
 CHUNK_DTYPE = np.dtype([("off", "<u8"), ("comp_bytes", "<u4"), ("raw_bytes_flags", "<u4")])
@@ -31,7 +32,7 @@ class DCError(RuntimeError):
 class _CParams(C.Structure):
     _fields_ = [("chunk_bytes", C.c_uint32), ("n_streams", C.c_uint32), ("policy", C.c_uint32),
                 ("raw_fraction", C.c_float), ("block_chunks", C.c_uint32), ("codec", C.c_uint32),
-                ("raw_mask", C.c_void_p)]
+                ("format", C.c_uint32), ("raw_mask", C.c_void_p)]
 
 
 class _CMatrix(C.Structure):
@@ -66,10 +67,11 @@ class Params:
     block_chunks: int = 0
     raw_mask: Optional[np.ndarray] = None
     codec: int = CODEC_HUFFMAN
+    format: int = FORMAT_ID
 
     def _c(self) -> _CParams:
         p = _CParams(self.chunk_bytes, self.n_streams, self.policy, float(self.raw_fraction),
-                     self.block_chunks, self.codec, None)
+                     self.block_chunks, self.codec, self.format, None)
         if self.raw_mask is not None:
             self._mask_keepalive = np.ascontiguousarray(self.raw_mask, dtype=np.uint8)
             p.raw_mask = self._mask_keepalive.ctypes.data
@@ -117,6 +119,8 @@ def _load():
     L.dc_compress_chunks_dev.argtypes = [vp, u64, pp, vp, u64, vp, u64, vp, u64, vp, vp]
     L.dc_compress_chunks_dev_static.restype = i32
     L.dc_compress_chunks_dev_static.argtypes = [vp, u64, pp, vp, u64, vp, u64, vp, vp]
+    L.dc_blob_trailer.restype = i32
+    L.dc_blob_trailer.argtypes = [vp, pp]
     L.dc_validate.restype = i32
     L.dc_validate.argtypes = [vp, u64, vp, u64, pp, pu64]
     L.dc_decompress_chunks.restype = i32
@@ -256,6 +260,14 @@ def compress_chunks_dev_static(src_dev, raw_bytes: int, params: Params, blob_dev
     _check(_L.dc_compress_chunks_dev_static(_dev(src_dev), raw_bytes, C.byref(cp), _dev(blob_dev), blob_cap,
                                             _dev(table_dev), table_cap, _dev(result_dev), stream),
            "dc_compress_chunks_dev_static")
+
+
+def blob_trailer(blob: np.ndarray) -> Params:
+    """dc_blob_trailer on the last 16 bytes of a blob in host memory: the parameters a reader needs."""
+    t = np.ascontiguousarray(np.asarray(blob, dtype=np.uint8).reshape(-1)[-16:])
+    cp = _CParams()
+    _check(_L.dc_blob_trailer(_host(t), C.byref(cp)), "dc_blob_trailer")
+    return Params(cp.chunk_bytes, cp.n_streams, codec=cp.codec, format=cp.format)
 
 
 def validate(blob: np.ndarray, table: np.ndarray, params: Params) -> None:

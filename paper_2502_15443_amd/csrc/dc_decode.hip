@@ -67,6 +67,7 @@ struct DecodeArgs {
     const dc_chunk *table;
     uint64_t n_chunks;
     uint32_t chunk_bytes;
+    uint32_t trailer[4]; // what the blob's last 16 bytes must be for this launch to decode it
     // kModeI8: all chunks decode into one buffer of dst_cap bytes
     void *dst;
     uint64_t dst_cap;
@@ -584,8 +585,12 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     const uint32_t ct = wave * 64 + cl;          // thread inside the chunk = sub-stream number
     const uint64_t k = (uint64_t)blockIdx.x * CPW + sub;
 
+    // ---- the blob's trailer: a blob of another format, or of other parameters, is left undecoded
+    const uint32_t *closing = reinterpret_cast<const uint32_t *>(a.blob + a.blob_bytes - DC_TRAILER_BYTES);
+    const bool readable = closing[0] == a.trailer[0] && closing[1] == a.trailer[1] && closing[2] == a.trailer[2] &&
+                          closing[3] == a.trailer[3];
     // ---- chunk table entry, checked so that nothing below can leave the blob or the destination
-    bool active = k < a.n_chunks;
+    bool active = readable && k < a.n_chunks;
     dc_chunk ent = {0, 0, 0};
     if (active) ent = a.table[k];
     const uint32_t raw = ent.raw_bytes_flags & ~DC_CHUNK_RAW;
@@ -1152,6 +1157,21 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 
 int launch_status() { return dc_launch_status(); }
 
+// Kernel arguments every decode launch shares; the trailer is what a blob of these parameters ends with.
+void common_args(DecodeArgs &a, const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev, uint64_t n_chunks,
+                 const dc_params *p)
+{
+    a.blob = blob_dev;
+    a.blob_bytes = blob_bytes;
+    a.table = table_dev;
+    a.n_chunks = n_chunks;
+    a.chunk_bytes = p->chunk_bytes;
+    a.trailer[0] = DC_TRAILER_MAGIC;
+    a.trailer[1] = DC_FORMAT_ID | (uint32_t)DC_LOOKAHEAD_BITS << 16;
+    a.trailer[2] = p->chunk_bytes;
+    a.trailer[3] = p->n_streams | p->codec << 16;
+}
+
 bool decode_params_ok(const dc_params *p)
 {
     if (!p) return false;
@@ -1211,16 +1231,14 @@ extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes
                                     uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
                                     void *hip_stream)
 {
-    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_dev || n_chunks == 0 || blob_bytes < 16)
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_dev || n_chunks == 0 ||
+        blob_bytes < DC_BLOB_TAIL_BYTES || blob_bytes % 16)
         return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
     if (!aligned16(blob_dev) || !aligned16(dst_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
     if (dst_cap < (n_chunks - 1) * (uint64_t)params->chunk_bytes + 1) return DC_E_CAP;
     DecodeArgs a = {};
-    a.blob = blob_dev;
-    a.blob_bytes = blob_bytes;
-    a.table = table_dev;
-    a.n_chunks = n_chunks;
-    a.chunk_bytes = params->chunk_bytes;
+    common_args(a, blob_dev, blob_bytes, table_dev, n_chunks, params);
     a.dst = dst_dev;
     a.dst_cap = dst_cap;
     return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream), params->codec);
@@ -1233,15 +1251,12 @@ int fused_args(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *tab
                const dc_params *params, const dc_matrix *mats, uint32_t n_mats, int mode, DecodeArgs &a)
 {
     if (!decode_params_ok(params) || !blob_dev || !table_dev || !mats || n_mats == 0 || n_mats > DC_MAX_MATRICES ||
-        n_chunks == 0 || blob_bytes < 16)
+        n_chunks == 0 || blob_bytes < DC_BLOB_TAIL_BYTES || blob_bytes % 16)
         return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
     if (!aligned16(blob_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u)) return DC_E_ARG;
     a = DecodeArgs{};
-    a.blob = blob_dev;
-    a.blob_bytes = blob_bytes;
-    a.table = table_dev;
-    a.n_chunks = n_chunks;
-    a.chunk_bytes = params->chunk_bytes;
+    common_args(a, blob_dev, blob_bytes, table_dev, n_chunks, params);
     a.n_mats = n_mats;
     uint64_t next_chunk = 0;
     for (uint32_t i = 0; i < n_mats; i++) {

@@ -536,8 +536,17 @@ __global__ __launch_bounds__(256) void dc_layout_kernel(EncArgs a)
         }
         a.result[0] = run + DC_BLOB_TAIL_BYTES;
         a.result[1] = run + DC_BLOB_TAIL_BYTES > a.blob_cap ? (uint64_t)(int64_t)DC_E_CAP : 0;
-        if (run + DC_BLOB_TAIL_BYTES <= a.blob_cap)
-            for (int i = 0; i < DC_BLOB_TAIL_BYTES; i++) a.blob[run + i] = 0;
+        if (run + DC_BLOB_TAIL_BYTES <= a.blob_cap) {
+            // the closing bytes: zeros, then the trailer (magic number, format id and look-ahead, chunk size,
+            // sub-streams and coder); the blob is 16-byte aligned and so is `run`
+            uint32_t *closing = reinterpret_cast<uint32_t *>(a.blob + run);
+            for (int i = 0; i < (DC_BLOB_TAIL_BYTES - DC_TRAILER_BYTES) / 4; i++) closing[i] = 0;
+            uint32_t *trailer = closing + (DC_BLOB_TAIL_BYTES - DC_TRAILER_BYTES) / 4;
+            trailer[0] = DC_TRAILER_MAGIC;
+            trailer[1] = DC_FORMAT_ID | (uint32_t)DC_LOOKAHEAD_BITS << 16;
+            trailer[2] = a.chunk_bytes;
+            trailer[3] = a.S | a.codec << 16;
+        }
     }
     __syncthreads();
     uint64_t off = part[t];
@@ -869,6 +878,7 @@ uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
 extern "C" int dc_compress_chunks_dev_workspace(uint64_t raw_bytes, const dc_params *params, uint64_t *workspace_bytes)
 {
     if (!enc_params_ok(params) || raw_bytes == 0 || !workspace_bytes) return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
     const uint64_t nc = (raw_bytes + params->chunk_bytes - 1) / params->chunk_bytes;
     *workspace_bytes = align256(nc * 256) + align256(nc * params->n_streams * 4) + align256(nc * 4);
     // tANS: the frequencies, the first states and one 16-bit item per byte besides
@@ -886,7 +896,7 @@ int compress_chunks_on_stream(const int8_t *src_dev, uint64_t raw_bytes, const d
                               uint64_t workspace_bytes, uint64_t *result_dev, void *hip_stream)
 {
     uint64_t need = 0;
-    if (dc_compress_chunks_dev_workspace(raw_bytes, params, &need) != DC_OK) return DC_E_ARG;
+    if (const int rc = dc_compress_chunks_dev_workspace(raw_bytes, params, &need)) return rc;
     if (!src_dev || !blob_dev || !table_dev || !workspace_dev || !result_dev) return DC_E_ARG;
     if ((reinterpret_cast<uintptr_t>(src_dev) & 15u) || (reinterpret_cast<uintptr_t>(blob_dev) & 15u) ||
         (reinterpret_cast<uintptr_t>(table_dev) & 7u) || (reinterpret_cast<uintptr_t>(workspace_dev) & 15u) ||
@@ -988,7 +998,7 @@ extern "C" int dc_compress_chunks_dev_static(const int8_t *src_dev, uint64_t raw
                                              uint64_t table_cap, uint64_t *result_dev, void *hip_stream)
 {
     uint64_t need = 0;
-    if (dc_compress_chunks_dev_workspace(raw_bytes, params, &need) != DC_OK) return DC_E_ARG;
+    if (const int rc = dc_compress_chunks_dev_workspace(raw_bytes, params, &need)) return rc;
     if (need > DC_STATIC_SCRATCH_BYTES) return DC_E_CAP; // the input is beyond what the fixed workspace serves
     void *ws = static_scratch();
     if (!ws) return DC_E_HIP;

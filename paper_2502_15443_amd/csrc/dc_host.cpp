@@ -57,6 +57,21 @@ bool params_ok(const dc_params *p)
     return true;
 }
 
+// The 16 bytes that close a blob: magic number, format id and its look-ahead, and the parameters a reader needs.
+void write_trailer(uint8_t *at, const dc_params *p)
+{
+    const uint32_t words[4] = {DC_TRAILER_MAGIC, DC_FORMAT_ID | (uint32_t)DC_LOOKAHEAD_BITS << 16, p->chunk_bytes,
+                               p->n_streams | p->codec << 16};
+    std::memcpy(at, words, sizeof(words));
+}
+
+bool trailer_matches(const uint8_t *at, const dc_params *p)
+{
+    uint8_t want[DC_TRAILER_BYTES];
+    write_trailer(want, p);
+    return std::memcmp(at, want, sizeof(want)) == 0;
+}
+
 inline uint32_t chunk_len(uint64_t total, uint32_t C, uint64_t k)
 {
     const uint64_t lo = k * C;
@@ -424,7 +439,22 @@ void write_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook 
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.4 (gfx950; canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.5 (gfx950; stored format 5: canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks, trailer)"; }
+
+extern "C" int dc_blob_trailer(const uint8_t *trailer_host, dc_params *params_out)
+{
+    if (!trailer_host || !params_out) return DC_E_ARG;
+    uint32_t words[4];
+    std::memcpy(words, trailer_host, sizeof(words));
+    if (words[0] != DC_TRAILER_MAGIC) return DC_E_FORMAT;
+    *params_out = dc_params{};
+    params_out->format = words[1] & 0xFFFFu;
+    params_out->chunk_bytes = words[2];
+    params_out->n_streams = words[3] & 0xFFFFu;
+    params_out->codec = words[3] >> 16;
+    if (params_out->format != DC_FORMAT_ID || (words[1] >> 16) != DC_LOOKAHEAD_BITS) return DC_E_FORMAT;
+    return DC_OK;
+}
 
 extern "C" const char *dc_strerror(int code)
 {
@@ -432,7 +462,7 @@ extern "C" const char *dc_strerror(int code)
     case DC_OK: return "DC_OK";
     case DC_E_ARG: return "DC_E_ARG: bad argument";
     case DC_E_CAP: return "DC_E_CAP: output buffer too small";
-    case DC_E_FORMAT: return "DC_E_FORMAT: table or payload violates the stored format";
+    case DC_E_FORMAT: return "DC_E_FORMAT: blob of another stored format, or table or payload violates the format";
     case DC_E_HIP: return "DC_E_HIP: HIP runtime call failed";
     default: return "unknown dc error code";
     }
@@ -571,6 +601,7 @@ extern "C" int dc_compress_bound(uint64_t raw_bytes, const dc_params *params, ui
                                  uint64_t *n_chunks)
 {
     if (!params_ok(params) || raw_bytes == 0) return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
     const uint64_t nc = (raw_bytes + C - 1) / C;
     // worst Huffman payload: header, 11 bits a byte, one partial block per stream
@@ -587,6 +618,7 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
                                   uint64_t table_cap, uint64_t *n_chunks_out)
 {
     if (!params_ok(params) || !src_i8 || raw_bytes == 0 || !blob_bytes || !n_chunks_out) return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
     const uint8_t *src = reinterpret_cast<const uint8_t *>(src_i8);
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
     const uint64_t nc = (raw_bytes + C - 1) / C;
@@ -669,6 +701,7 @@ extern "C" int dc_compress_chunks(const int8_t *src_i8, uint64_t raw_bytes, cons
     }
 
     std::memset(blob + off, 0, DC_BLOB_TAIL_BYTES);
+    write_trailer(blob + off + DC_BLOB_TAIL_BYTES - DC_TRAILER_BYTES, params);
 
     // pass 2: emit
     parallel_ranges(nc, [&](uint64_t k0, uint64_t k1) {
@@ -850,7 +883,16 @@ extern "C" int dc_validate(const uint8_t *blob, uint64_t blob_bytes, const dc_ch
                            const dc_params *params, uint64_t *bad_chunk)
 {
     if (!params_ok(params) || !blob || !table || n_chunks == 0) return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) {
+        if (bad_chunk) *bad_chunk = n_chunks;
+        return DC_E_FORMAT;
+    }
     const uint32_t C = params->chunk_bytes, S = params->n_streams;
+    // the blob ends with the trailer of this format and of these parameters
+    if (blob_bytes < DC_BLOB_TAIL_BYTES || !trailer_matches(blob + blob_bytes - DC_TRAILER_BYTES, params)) {
+        if (bad_chunk) *bad_chunk = n_chunks;
+        return DC_E_FORMAT;
+    }
     {
         // the blob must extend DC_BLOB_TAIL_BYTES beyond the last payload
         const dc_chunk &last = table[n_chunks - 1];
@@ -867,8 +909,9 @@ extern "C" int dc_validate(const uint8_t *blob, uint64_t blob_bytes, const dc_ch
             const uint32_t raw = e.raw_bytes_flags & ~DC_CHUNK_RAW;
             bool ok = raw >= 1 && raw <= C && (k + 1 == n_chunks || raw == C) && e.off % 16 == 0 &&
                       e.comp_bytes % 16 == 0 && e.off <= blob_bytes && e.comp_bytes <= blob_bytes - e.off;
-            if (ok && k > 0) ok = e.off == table[k - 1].off + table[k - 1].comp_bytes;
-            if (ok && k == 0) ok = e.off == 0;
+            // in chunk order, not overlapping; what lies between two payloads (the closing bytes of a blob
+            // that another was appended to) is not a payload's business
+            if (ok && k > 0) ok = e.off >= table[k - 1].off && e.off - table[k - 1].off >= table[k - 1].comp_bytes;
             if (ok) {
                 if (e.raw_bytes_flags & DC_CHUNK_RAW) ok = e.comp_bytes == align_up(raw, 16);
                 else ok = coded_payload_ok(blob + e.off, e.comp_bytes, raw, S, params->codec);

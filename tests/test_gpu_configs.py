@@ -249,6 +249,7 @@ def test_offsets_beyond_4_gib_in_blob_and_destination(codec):
             low_end += padded
         blob_d[base:base + size] = torch.from_numpy(c.blob[off:off + size].copy()).cuda()
         place[r] = base
+    blob_d[blob_bytes - 64:] = torch.from_numpy(c.blob[-64:].copy()).cuda()  # the closing bytes with the trailer
     for k in range(n_chunks):
         r = 8 if k == n_chunks - 1 else k % 8
         table[k] = (place[r], c.table["comp_bytes"][r], c.table["raw_bytes_flags"][r])

@@ -146,6 +146,59 @@ def test_destination_untouched_beyond_decoded_bytes():
     assert np.array_equal(out[:n], data) and (out[n:] == 0x5A).all()
 
 
+@pytest.mark.parametrize("S,codec", [(32, oc.HUFFMAN), (256, oc.HUFFMAN), (64, oc.TANS)])
+def test_blob_of_another_format_is_not_decoded(S, codec):
+    """A blob that a writer of format 3 would have closed (look-ahead 320), one without a trailer, one of
+    another coder or sub-stream count than the caller says: every decode call leaves its output untouched
+    (the kernels compare the blob's last 16 bytes with what the parameters imply), and a caller that states
+    another format id is refused on the host with DC_E_FORMAT."""
+    print(f"case other format S={S} codec={codec}", flush=True)
+    C, rows, cols = 16384, 64, 1024
+    q, scale = oracle_matrix(rows, cols, synth.matrix_seed(7, 2), False)
+    n = q.size
+    c = oc.compress(q, C, S, codec=codec)
+    p = dc.Params(C, S, codec=codec)
+    scale_d = torch.from_numpy(scale).cuda()
+    x_d = torch.from_numpy(synth.gen_activation_bf16(cols, 5).view(np.int16)).cuda()
+    old = c.blob.copy()
+    old[-12:-8] = np.frombuffer((3).to_bytes(2, "little") + (320).to_bytes(2, "little"), np.uint8)
+    bare = c.blob.copy()
+    bare[-16:] = 0
+    params_differ = [dc.Params(C, 64 if S != 64 else 128, codec=codec), dc.Params(C, max(S, 64), codec=1 - codec),
+                     dc.Params(2 * C, S, codec=codec)]
+    cases = [(old, p), (bare, p)] + [(c.blob, pp) for pp in params_differ]
+    for blob, pp in cases:
+        blob_d, table_d = dev(blob), dev(c.table)
+        dst = torch.full((2 * n,), 0x5A, dtype=torch.uint8, device="cuda")
+        out16 = torch.full((n,), 0x5A5A, dtype=torch.int16, device="cuda")
+        dc.decompress_chunks(blob_d, blob.size, table_d, c.n_chunks, pp, dst, 2 * n, stream())
+        if pp.chunk_bytes == C:
+            dc.decompress_dequant_bf16(blob_d, blob.size, table_d, c.n_chunks, pp, scale_d, rows, cols, out16, n, stream())
+        torch.cuda.synchronize()
+        assert (dst.cpu().numpy() == 0x5A).all() and (out16.cpu().numpy() == 0x5A5A).all()
+    # the blob as it is decodes
+    blob_d, table_d = dev(c.blob), dev(c.table)
+    dst = torch.full((n,), 0x5A, dtype=torch.uint8, device="cuda")
+    dc.decompress_chunks(blob_d, c.blob.size, table_d, c.n_chunks, p, dst, n, stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), q.view(np.uint8).ravel())
+    stale = dc.Params(C, S, codec=codec, format=4)
+    y32 = torch.zeros(rows, dtype=torch.float32, device="cuda")
+    calls = [
+        lambda: dc.decompress_chunks(blob_d, c.blob.size, table_d, c.n_chunks, stale, dst, n, stream()),
+        lambda: dc.decompress_dequant_bf16(blob_d, c.blob.size, table_d, c.n_chunks, stale, scale_d, rows, cols,
+                                           torch.zeros(n, dtype=torch.int16, device="cuda"), n, stream()),
+        lambda: dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, stale, scale_d, rows, cols, x_d, y32, None,
+                                   *gemv_workspace(c.n_chunks), stream()),
+        lambda: dc.decompress_gemv_w8a8(blob_d, c.blob.size, table_d, c.n_chunks, stale, scale_d, rows, cols,
+                                        torch.zeros(cols, dtype=torch.int8, device="cuda"), 1.0, y32, None, stream()),
+    ]
+    for call in calls:
+        with pytest.raises(dc.DCError) as e:
+            call()
+        assert e.value.code == -3
+
+
 @pytest.mark.parametrize("S", [32, 256])
 def test_corrupt_payloads_and_table_entries_stay_inside_the_buffers(S):
     """Whatever the payloads and the table hold, the kernels read inside the blob and write inside the

@@ -228,8 +228,100 @@ def test_validate_catches_corruption():
     expect_bad(blob, t, 3)
     t = table.copy(); t["comp_bytes"][-1] += 1 << 20  # beyond the blob
     expect_bad(blob, t, len(t) - 1)
-    expect_bad(blob[:o + 64].copy(), table, len(table) - 1)  # truncated blob
-    expect_bad(blob[:-1].copy(), table, len(table) - 1)  # closing 64 zero bytes incomplete
+    expect_bad(blob[:o + 64].copy(), table, len(table))  # truncated blob: it no longer ends in its trailer
+    expect_bad(blob[:-1].copy(), table, len(table))
+    b = np.concatenate([blob[:-64], blob[-16:]])  # the trailer right behind the last payload: closing bytes incomplete
+    expect_bad(b, table, len(table) - 1)
+
+
+def test_trailer_names_format_and_parameters():
+    """The blob's last 16 bytes, spelled out: 'DCBF', format id 5, look-ahead 392, chunk size, sub-streams,
+    coder; the same bytes from the oracle; and every host entry point refuses another format id."""
+    for C, S, codec in [(4096, 32, dc.CODEC_HUFFMAN), (65536, 256, dc.CODEC_TANS), (1 << 20, 64, dc.CODEC_HUFFMAN)]:
+        data = weightlike_bytes(C + 100, 5)
+        p = dc.Params(C, S, codec=codec)
+        blob, table = dc.compress_chunks(data, p)
+        want = b"DCBF" + (5).to_bytes(2, "little") + (392).to_bytes(2, "little") + C.to_bytes(4, "little") \
+            + S.to_bytes(2, "little") + codec.to_bytes(2, "little")
+        assert blob[-16:].tobytes() == want and not blob[-64:-16].any()
+        assert oc.compress(data, C, S, codec=codec).blob[-64:].tobytes() == blob[-64:].tobytes()
+        got = dc.blob_trailer(blob)
+        assert (got.chunk_bytes, got.n_streams, got.codec, got.format) == (C, S, codec, dc.FORMAT_ID)
+    with pytest.raises(dc.DCError) as e:
+        dc.blob_trailer(np.zeros(64, np.uint8))  # a blob of the formats before this one ended in zeros
+    assert e.value.code == -3
+
+
+def test_blob_of_another_format_is_refused():
+    """A blob as format 3 would have closed it (look-ahead 320), one without a trailer, and one whose trailer
+    names other parameters: dc_validate returns DC_E_FORMAT for each, the oracle's decoder refuses them too,
+    and a caller that states another format id is refused by every entry point that takes parameters."""
+    C, S = 4096, 64
+    data = weightlike_bytes(3 * C, 6)
+    p = dc.Params(C, S)
+    blob, table = dc.compress_chunks(data, p)
+    dc.validate(blob, table, p)
+    old = blob.copy()
+    old[-12:-8] = np.frombuffer((3).to_bytes(2, "little") + (320).to_bytes(2, "little"), np.uint8)
+    bare = blob.copy()
+    bare[-16:] = 0
+    other = blob.copy()
+    other[-4] = 128  # says 128 sub-streams
+    for b in (old, bare, other):
+        with pytest.raises(dc.DCError) as e:
+            dc.validate(b, table, p)
+        assert e.value.code == -3 and f"chunk {len(table)})" in str(e.value)
+        with pytest.raises(ValueError):
+            oc.decompress(b, table, C, S, data.size)
+    with pytest.raises(dc.DCError) as e:
+        dc.blob_trailer(old)
+    assert e.value.code == -3
+    stale = dc.Params(C, S, format=4)
+    for call in (lambda: dc.validate(blob, table, stale), lambda: dc.compress_chunks(data, stale),
+                 lambda: dc.compress_bound(data.size, stale), lambda: dc.compress_chunks_dev_workspace(data.size, stale)):
+        with pytest.raises(dc.DCError) as e:
+            call()
+        assert e.value.code == -3
+
+
+def test_validate_takes_appended_blobs_and_parts_of_a_table():
+    """Blobs put one after the other (a layer's matrices, each compressed alone, offsets moved) and a part of
+    such a table (one matrix of the layer): both are what the decode calls take, and the validator checks them."""
+    C, S = 4096, 64
+    p = dc.Params(C, S, dc.POLICY_AUTO)
+    parts = [weightlike_bytes(n, 40 + i) for i, n in enumerate((5 * C, 2 * C + 7, 3 * C))]
+    blobs, tables, off = [], [], 0
+    for d in parts:
+        b, t = dc.compress_chunks(d, p)
+        t = t.copy()
+        t["off"] += off
+        off += b.size
+        blobs.append(b)
+        tables.append(t)
+    blob, table = np.concatenate(blobs), np.concatenate(tables)
+    with pytest.raises(dc.DCError):  # as one table it is not one byte string: the middle part ends in a short chunk
+        dc.validate(blob, table, p)
+    k = 0
+    for t in tables:  # every part on its own, against the whole blob
+        dc.validate(blob, table[k:k + len(t)], p)
+        k += len(t)
+    whole = [weightlike_bytes(n, 50 + i) for i, n in enumerate((5 * C, 2 * C, 3 * C))]
+    blobs, tables, off = [], [], 0
+    for d in whole:
+        b, t = dc.compress_chunks(d, p)
+        t = t.copy()
+        t["off"] += off
+        off += b.size
+        blobs.append(b)
+        tables.append(t)
+    blob, table = np.concatenate(blobs), np.concatenate(tables)
+    dc.validate(blob, table, p)
+    assert np.array_equal(oc.decompress(blob, table, C, S, 10 * C), np.concatenate(whole))
+    t = table.copy()
+    t["off"][6] -= 16  # a payload that begins inside the one before it
+    with pytest.raises(dc.DCError) as e:
+        dc.validate(blob, t, p)
+    assert "chunk 6)" in str(e.value)
 
 
 def test_compress_bound_holds_on_worst_case():

@@ -401,7 +401,10 @@ def test_whole_buffer_round_trip_ragged_tail():
     assert int(c.table["raw_bytes_flags"][-1]) == 777
     assert (np.diff(c.table["off"].astype(np.int64)) == c.table["comp_bytes"][:-1]).all()
     assert c.blob.size == int(c.table["off"][-1]) + int(c.table["comp_bytes"][-1]) + 64
-    assert not c.blob[-64:].any()  # the blob closes with 64 zero bytes
+    # the blob closes with 48 zero bytes and the trailer: magic, format 5, look-ahead 392, C, S, coder 0
+    assert not c.blob[-64:-16].any()
+    assert c.blob[-16:].tobytes() == b"DCBF" + bytes([5, 0, 392 & 255, 392 >> 8]) + (16384).to_bytes(4, "little") \
+        + (32).to_bytes(2, "little") + bytes(2)
     out = oc.decompress(c.blob, c.table, 16384, 32, data.size)
     assert (out == data).all()
     out2 = oc.decompress(c.blob, c.table, 16384, 32, data.size, threads=3)
