@@ -10,7 +10,7 @@ import oracle.quant as oq
 import synth
 
 
-@functools.lru_cache(maxsize=40)
+@functools.lru_cache(maxsize=64)
 def oracle_matrix(rows: int, cols: int, seed: int, rescale: bool):
     """(q int8[rows, cols], row_scale fp32[rows]) by the oracle: generate, (rescale), quantise, prune."""
     w = synth.gen_weight(rows, cols, seed)

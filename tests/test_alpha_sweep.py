@@ -1,0 +1,53 @@
+"""The paper's own compression stage on a small synthetic tensor (Section 3.2: per-tensor scale, rescale
+s = a^alpha of Eq. 2, score pruning of Eq. 5) over the grid of its ablation on alpha (Section 4.4:
+alpha = 0, 0.1, ..., 1; sparsity 0, 20 %, 40 %): at every point the library's quantised bytes and its blob are
+the oracle's, and the compression ratio rises with alpha (more weight mass moves to the codes near zero).
+That rise is an observation of the paper's, not a theorem: between alpha = 0 and 0.2, where the rescale
+hardly changes the histogram, neighbouring points of a tensor this small may differ by a fraction of a
+percent either way, so the assertion there is "does not fall by more than 1 %"; from 0.2 on the ratio
+must grow strictly.  bench.py --alpha-sweep prints the same table for the config-1 tensor."""
+import numpy as np
+import pytest
+
+import bench
+import oracle.codec as oc
+import oracle.quant as oq
+import paper_2502_15443_amd as dc
+import synth
+
+ROWS, COLS, C, S = 1024, 2048, 16384, 64
+ALPHAS = [i / 10 for i in range(11)]
+
+
+@pytest.mark.parametrize("sparsity", [0.0, 0.2, 0.4])
+def test_ratio_rises_with_alpha_and_library_bytes_are_the_oracles(sparsity):
+    seed = synth.matrix_seed(0, 0)
+    w = synth.gen_weight(ROWS, COLS, seed)
+    a = synth.gen_act_absmax(COLS, seed)
+    ratios = []
+    for alpha in ALPHAS:
+        q, scale, s = dc.quantize_tensor(w, a, alpha, sparsity)
+        s_ref = oq.channel_scale(a, alpha)
+        q_ref, scale_ref = oq.quantise_tensor(oq.rescale(w, s_ref))
+        q_ref = oq.prune_by_score(q_ref, a, sparsity)
+        assert np.array_equal(s, s_ref) and np.float32(scale) == scale_ref and np.array_equal(q, q_ref), alpha
+        assert np.count_nonzero(q == 0) >= int(sparsity * q.size)
+        blob, table = dc.compress_chunks(q, dc.Params(C, S, dc.POLICY_AUTO))
+        c = oc.compress(q_ref, C, S, oc.AUTO, threads=8)
+        assert np.array_equal(blob, c.blob) and np.array_equal(table, c.table), alpha
+        ratios.append(q.size / (blob.size + table.nbytes))
+    assert all(b >= 0.99 * a_ for a_, b in zip(ratios, ratios[1:])), ratios
+    assert all(b > a_ for a_, b in zip(ratios[2:], ratios[3:])), ratios
+    assert ratios[-1] > 2 * ratios[0]  # steep at large alpha, as in the paper's figure of the ratio against alpha
+
+
+def test_bench_table_is_the_same_computation():
+    """bench.py's table (what --alpha-sweep prints) on this tensor gives the ratios the loop above gives."""
+    got = bench.alpha_sweep_table(dc, synth, ROWS, COLS, [0.0, 0.5, 1.0], [0.2], chunk_bytes=C, n_streams=S)
+    seed = synth.matrix_seed(0, 0)
+    w, a = synth.gen_weight(ROWS, COLS, seed), synth.gen_act_absmax(COLS, seed)
+    want = []
+    for alpha in (0.0, 0.5, 1.0):
+        q = oq.prune_by_score(oq.quantise_tensor(oq.rescale(w, oq.channel_scale(a, alpha)))[0], a, 0.2)
+        want.append(oc.compress(q, C, S, oc.AUTO, threads=8).ratio)
+    assert got[0][0] == 0.2 and np.allclose(got[0][1], want, rtol=0, atol=1e-12)

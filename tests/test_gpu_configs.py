@@ -106,19 +106,20 @@ def test_config2_llama7b_layer_tans_coded(C, S):
 
 @pytest.mark.parametrize("C,S", [(16384, 64), (65536, 64), (262144, 64), (16384, 256), (262144, 256)])
 def test_config3_layers_into_one_buffer_chunk_sweep(C, S):
-    """Two layers of the 32-layer weight set (per-layer seeds, no rescale) decoded into one buffer by
-    one launch, for the chunk sizes of the sweep."""
+    """Four layers of the 32-layer weight set (the first two and the last two; per-layer seeds, no rescale)
+    decoded into one buffer by one launch, for the chunk sizes of the sweep.  (bench.py decodes all 32 in its
+    timed launch and compares every byte with the quantised input.)"""
     print(f"case config 3 C={C} S={S}", flush=True)
     qs = []
-    for layer in (0, 31):
+    for layer in (0, 1, 30, 31):
         qs += [q for _, q, _ in oracle_layer("llama7b", layer, False)]
     p = dc.Params(C, S)
     blob, table = compress_concat(qs, p)
     flat = np.concatenate([q.reshape(-1) for q in qs]).view(np.uint8)
-    assert len(table) == 2 * 202375168 // C
+    assert len(table) == 4 * 202375168 // C
     out = gpu_decode(blob, table, p, flat.size)
     assert np.array_equal(out, flat)
-    check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, len(table) // 2, len(table) - 1])
+    check_sampled_chunks_with_oracle(blob, table, C, S, flat, [0, len(table) // 4, len(table) // 2, len(table) - 1])
 
 
 @pytest.mark.parametrize("f", [0.0, 0.25, 0.5, 0.75, 1.0])
@@ -144,7 +145,8 @@ def test_config4_raw_fraction_on_config1_matrix(f):
 @pytest.mark.parametrize("index", [0, 4, 6])
 def test_config5_llama13b_fused_paths(index):
     """q_proj (5120x5120), gate_proj (13824x5120) and down_proj (5120x13824) of the 13B-shaped layer:
-    fused GEMV against the fp64 reference, fused bf16 dequantisation bit for bit on sampled rows."""
+    fused GEMV against the fp64 reference on every row, fused bf16 dequantisation bit for bit on every element
+    (the oracle's result is uploaded and compared on the device)."""
     print(f"case config 5 matrix {index}", flush=True)
     m = synth.layer_specs("llama13b")[index]
     seed = synth.matrix_seed(0, m.index)
@@ -169,9 +171,8 @@ def test_config5_llama13b_fused_paths(index):
     assert (np.abs(y - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
     yb = oq.bf16_to_f64(y16.cpu().numpy().view(np.uint16))
     assert (np.abs(yb - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all()
-    got = out16.cpu().numpy().view(np.uint16).reshape(m.rows, m.cols)
-    rows = np.unique(np.concatenate([np.arange(0, m.rows, 97), [m.rows - 1]]))
-    assert np.array_equal(got[rows], oq.dequant_bf16(q[rows], scale[rows]))
+    want = torch.from_numpy(oq.dequant_bf16(q, scale).view(np.int16).reshape(-1)).cuda()
+    assert torch.equal(out16, want)
 
 
 def test_config5_whole_layer_in_one_fused_call():
@@ -208,9 +209,8 @@ def test_config5_whole_layer_in_one_fused_call():
         assert (np.abs(y - y_ref) <= 1e-2 * np.abs(y_ref) + 1e-2 * rms).all(), m.name
         assert np.abs(y - y_ref).max() / np.abs(y_ref).max() < 1e-4
         assert np.array_equal(y16.cpu().numpy().view(np.uint16), oq.bf16_round(y32.cpu().numpy()))
-        got = o16.cpu().numpy().view(np.uint16).reshape(m.rows, m.cols)
-        rows = np.unique(np.concatenate([np.arange(0, m.rows, 211), [m.rows - 1]]))
-        assert np.array_equal(got[rows], oq.dequant_bf16(q[rows], scale[rows])), m.name
+        want = torch.from_numpy(oq.dequant_bf16(q, scale).view(np.int16).reshape(-1)).cuda()
+        assert torch.equal(o16, want), m.name
     # descriptor errors are caught on the host
     bad = [dc.Matrix(mm.first_chunk + 1, mm.rows, mm.cols, mm.row_scale_dev, x_bf16_dev=mm.x_bf16_dev,
                      y_accum_dev=mm.y_accum_dev) for mm in mats_g]
