@@ -750,6 +750,8 @@ def main() -> int:
     ap.add_argument("--codec", choices=("huffman", "tans"), default="huffman",
                     help="coder of the timed launches (the headline is Huffman)")
     ap.add_argument("--tile", type=int, default=1, help="config2: decode this many copies of the layer in one launch")
+    ap.add_argument("--first-chunks", type=int, default=0, metavar="K",
+                    help="config2: decode only the first K chunks of the (tiled) layer in the timed launch")
     ap.add_argument("--fused", choices=("none", "dequant", "gemv"), default="none",
                     help="time only the whole-layer fused call of config 5 (for a profiler) and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
@@ -838,6 +840,10 @@ def run_config2_headline(torch, dc, synth, args, counters):
             t["off"] += i * blob.size
             tables.append(t)
         blob, table, q = np.tile(blob, args.tile), np.concatenate(tables), np.tile(q, args.tile)
+    if args.first_chunks:
+        # only the first K chunks of the (tiled) layer: the launch-shape measurements (how long K workgroups take)
+        k = min(args.first_chunks, len(table))
+        table, q = table[:k], q[:k * C]
     raw_bytes, n_chunks = q.size, len(table)
     ratio = raw_bytes / (blob.size + table.nbytes)
     nbuf = max(2, int(np.ceil(640e6 / (raw_bytes + blob.size))))
@@ -856,7 +862,7 @@ def run_config2_headline(torch, dc, synth, args, counters):
     algo_bytes = raw_bytes + blob.size + table.nbytes
     achieved = algo_bytes / ms / 1e6
     kernel = f"dc_decode_kernel<{S},int8" + (",tANS>" if args.codec == "tans" else ">")
-    tag = f"{kernel}|config2_layer_x{args.tile}_{C // 1024}KiB"
+    tag = f"{kernel}|config2_layer_x{args.tile}_{C // 1024}KiB" + (f"_first{n_chunks}" if args.first_chunks else "")
     head = {
         "value": round(raw_bytes / ms / 1e6, 2), "ms_per_step": round(ms, 5),
         "config": {"workload": "config 2" + (f" x {args.tile} in one launch" if args.tile > 1 else "") +
@@ -871,7 +877,7 @@ def run_config2_headline(torch, dc, synth, args, counters):
         "launch_index_against_duration": {"cold_launches_0_to_20_ms": [round(t, 4) for t in cold],
                                           "cold_mean_ms": round(float(np.mean(cold)), 4), "steady_ms": round(ms, 5)},
     }
-    n_sample = min(n_chunks, 1024, layer["slices"][0]["n_chunks"] if args.tile == 1 else n_chunks)
+    n_sample = min(n_chunks, 1024, layer["slices"][0]["n_chunks"])
     end = int(table["off"][n_sample - 1]) + int(table["comp_bytes"][n_sample - 1])
     sample = dict(blob=np.concatenate([blob[:end], blob[-64:]]), table=table[:n_sample], q=q[:n_sample * C].view(np.uint8),
                   C=C, S=S, codec=codec)
