@@ -83,5 +83,9 @@ def test_the_bench_imports_the_oracle_only_in_its_cpu_baseline_leg():
              or (isinstance(n, ast.ImportFrom) and (n.module or "").startswith("oracle"))]
     assert len(lines) == 1
     fn = [n for n in ast.walk(tree) if isinstance(n, ast.FunctionDef) and n.lineno <= lines[0] <= n.end_lineno]
-    guard = src.splitlines()[max(0, lines[0] - 12):lines[0]]
-    assert fn and any("no_cpu" in ln for ln in guard), "the oracle import must sit inside the cpu_baseline leg"
+    assert [f.name for f in fn] == ["cpu_baseline"], "the oracle import must sit inside the cpu_baseline leg"
+    # and that leg is entered from one place, which --no-cpu switches off
+    calls = [n for n in ast.walk(tree) if isinstance(n, ast.Call) and getattr(n.func, "id", "") == "cpu_baseline"]
+    assert len(calls) == 1
+    guard = src.splitlines()[max(0, calls[0].lineno - 3):calls[0].lineno]
+    assert any("no_cpu" in ln for ln in guard)
