@@ -208,7 +208,10 @@ struct TansModel {
     uint16_t number_of[kTansL];
 };
 
-// Frequencies normalised to 2048 by the rule of the format.
+// Frequencies normalised to 2048 by the rule of the format.  The rule settles the difference one state at a
+// time, each time at the value with the extreme ratio count/q (or count/(q-1)); only that value's ratio changes,
+// so the values sit in a heap ordered by the exact ratio (cross products, the lower value first among equals)
+// and one state costs one re-insertion.
 void tans_normalise(const uint32_t cnt[256], uint32_t n, uint16_t q[256])
 {
     uint32_t sum = 0;
@@ -217,17 +220,31 @@ void tans_normalise(const uint32_t cnt[256], uint32_t n, uint16_t q[256])
         q[v] = cnt[v] == 0 ? 0 : (uint16_t)std::max<uint64_t>(f, 1);
         sum += q[v];
     }
-    for (; sum < kTansL; sum++) {
-        int best = -1;
-        for (int v = 0; v < 256; v++)
-            if (cnt[v] && (best < 0 || (uint64_t)cnt[v] * q[best] > (uint64_t)cnt[best] * q[v])) best = v;
-        q[best]++;
-    }
-    for (; sum > kTansL; sum--) {
-        int best = -1;
-        for (int v = 0; v < 256; v++)
-            if (q[v] > 1 && (best < 0 || (uint64_t)cnt[v] * (q[best] - 1u) < (uint64_t)cnt[best] * (q[v] - 1u))) best = v;
-        q[best]--;
+    if (sum == kTansL) return;
+    const bool grow = sum < kTansL;
+    // "a comes after b" in the order in which values are served
+    auto later = [&](int a, int b) {
+        const uint64_t da = grow ? q[a] : q[a] - 1u, db = grow ? q[b] : q[b] - 1u;
+        const uint64_t lhs = (uint64_t)cnt[a] * db, rhs = (uint64_t)cnt[b] * da; // cnt[a]/da against cnt[b]/db
+        if (lhs != rhs) return grow ? lhs < rhs : lhs > rhs;
+        return a > b;
+    };
+    std::vector<int> heap;
+    for (int v = 0; v < 256; v++)
+        if (grow ? cnt[v] != 0 : q[v] > 1) heap.push_back(v);
+    std::make_heap(heap.begin(), heap.end(), later);
+    while (sum != kTansL) {
+        std::pop_heap(heap.begin(), heap.end(), later);
+        const int v = heap.back();
+        if (grow) {
+            q[v]++;
+            sum++;
+        } else {
+            q[v]--;
+            sum--;
+        }
+        if (grow || q[v] > 1) std::push_heap(heap.begin(), heap.end(), later);
+        else heap.pop_back();
     }
 }
 
@@ -402,27 +419,46 @@ void write_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook 
         if (fill > 0) *w++ = (uint32_t)acc;
     }
 
+    // Placement.  The rule of the format is a walk through the steps; here it is turned round.  Call the
+    // carrying-outs of the rule "times": T = 0..3 come before anything of a stream is read, T = 4 + h is step h
+    // (T = 4 is the fifth time of step 0).  A stream's position c(T) does not fall with T, and a stream takes at
+    // most one block a time, so block b of a stream is taken at the first time T_b > T_(b-1) with
+    // 128 b < c(T_b) + look-ahead: one pass over the stream's positions gives the times of all its blocks.  The
+    // region is then the blocks b >= 1 of the set's streams sorted by (time, stream), a counting sort.
     uint32_t pos = header_bytes(S, codec);
-    std::vector<uint32_t> f(W);
+    const uint32_t times = steps + 4;
+    std::vector<uint32_t> at_time(times + 1);
+    std::vector<uint32_t> when; // time of every block b >= 1 of the set's streams, stream after stream
+    std::vector<uint32_t> begin(W + 1);
     for (uint32_t s0 = 0, w = 0; s0 < S; s0 += W, w++) {
         std::memcpy(out + front + 2 * S + 4 * w, &pos, 4);
-        std::fill(f.begin(), f.end(), 0);
-        for (uint32_t h = 0; h < steps; h++) {
-            for (int t = 0; t < (h == 0 ? 5 : 1); t++) {
-                for (uint32_t i = 0; i < W; i++) {
-                    const uint32_t j = s0 + i;
-                    // the first four times of step 0 come before anything of the stream is read
-                    const uint64_t c = (h == 0 && t < 4) ? start[j] : used[(size_t)j * (steps + 1) + h];
-                    if (f[i] < nb[j] && (uint64_t)kBlockBits * f[i] < c + DC_LOOKAHEAD_BITS) {
-                        if (f[i] > 0) { // block 0 goes to the heads
-                            std::memcpy(out + pos, coded.data() + ((size_t)first_block[j] + f[i]) * kBlock, kBlock);
-                            pos += kBlock;
-                        }
-                        f[i]++;
-                    }
-                }
+        when.clear();
+        std::fill(at_time.begin(), at_time.end(), 0);
+        for (uint32_t i = 0; i < W; i++) {
+            const uint32_t j = s0 + i;
+            begin[i] = (uint32_t)when.size();
+            const uint32_t *u = &used[(size_t)j * (steps + 1)];
+            uint32_t T = 0; // block 0, the head, is taken at time 0 (0 < c + look-ahead always holds)
+            for (uint32_t b = 1; b < nb[j]; b++) {
+                T++;
+                while (T < times && (uint64_t)kBlockBits * b >= (uint64_t)(T < 4 ? start[j] : u[T - 4]) + DC_LOOKAHEAD_BITS) T++;
+                // (every block is placed by the last step: the format's look-ahead guarantees it)
+                if (T >= times) T = times - 1;
+                when.push_back(T);
+                at_time[T + 1]++;
             }
         }
+        begin[W] = (uint32_t)when.size();
+        for (uint32_t T = 0; T < times; T++) at_time[T + 1] += at_time[T]; // first region slot of every time
+        for (uint32_t i = 0; i < W; i++) {
+            const uint32_t j = s0 + i;
+            for (uint32_t n = begin[i]; n < begin[i + 1]; n++) {
+                const uint32_t b = n - begin[i] + 1;
+                const uint32_t slot = at_time[when[n]]++; // streams are visited in ascending order: stable
+                std::memcpy(out + pos + (size_t)slot * kBlock, coded.data() + ((size_t)first_block[j] + b) * kBlock, kBlock);
+            }
+        }
+        pos += (uint32_t)when.size() * kBlock;
         for (uint32_t j = s0; j < s0 + W; j++) {
             if (nb[j] == 0) continue;
             const uint32_t n = head_bytes_of(bits[j]);
