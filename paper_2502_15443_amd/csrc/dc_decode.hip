@@ -631,7 +631,31 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
     constexpr bool UNI = CPW == 1; // all lanes of the wave belong to one stream set
 
     // ---- raw chunks: the threads of the chunk copy it, eight 16-byte loads in flight per thread
-    if (MODE == kModeI8 && active && is_raw) {
+    if (MODE == kModeI8 && CPW == 2) {
+        // S = 32: the wavefront's two chunks one after the other, each copied by all 64 lanes with sixteen loads in
+        // flight per lane (a wavefront alone on its SIMD has nothing but its own loads to hide a trip to memory behind)
+        for (uint32_t h = 0; h < 2; h++) {
+            const int from = 32 * (int)h;
+            if (!__shfl((int)(active && is_raw), from)) continue;
+            const uint64_t off_h = (uint64_t)(uint32_t)__shfl((int)(uint32_t)ent.off, from) |
+                                   (uint64_t)(uint32_t)__shfl((int)(uint32_t)(ent.off >> 32), from) << 32;
+            const uint32_t raw_h = (uint32_t)__shfl((int)raw, from);
+            const uint8_t *p8 = a.blob + off_h;
+            uint8_t *d8 = static_cast<uint8_t *>(a.dst) + ((uint64_t)blockIdx.x * CPW + h) * (uint64_t)a.chunk_bytes;
+            const uint32_t n16 = raw_h / 16;
+            for (uint32_t base = lane; base < n16; base += 16 * 64) {
+                u32x4 v[16];
+#pragma unroll
+                for (int j = 0; j < 16; j++)
+                    if (base + j * 64 < n16) v[j] = load16_stream(p8 + 16 * (size_t)(base + j * 64));
+#pragma unroll
+                for (int j = 0; j < 16; j++)
+                    if (base + j * 64 < n16)
+                        __builtin_nontemporal_store(v[j], reinterpret_cast<u32x4 *>(d8 + 16 * (size_t)(base + j * 64)));
+            }
+            for (uint32_t i = n16 * 16 + lane; i < raw_h; i += 64) d8[i] = p8[i];
+        }
+    } else if (MODE == kModeI8 && active && is_raw) {
         uint8_t *d8 = static_cast<uint8_t *>(a.dst) + dst_pos;
         const uint32_t n16 = raw / 16;
         for (uint32_t base = ct; base < n16; base += 8 * TPC) {
