@@ -51,3 +51,20 @@ def test_bench_table_is_the_same_computation():
         q = oq.prune_by_score(oq.quantise_tensor(oq.rescale(w, oq.channel_scale(a, alpha)))[0], a, 0.2)
         want.append(oc.compress(q, C, S, oc.AUTO, threads=8).ratio)
     assert got[0][0] == 0.2 and np.allclose(got[0][1], want, rtol=0, atol=1e-12)
+
+
+def test_pair_statistics_of_the_bench(capsys):
+    """bench.py --pair-stats (host only): what a decode table with two symbols per entry would deliver.  A lane
+    needs at most 8 look-ups per half group of 8 symbols and at least 4; a wavefront that moves in step needs as
+    many as its slowest lane, so never fewer than a lane on average; on the data of configs 1 and 3 (7 bits a
+    symbol) hardly any pair of codes fits the 11-bit window."""
+    import json
+
+    assert bench.pair_stats(dc, synth) == 0
+    rows = json.loads(capsys.readouterr().out)["two_symbol_table_entries"]
+    assert len(rows) == 2
+    for r in rows:
+        assert 4 <= r["lookups_per_half_group_a_lane_alone"] <= r["lookups_per_half_group_a_wavefront_in_step"] <= 8
+        assert 0 <= r["adjacent_pairs_that_fit_11_bits"] <= 1
+    assert rows[0]["adjacent_pairs_that_fit_11_bits"] < 0.05 and rows[0]["mean_code_bits"] > 6.5
+    assert rows[1]["mean_code_bits"] < rows[0]["mean_code_bits"]
