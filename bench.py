@@ -754,6 +754,8 @@ def main() -> int:
                     help="config2: decode only the first K chunks of the (tiled) layer in the timed launch")
     ap.add_argument("--fused", choices=("none", "dequant", "gemv"), default="none",
                     help="time only the whole-layer fused call of config 5 (for a profiler) and exit")
+    ap.add_argument("--streaming-only", action="store_true",
+                    help="only the layer-streaming loop on the config-2 layer (for a kernel trace) and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-side", action="store_true", help="skip the side timings of the headline launch")
@@ -783,6 +785,10 @@ def main() -> int:
 
     if args.fused != "none":
         return fused_only(torch, dc, synth, args)
+    if args.streaming_only:
+        p2 = dc.Params(65536, 256)
+        print(json.dumps(layer_streaming(torch, dc, synth, p2, build_layer("llama7b", 0, True, p2, dc, synth))))
+        return 0
 
     out = {"metric": "decoded weight GB/s on 1 MI355X (and % HBM roofline); compression ratio", "value": None,
            "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,

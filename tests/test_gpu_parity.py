@@ -342,7 +342,7 @@ def test_gemv_within_tolerance(S, rows, cols, C, f):
     y_ref = oq.gemv_ref(q, scale, x)
     blob_d, table_d, scale_d = dev(c.blob), dev(c.table), torch.from_numpy(scale).cuda()
     x_d = torch.from_numpy(x.view(np.int16)).cuda()
-    y32 = torch.full((rows,), 7.0, dtype=torch.float32, device="cuda")  # the call must zero it itself
+    y32 = torch.full((rows,), 7.0, dtype=torch.float32, device="cuda")  # what it holds before the call must not matter
     y16 = torch.zeros(rows, dtype=torch.int16, device="cuda")
     dc.decompress_gemv(blob_d, c.blob.size, table_d, c.n_chunks, dc.Params(C, S), scale_d, rows, cols, x_d, y32, y16,
                        *gemv_workspace(c.n_chunks), stream())
