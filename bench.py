@@ -737,6 +737,65 @@ def pair_stats(dc, synth):
     return 0
 
 
+def mix_sweep(torch, dc, synth):
+    """Raw and coded chunks in one launch (Section 3.3's speed-adaptive storage), on the config-2 layer and on a
+    four-layer weight set: the share f of raw chunks by gain and the positional rule with blocks of N, and, on the
+    layer at f = 0.5, the same chunks with the table (and the expected bytes) put into other orders: runs of c coded
+    then r raw chunks.  One JSON line."""
+    p0 = dc.Params(65536, 256)
+    layer_q = build_layer("llama7b", 0, True, p0, dc, synth)["q"]
+    model_q = model_weights(4, dc, synth)
+    out = {"n_streams": 256, "chunk_bytes": 65536}
+
+    def rate(q, p, table_order=None, **kw):
+        blob, table = dc.compress_chunks(q, p)
+        if table_order is not None:  # chunk k of the launch is chunk table_order[k] of the blob
+            order = table_order(table)
+            table = table[order]
+            q = q.reshape(len(order), -1)[order].reshape(-1)
+        r = decode_row(torch, dc, blob, table, p, q, **kw)
+        return {"decoded_GBps": r["decoded_GBps"], "compression_ratio": r["compression_ratio"], "exact": r["exact"],
+                "raw_chunks": int(((table["raw_bytes_flags"] >> 31) & 1).sum()), "n_chunks": len(table)}
+
+    for name, q, kw in (("config2_layer", layer_q, dict(steps=300, warmup=30)), ("four_layers", model_q, dict(steps=40, warmup=5))):
+        rows = []
+        for f in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0):
+            rows.append(dict(raw_fraction=f, **rate(q, dc.Params(65536, 256, dc.POLICY_RAW_FRACTION, f), **kw)))
+        out[name + "_by_gain"] = rows
+    rows = []
+    for n in (2, 3, 4, 5, 6, 7, 8, 9, 16):
+        rows.append(dict(block_chunks=n, **rate(layer_q, dc.Params(65536, 256, dc.POLICY_BLOCK_LAST, 0.0, n), steps=300, warmup=30)))
+    out["config2_layer_positional"] = rows
+
+    def runs(c, r, raw_first=False):
+        def order(table):
+            is_raw = ((table["raw_bytes_flags"] >> 31) & 1).astype(bool)
+            raw, coded, o = list(np.nonzero(is_raw)[0]), list(np.nonzero(~is_raw)[0]), []
+            while raw or coded:
+                for src, cnt in (((raw, r), (coded, c)) if raw_first else ((coded, c), (raw, r))):
+                    o += src[:cnt]
+                    del src[:cnt]
+            return np.array(o)
+        return order
+
+    rows = []
+    half = dc.Params(65536, 256, dc.POLICY_RAW_FRACTION, 0.5)
+    for label, order in (("as stored", None), ("1 coded, 1 raw", runs(1, 1)), ("1 raw, 1 coded", runs(1, 1, True)),
+                         ("8, 8", runs(8, 8)), ("32, 32", runs(32, 32)), ("256, 256", runs(256, 256)),
+                         ("all coded, then all raw", runs(1 << 30, 1 << 30)), ("all raw, then all coded", runs(1 << 30, 1 << 30, True))):
+        rows.append(dict(order=label, **rate(layer_q, half, order, steps=300, warmup=30)))
+    out["config2_layer_half_raw_by_order"] = rows
+    # the same share chosen by place and not by gain, the decoded bytes in their own order: the back half of the layer raw
+    n = (layer_q.size + 65535) // 65536
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[n - n // 2:] = 1
+    out["config2_layer_back_half_raw"] = [dict(rule="DC_POLICY_RAW_MASK, the last half of the chunks",
+                                               **rate(layer_q, dc.Params(65536, 256, dc.POLICY_RAW_MASK, 0.0, 0, mask), steps=300, warmup=30))]
+    ok = all(r["exact"] for k in out if isinstance(out[k], list) for r in out[k])
+    print(json.dumps({"mix_sweep": out, "exact": ok}))
+    return 0 if ok else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -756,6 +815,8 @@ def main() -> int:
                     help="time only the whole-layer fused call of config 5 (for a profiler) and exit")
     ap.add_argument("--streaming-only", action="store_true",
                     help="only the layer-streaming loop on the config-2 layer (for a kernel trace) and exit")
+    ap.add_argument("--mix-sweep", action="store_true",
+                    help="only launches that mix raw and coded chunks: by share, by rule and by order, and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-side", action="store_true", help="skip the side timings of the headline launch")
@@ -785,6 +846,8 @@ def main() -> int:
 
     if args.fused != "none":
         return fused_only(torch, dc, synth, args)
+    if args.mix_sweep:
+        return mix_sweep(torch, dc, synth)
     if args.streaming_only:
         p2 = dc.Params(65536, 256)
         print(json.dumps(layer_streaming(torch, dc, synth, p2, build_layer("llama7b", 0, True, p2, dc, synth))))
