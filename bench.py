@@ -796,6 +796,70 @@ def mix_sweep(torch, dc, synth):
     return 0 if ok else 1
 
 
+def workgroup_timeline(torch, dc, synth):
+    """One traced launch (dc_decompress_chunks_traced) of the config-2 layer per storage rule, after 60 launches without
+    the record: when the workgroups of coded and of raw chunks began, how long they took, how many were resident at
+    once and how the coded ones were spread over the compute units.  Times in microseconds from the launch's first
+    workgroup.  One JSON line."""
+    p0 = dc.Params(65536, 256)
+    q = build_layer("llama7b", 0, True, p0, dc, synth)["q"]
+    n = (q.size + 65535) // 65536
+    back_half = np.zeros(n, dtype=np.uint8)
+    back_half[n - n // 2:] = 1
+    cases = (("all coded", p0),
+             ("half raw, lowest gain", dc.Params(65536, 256, dc.POLICY_RAW_FRACTION, 0.5)),
+             ("half raw, the back half", dc.Params(65536, 256, dc.POLICY_RAW_MASK, 0.0, 0, back_half)),
+             ("blocks of 2, last coded", dc.Params(65536, 256, dc.POLICY_BLOCK_LAST, 0.0, 2)),
+             ("blocks of 3, last coded", dc.Params(65536, 256, dc.POLICY_BLOCK_LAST, 0.0, 3)),
+             ("all raw", dc.Params(65536, 256, dc.POLICY_RAW_FRACTION, 1.0)))
+    stream = torch.cuda.current_stream().cuda_stream
+    want = up(torch, q)
+    rows, ok = [], True
+
+    def pct(x, *ps):
+        return [round(float(np.percentile(x, p_)), 1) for p_ in ps]
+
+    for label, p in cases:
+        blob, table = dc.compress_chunks(q, p)
+        blob_d, table_d = up(torch, blob), up(torch, table)
+        dst = torch.zeros(q.size, dtype=torch.uint8, device="cuda")
+        trace = torch.zeros(4 * n, dtype=torch.int64, device="cuda")
+        for _ in range(60):
+            dc.decompress_chunks(blob_d, blob.size, table_d, n, p, dst, q.size, stream)
+        dst.zero_()
+        for _ in range(3):
+            dc.decompress_chunks_traced(blob_d, blob.size, table_d, n, p, dst, q.size, trace, stream)
+        torch.cuda.synchronize()
+        exact = bool(torch.equal(dst, want))
+        ok = ok and exact
+        t = trace.cpu().numpy().reshape(n, 4)
+        t0 = t[:, 0].min()
+        began, ended = (t[:, 0] - t0) / 100.0, (t[:, 1] - t0) / 100.0
+        hw, xcd = t[:, 2] & 0xFFFFFFFF, (t[:, 2] >> 32) & 0xF
+        unit = xcd * 256 + ((hw >> 13) & 7) * 16 + ((hw >> 8) & 0xF)  # compute unit: XCD, shader engine, unit
+        row = {"stored": label, "exact": exact, "span_us": round(float(ended.max()), 1),
+               "resident_at_once": int((began < 2.0).sum()), "compute_units_seen": int(len(np.unique(unit))),
+               "xcd_is_workgroup_mod_8": bool(np.all(xcd == np.arange(n) % 8))}
+        for name, kind in (("coded", dc.TRACE_DECODED), ("raw", dc.TRACE_COPIED)):
+            m = t[:, 3] == kind
+            if not m.any():
+                continue
+            dur = ended[m] - began[m]
+            d = {"workgroups": int(m.sum()), "began_p50_p90_max": pct(began[m], 50, 90, 100),
+                 "took_p10_p50_p90": pct(dur, 10, 50, 90), "last_ended": round(float(ended[m].max()), 1)}
+            late = m & (began >= 2.0)
+            if late.any():
+                d["took_p50_when_begun_later"] = pct(ended[late] - began[late], 50)[0]
+            if kind == dc.TRACE_DECODED:
+                per_unit = np.bincount(unit[m], minlength=int(unit.max()) + 1)[np.unique(unit)]
+                d["per_compute_unit_min_mean_max"] = [int(per_unit.min()), round(float(per_unit.mean()), 1), int(per_unit.max())]
+            row[name] = d
+        rows.append(row)
+    print(json.dumps({"workgroup_timeline": {"workload": "config-2 layer, 3088 chunks of 64 KiB, 256 sub-streams; launch 63 of its run",
+                                             "clock": "wall_clock64, 100 MHz", "launches": rows}, "exact": ok}))
+    return 0 if ok else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -817,6 +881,8 @@ def main() -> int:
                     help="only the layer-streaming loop on the config-2 layer (for a kernel trace) and exit")
     ap.add_argument("--mix-sweep", action="store_true",
                     help="only launches that mix raw and coded chunks: by share, by rule and by order, and exit")
+    ap.add_argument("--wg-trace", action="store_true",
+                    help="only one traced launch of the config-2 layer per storage rule: when its workgroups ran and where, and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-side", action="store_true", help="skip the side timings of the headline launch")
@@ -848,6 +914,8 @@ def main() -> int:
         return fused_only(torch, dc, synth, args)
     if args.mix_sweep:
         return mix_sweep(torch, dc, synth)
+    if args.wg_trace:
+        return workgroup_timeline(torch, dc, synth)
     if args.streaming_only:
         p2 = dc.Params(65536, 256)
         print(json.dumps(layer_streaming(torch, dc, synth, p2, build_layer("llama7b", 0, True, p2, dc, synth))))

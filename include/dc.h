@@ -367,6 +367,25 @@ int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_
                          void *hip_stream);
 
 /*
+ * dc_decompress_chunks with a record of every workgroup of the launch, for whoever wants to see how a launch
+ * is laid out in time and over the chip (the tail of a short launch, launches that mix raw and coded chunks); not
+ * part of the method.  Same arguments, results and errors as dc_decompress_chunks, Huffman coded blobs of 256
+ * sub-streams only (DC_E_ARG otherwise), and
+ *   trace_dev   4 * n_chunks 64-bit words of device memory, 8-byte aligned, owned by the caller.  Workgroup b
+ *               (= chunk b) writes words 4b .. 4b+3 when it ends: [0] and [1] the readings of the constant 100 MHz
+ *               clock (wall_clock64) when it began and when it ended; [2] the wavefront's HW_ID register in the
+ *               low 32 bits (compute unit in bits 8-11, shader engine from bit 13) and its XCC_ID register in
+ *               the high 32 (the XCD in bits 0-3); [3] one of DC_TRACE_*.
+ * The record costs a launch about 1 % of its speed.
+ */
+#define DC_TRACE_DECODED 0u /* a coded chunk, decoded */
+#define DC_TRACE_COPIED 1u  /* a raw chunk, copied */
+#define DC_TRACE_SKIPPED 2u /* left alone: the table entry or the blob's trailer did not pass the checks */
+int dc_decompress_chunks_traced(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
+                                uint64_t *trace_dev, void *hip_stream);
+
+/*
  * Decompression fused with dequantisation to bf16 (replaces the separate conversion of the
  * decompressed memory into tensors that Section 4.6 counts as overhead; dequantisation inverts Eq. 4):
  *   dst[i*cols + j] = bf16_round_nearest_even( float(q_ij) * row_scale[i] ).

@@ -20,6 +20,7 @@ CODEC_HUFFMAN, CODEC_TANS = 0, 1
 FORMAT_ID = 5  # DC_FORMAT_ID of include/dc.h
 CHUNK_RAW = 0x80000000
 STATIC_SCRATCH_BYTES = 16 << 20
+TRACE_DECODED, TRACE_COPIED, TRACE_SKIPPED = 0, 1, 2
 CHUNK_DTYPE = np.dtype([("off", "<u8"), ("comp_bytes", "<u4"), ("raw_bytes_flags", "<u4")])
 
 
@@ -125,6 +126,8 @@ def _load():
     L.dc_validate.argtypes = [vp, u64, vp, u64, pp, pu64]
     L.dc_decompress_chunks.restype = i32
     L.dc_decompress_chunks.argtypes = [vp, u64, vp, u64, pp, vp, u64, vp]
+    L.dc_decompress_chunks_traced.restype = i32
+    L.dc_decompress_chunks_traced.argtypes = [vp, u64, vp, u64, pp, vp, u64, vp, vp]
     L.dc_decompress_dequant_bf16.restype = i32
     L.dc_decompress_dequant_bf16.argtypes = [vp, u64, vp, u64, pp, vp, u32, u32, vp, u64, vp]
     L.dc_decompress_gemv.restype = i32
@@ -286,6 +289,13 @@ def decompress_chunks(blob_dev, blob_bytes: int, table_dev, n_chunks: int, param
     cp = params._c()
     _check(_L.dc_decompress_chunks(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
                                    _dev(dst_dev), dst_cap, stream), "dc_decompress_chunks")
+
+
+def decompress_chunks_traced(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, dst_dev,
+                             dst_cap: int, trace_dev, stream: int = 0) -> None:
+    cp = params._c()
+    _check(_L.dc_decompress_chunks_traced(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
+                                          _dev(dst_dev), dst_cap, _dev(trace_dev), stream), "dc_decompress_chunks_traced")
 
 
 def decompress_dequant_bf16(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, row_scale_dev,

@@ -68,6 +68,7 @@ struct DecodeArgs {
     uint64_t n_chunks;
     uint32_t chunk_bytes;
     uint32_t trailer[4]; // what the blob's last 16 bytes must be for this launch to decode it
+    uint64_t *trace;     // traced launches: four words per workgroup (see dc_decompress_chunks_traced), else null
     // kModeI8: all chunks decode into one buffer of dst_cap bytes
     void *dst;
     uint64_t dst_cap;
@@ -567,10 +568,23 @@ __device__ __forceinline__ bool build_tans_table(const uint8_t *payload8, uint32
     return true;
 }
 
-template <int S, int MODE, int CODEC>
+template <int S, int MODE, int CODEC, bool TRACE = false>
 __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(DecodeArgs a)
 {
     using G = Geometry<S>;
+    // traced launches: when the workgroup began and ended (ticks of the constant 100 MHz clock), where it ran (the
+    // HW_ID register, the XCC_ID register above it) and what it did with its chunk
+    const uint64_t began = TRACE ? wall_clock64() : 0;
+    auto leave_record = [&](uint32_t did) {
+        if (TRACE && threadIdx.x == 0) {
+            uint64_t *r = a.trace + 4 * (size_t)blockIdx.x;
+            r[0] = began;
+            r[1] = wall_clock64();
+            r[2] = (uint64_t)(uint32_t)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4) |
+                   (uint64_t)(uint32_t)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 20) << 32;
+            r[3] = did;
+        }
+    };
     constexpr int LPC = G::kLanesPerChunk;
     constexpr int CPW = G::kChunksPerWave;
     constexpr int WAVES = G::kWaves;
@@ -671,7 +685,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
         for (uint32_t i = n16 * 16 + ct; i < raw; i += TPC) d8[i] = payload8[i];
     }
     if (MODE != kModeI8 && !(active)) return;
-    if (MODE == kModeI8 && !huff) return;
+    if (MODE == kModeI8 && !huff) {
+        leave_record(active ? DC_TRACE_COPIED : DC_TRACE_SKIPPED);
+        return;
+    }
 
     // The table is only needed where a chunk of the workgroup is Huffman coded; the condition is the
     // same for every thread that is still here, so the barriers inside are reached together.
@@ -858,6 +875,7 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
             for (uint32_t i = 8; i < n; i++)
                 d[i] = (uint8_t)(CODEC == DC_CODEC_TANS ? tans_decode1(st, tbl_addr, ring_lane) : decode1(st, tbl_addr, ring_lane));
         }
+        leave_record(DC_TRACE_DECODED);
         return;
     }
 
@@ -1309,6 +1327,29 @@ extern "C" int dc_decompress_chunks(const uint8_t *blob_dev, uint64_t blob_bytes
     a.dst = dst_dev;
     a.dst_cap = dst_cap;
     return launch_decode<kModeI8>(a, params->n_streams, static_cast<hipStream_t>(hip_stream), params->codec);
+}
+
+extern "C" int dc_decompress_chunks_traced(const uint8_t *blob_dev, uint64_t blob_bytes, const dc_chunk *table_dev,
+                                           uint64_t n_chunks, const dc_params *params, int8_t *dst_dev, uint64_t dst_cap,
+                                           uint64_t *trace_dev, void *hip_stream)
+{
+    if (!decode_params_ok(params) || !blob_dev || !table_dev || !dst_dev || !trace_dev || n_chunks == 0 ||
+        n_chunks > 0x7FFFFFFFull || blob_bytes < DC_BLOB_TAIL_BYTES || blob_bytes % 16)
+        return DC_E_ARG;
+    if (params->format != DC_FORMAT_ID) return DC_E_FORMAT;
+    if (params->codec != DC_CODEC_HUFFMAN || params->n_streams != 256) return DC_E_ARG;
+    if (!aligned16(blob_dev) || !aligned16(dst_dev) || (reinterpret_cast<uintptr_t>(table_dev) & 7u) ||
+        (reinterpret_cast<uintptr_t>(trace_dev) & 7u))
+        return DC_E_ARG;
+    if (dst_cap < (n_chunks - 1) * (uint64_t)params->chunk_bytes + 1) return DC_E_CAP;
+    DecodeArgs a = {};
+    common_args(a, blob_dev, blob_bytes, table_dev, n_chunks, params);
+    a.dst = dst_dev;
+    a.dst_cap = dst_cap;
+    a.trace = trace_dev;
+    hipLaunchKernelGGL((dc_decode_kernel<256, kModeI8, DC_CODEC_HUFFMAN, true>), dim3((uint32_t)n_chunks), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), a);
+    return launch_status();
 }
 
 namespace {
