@@ -796,6 +796,35 @@ def mix_sweep(torch, dc, synth):
     return 0 if ok else 1
 
 
+def compress_only(torch, dc, synth, args):
+    """dc_compress_chunks_dev alone (for a profiler): the config-2 layer and a four-layer weight set, both coders,
+    --steps calls each after 3 untimed ones.  One JSON line."""
+    stream = torch.cuda.current_stream().cuda_stream
+    sets = (("config2_layer", build_layer("llama7b", 0, True, dc.Params(65536, 256), dc, synth)["q"]),
+            ("four_layers", model_weights(4, dc, synth)))
+    rows = []
+    for name, q in sets:
+        q_d = up(torch, q)
+        for codec_name, codec in (("huffman", dc.CODEC_HUFFMAN), ("tans", dc.CODEC_TANS)):
+            p = dc.Params(args.chunk, args.streams, codec=codec)
+            cap, nc = dc.compress_bound(q.size, p)
+            blob = torch.empty(cap, dtype=torch.uint8, device="cuda")
+            table = torch.empty(nc * 16, dtype=torch.uint8, device="cuda")
+            ws_n = dc.compress_chunks_dev_workspace(q.size, p)
+            ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
+            res = torch.zeros(2, dtype=torch.int64, device="cuda")
+            ms, _ = time_launches(
+                torch, lambda i: dc.compress_chunks_dev(q_d, q.size, p, blob, cap, table, nc, ws, ws_n, res, stream), args.steps, 3)
+            blob_bytes = int(res.cpu()[0])
+            rows.append({"input": name, "codec": codec_name, "raw_bytes": int(q.size), "ms": round(ms, 4),
+                         "GBps": round(q.size / ms / 1e6, 1), "compression_ratio": round(q.size / (blob_bytes + nc * 16), 5),
+                         "hbm_frac": round((q.size * 2 + blob_bytes) / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                         "bytes_moved": "the input is read twice (statistics, then coding) and the blob written once"})
+            del blob, table, ws
+    print(json.dumps({"compress_on_gpu": rows, "n_streams": args.streams, "chunk_bytes": args.chunk, "steps": args.steps}))
+    return 0
+
+
 def workgroup_timeline(torch, dc, synth):
     """One traced launch (dc_decompress_chunks_traced) of the config-2 layer per storage rule, after 60 launches without
     the record: when the workgroups of coded and of raw chunks began, how long they took, how many were resident at
@@ -881,6 +910,8 @@ def main() -> int:
                     help="only the layer-streaming loop on the config-2 layer (for a kernel trace) and exit")
     ap.add_argument("--mix-sweep", action="store_true",
                     help="only launches that mix raw and coded chunks: by share, by rule and by order, and exit")
+    ap.add_argument("--compress-only", action="store_true",
+                    help="only the compression on the GPU, both coders (for a profiler), and exit")
     ap.add_argument("--wg-trace", action="store_true",
                     help="only one traced launch of the config-2 layer per storage rule: when its workgroups ran and where, and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
@@ -916,6 +947,8 @@ def main() -> int:
         return mix_sweep(torch, dc, synth)
     if args.wg_trace:
         return workgroup_timeline(torch, dc, synth)
+    if args.compress_only:
+        return compress_only(torch, dc, synth, args)
     if args.streaming_only:
         p2 = dc.Params(65536, 256)
         print(json.dumps(layer_streaming(torch, dc, synth, p2, build_layer("llama7b", 0, True, p2, dc, synth))))
