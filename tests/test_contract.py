@@ -89,3 +89,15 @@ def test_the_bench_imports_the_oracle_only_in_its_cpu_baseline_leg():
     assert len(calls) == 1
     guard = src.splitlines()[max(0, calls[0].lineno - 3):calls[0].lineno]
     assert any("no_cpu" in ln for ln in guard)
+
+
+def test_every_bench_flag_the_readme_names_exists():
+    """README.md tells a user which flags time which workload; each of them is one bench.py accepts."""
+    import re
+    readme = open(os.path.join(ROOT, "README.md")).read()
+    named = set(re.findall(r"`(--[a-z][a-z0-9-]*)", readme))
+    assert {"--workload", "--mix-sweep", "--wg-trace", "--alpha-sweep", "--pair-stats"} <= named
+    helptext = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True,
+                              timeout=120).stdout
+    missing = sorted(f for f in named if f not in helptext)
+    assert not missing, missing
