@@ -50,6 +50,24 @@ def load_counters(dc):
     return doc.get("kernels", {})
 
 
+def issue_rates(counters, key, raw_bytes, ms):
+    """What keeps the decode launch below the HBM roofline: vector-ALU instructions (SQ_INSTS_VALU x 64 lanes, from the
+    tracked counter run) over this run's duration against the rate the chip issues them at its nominal clock, and the
+    share of LDS cycles lost to bank conflicts.  None where no counter run of this kernel and workload is tracked."""
+    c = (counters or {}).get(key)
+    if not c or "valu_insts" not in c:
+        return None
+    lane_ops = c["valu_insts"] * 64
+    out = {"bound": "alu", "achieved": round(lane_ops / (ms * 1e-3) / 1e12, 2), "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2),
+           "unit": "T lane-ops/s", "frac": round(lane_ops / (ms * 1e-3) / ALU_PEAK_LANE_OPS, 4),
+           "lane_ops_per_decoded_byte": round(lane_ops / raw_bytes, 2),
+           "peak_is": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; under this load the clock reads 2.0 GHz",
+           "source": f"profiles/counters.json [{key}]"}
+    if "lds_idx_active" in c and "lds_bank_conflict" in c:
+        out["lds_cycles_lost_to_bank_conflicts"] = round(c["lds_bank_conflict"] / c["lds_idx_active"], 3)
+    return out
+
+
 def measured_traffic(counters, key):
     """HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE readings of `key`, scaled by what the same
     counters read for the plain copy kernel; None when profiles/ has no reading for this kernel and workload."""
@@ -222,6 +240,7 @@ def run_config3(torch, dc, synth, args, counters):
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "traffic_source": f"profiles/counters.json [{tag}]" if traffic else None,
                      "kernel": kernel, "algorithmic_bytes_per_launch": int(algo_bytes), "avg_launch_ms": round(ms, 5)},
+        "issue_rates": issue_rates(counters, tag, raw_bytes, ms),
         "wall_ms_per_step": round(wall_ms, 5),
         "roofline_limited_decoded_gbps": round(HBM_PEAK_GBPS / (1 + 1 / ratio), 1),
         "launch_index_against_duration": {
