@@ -181,11 +181,13 @@ def compress_on_device(torch, dc, src_d, raw_bytes, params, stream):
     ws_n = dc.compress_chunks_dev_workspace(raw_bytes, params)
     ws = torch.empty(ws_n, dtype=torch.uint8, device="cuda")
     res = torch.zeros(2, dtype=torch.int64, device="cuda")
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    dc.compress_chunks_dev(src_d, raw_bytes, params, big, cap, table_d, nc, ws, ws_n, res, stream)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3
+    ms = None
+    for _ in range(2):  # the second call is the one timed: the first loads the compression kernels
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dc.compress_chunks_dev(src_d, raw_bytes, params, big, cap, table_d, nc, ws, ws_n, res, stream)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
     used, status = (int(v) for v in res.cpu())
     if status != 0:
         raise RuntimeError("dc_compress_chunks_dev: blob buffer too small")
