@@ -31,9 +31,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# vector ALU: 256 compute units x 4 SIMDs x 16 lanes, one operation per lane and clock at 2.4 GHz
-# (the fp32 peak of 157.3 TFLOP/s is this figure times two for a fused multiply-add)
-ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# Vector-ALU peak in lane-operations per second: 256 compute units x 4 SIMDs x 64 lanes of a wavefront instruction every
+# `cycles` cycles at 2.4 GHz.  A SIMD issues plain 32-bit logic, add, subtract, right shift, move and fp32 add / multiply
+# every 2 cycles and every other instruction the kernels use every 4 (bench.py --issue-rates); a kernel's peak follows
+# from the mix of its main loop (profiles/counters.json, valu_cycles_per_instruction), 4 where no mix is recorded.
+def alu_peak_lane_ops(cycles_per_instruction=4.0):
+    return 256 * 4 * 64 * 2.4e9 / cycles_per_instruction
+
+
 COUNTERS_FILE = os.path.join(ROOT, "profiles", "counters.json")
 
 
@@ -58,10 +63,13 @@ def issue_rates(counters, key, raw_bytes, ms):
     if not c or "valu_insts" not in c:
         return None
     lane_ops = c["valu_insts"] * 64
-    out = {"bound": "alu", "achieved": round(lane_ops / (ms * 1e-3) / 1e12, 2), "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2),
-           "unit": "T lane-ops/s", "frac": round(lane_ops / (ms * 1e-3) / ALU_PEAK_LANE_OPS, 4),
+    cpi = c.get("valu_cycles_per_instruction", 4.0)
+    peak = alu_peak_lane_ops(cpi)
+    out = {"bound": "alu", "achieved": round(lane_ops / (ms * 1e-3) / 1e12, 2), "peak": round(peak / 1e12, 2),
+           "unit": "T lane-ops/s", "frac": round(lane_ops / (ms * 1e-3) / peak, 4),
            "lane_ops_per_decoded_byte": round(lane_ops / raw_bytes, 2),
-           "peak_is": "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; under this load the clock reads 2.0 GHz",
+           "peak_is": f"256 CUs x 4 SIMDs x 64 lanes / {cpi} cycles an instruction (this kernel's mix of 2- and 4-cycle "
+                      "instructions) x 2.4 GHz; under this load the clock reads 2.0 GHz",
            "source": f"profiles/counters.json [{key}]"}
     if "lds_idx_active" in c and "lds_bank_conflict" in c:
         out["lds_cycles_lost_to_bank_conflicts"] = round(c["lds_bank_conflict"] / c["lds_idx_active"], 3)
@@ -512,19 +520,13 @@ def run_config5(torch, dc, synth, counters):
                               "within_1e-2_of_fp64": g_ok, "max_normwise_error": float(f"{g_err:.3e}")}}
     # the product is bound by the vector ALU, not by HBM: lane-operations issued (counter reading kept under
     # profiles/) over the chip's lane-operations per second
-    c = counters.get("dc_decode_kernel<256,gemv>|config5_layer", {})
     g = res["whole_layer_call"]["gemv"]
-    if "valu_insts" in c:
-        lane_ops = c["valu_insts"] * 64
-        g["roofline_alu"] = {"bound": "alu", "achieved": round(lane_ops / (g["ms"] * 1e-3) / 1e12, 2),
-                             "peak": round(ALU_PEAK_LANE_OPS / 1e12, 2), "unit": "T lane-ops/s",
-                             "frac": round(lane_ops / (g["ms"] * 1e-3) / ALU_PEAK_LANE_OPS, 4),
-                             "lane_ops_per_weight": round(lane_ops / raw13, 2),
-                             "source": "profiles/counters.json (SQ_INSTS_VALU x 64 lanes)"}
-        g["gemv_alu_frac"] = g["roofline_alu"]["frac"]
-    else:
-        g["roofline_alu"] = None
-        g["gemv_alu_frac"] = None
+    g["roofline_alu"] = issue_rates(counters, "dc_decode_kernel<256,gemv>|config5_layer", raw13, g["ms"])
+    if g["roofline_alu"]:
+        g["roofline_alu"]["lane_ops_per_weight"] = g["roofline_alu"].pop("lane_ops_per_decoded_byte")
+    g["gemv_alu_frac"] = g["roofline_alu"]["frac"] if g["roofline_alu"] else None
+    d = res["whole_layer_call"]["dequant_bf16"]
+    d["issue_rates"] = issue_rates(counters, "dc_decode_kernel<256,bf16>|config5_layer", raw13, d["ms"])
     return {"workload": "config 5: fused paths on one Llama-13B-shaped layer (4 x 5120x5120, 2 x 13824x5120, 5120x13824; per-row "
                         "INT8, |q|<=1 pruned), 64 KiB chunks, 256 sub-streams, bf16 activations ~N(0,1)",
             "raw_bytes": int(raw13), "n_chunks": nc13, "compression_ratio": round(raw13 / (blob13 + 16 * nc13), 5), **res}
@@ -846,6 +848,23 @@ def compress_only(torch, dc, synth, args):
     return 0
 
 
+def issue_rates_table(torch, dc):
+    """dc_issue_rate for every instruction the library knows: time from one wavefront instruction to the next on a
+    SIMD (eight wavefronts resident), and the class it falls into, the fastest instruction's time taken as two
+    cycles.  One JSON line."""
+    sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    names = dc.issue_rate_names()
+    ns = [min(dc.issue_rate(i, sink, 1024, stream) for _ in range(3)) for i in range(len(names))]
+    fastest = min(ns)
+    rows = [{"instruction": n, "ns": round(t, 3), "cycles_if_the_fastest_takes_two": round(2 * t / fastest, 2)}
+            for n, t in zip(names, ns)]
+    print(json.dumps({"vector_alu_issue": rows, "implied_clock_GHz": round(2 / fastest, 2),
+                      "how": "32 copies of the instruction per loop turn on registers only, 1000 turns, 8 wavefronts per SIMD, "
+                             "best of 3 timed launches"}))
+    return 0
+
+
 def workgroup_timeline(torch, dc, synth):
     """One traced launch (dc_decompress_chunks_traced) of the config-2 layer per storage rule, after 60 launches without
     the record: when the workgroups of coded and of raw chunks began, how long they took, how many were resident at
@@ -933,6 +952,8 @@ def main() -> int:
                     help="only launches that mix raw and coded chunks: by share, by rule and by order, and exit")
     ap.add_argument("--compress-only", action="store_true",
                     help="only the compression on the GPU, both coders (for a profiler), and exit")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="only the issue rate of single vector-ALU instructions (dc_issue_rate), and exit")
     ap.add_argument("--wg-trace", action="store_true",
                     help="only one traced launch of the config-2 layer per storage rule: when its workgroups ran and where, and exit")
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (extras.configs)")
@@ -968,6 +989,8 @@ def main() -> int:
         return mix_sweep(torch, dc, synth)
     if args.wg_trace:
         return workgroup_timeline(torch, dc, synth)
+    if args.issue_rates:
+        return issue_rates_table(torch, dc)
     if args.compress_only:
         return compress_only(torch, dc, synth, args)
     if args.streaming_only:

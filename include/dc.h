@@ -386,6 +386,20 @@ int dc_decompress_chunks_traced(const uint8_t *blob_dev, uint64_t blob_bytes, co
                                 uint64_t *trace_dev, void *hip_stream);
 
 /*
+ * How fast a SIMD issues one vector-ALU instruction, for whoever wants to know how close a kernel's instruction mix
+ * comes to what the chip issues (the decode kernels are bound by instruction issue and the LDS, not by memory); not
+ * part of the method.  dc_issue_rate_count() instructions are known, dc_issue_rate_name(which) is the mnemonic of
+ * one (NULL beyond the count).  dc_issue_rate(which, ...) runs a chain of that instruction on values in registers
+ * with eight wavefronts resident on every SIMD, twice (the second launch is timed with events on the stream), waits
+ * for it, and writes to *ns_per_instruction_host the time from one wavefront instruction to the next on a SIMD.
+ *   sink_dev, sink_bytes   at least 1024 bytes of device memory that the kernel may overwrite, owned by the caller
+ * Returns DC_OK, DC_E_ARG or DC_E_HIP.  A blocking call; allocates nothing on the device.
+ */
+uint32_t dc_issue_rate_count(void);
+const char *dc_issue_rate_name(uint32_t which);
+int dc_issue_rate(uint32_t which, uint32_t *sink_dev, uint64_t sink_bytes, void *hip_stream, double *ns_per_instruction_host);
+
+/*
  * Decompression fused with dequantisation to bf16 (replaces the separate conversion of the
  * decompressed memory into tensors that Section 4.6 counts as overhead; dequantisation inverts Eq. 4):
  *   dst[i*cols + j] = bf16_round_nearest_even( float(q_ij) * row_scale[i] ).

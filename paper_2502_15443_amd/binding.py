@@ -126,6 +126,12 @@ def _load():
     L.dc_validate.argtypes = [vp, u64, vp, u64, pp, pu64]
     L.dc_decompress_chunks.restype = i32
     L.dc_decompress_chunks.argtypes = [vp, u64, vp, u64, pp, vp, u64, vp]
+    L.dc_issue_rate_count.restype = u32
+    L.dc_issue_rate_count.argtypes = []
+    L.dc_issue_rate_name.restype = C.c_char_p
+    L.dc_issue_rate_name.argtypes = [u32]
+    L.dc_issue_rate.restype = i32
+    L.dc_issue_rate.argtypes = [u32, vp, u64, vp, C.POINTER(C.c_double)]
     L.dc_decompress_chunks_traced.restype = i32
     L.dc_decompress_chunks_traced.argtypes = [vp, u64, vp, u64, pp, vp, u64, vp, vp]
     L.dc_decompress_dequant_bf16.restype = i32
@@ -289,6 +295,17 @@ def decompress_chunks(blob_dev, blob_bytes: int, table_dev, n_chunks: int, param
     cp = params._c()
     _check(_L.dc_decompress_chunks(_dev(blob_dev), blob_bytes, _dev(table_dev), n_chunks, C.byref(cp),
                                    _dev(dst_dev), dst_cap, stream), "dc_decompress_chunks")
+
+
+def issue_rate_names() -> list:
+    return [_L.dc_issue_rate_name(i).decode() for i in range(_L.dc_issue_rate_count())]
+
+
+def issue_rate(which: int, sink_dev, sink_bytes: int, stream: int = 0) -> float:
+    """ns from one wavefront instruction to the next on a SIMD, for instruction number `which`."""
+    ns = C.c_double(0.0)
+    _check(_L.dc_issue_rate(which, _dev(sink_dev), sink_bytes, stream, C.byref(ns)), "dc_issue_rate")
+    return ns.value
 
 
 def decompress_chunks_traced(blob_dev, blob_bytes: int, table_dev, n_chunks: int, params: Params, dst_dev,

@@ -1,0 +1,111 @@
+// Device side of libdc_mi355x: how fast the vector ALU issues single instructions (dc_issue_rate).  A measuring
+// tool for the figures that say how close the decode kernels are to the instruction issue of the chip; not part
+// of the method.  One kernel per instruction: a chain of 32 copies of it per loop turn on values that stay in
+// registers, eight wavefronts resident on every SIMD, so that what is timed is the rate at which a SIMD issues
+// the instruction, not its latency.
+#include <hip/hip_runtime.h>
+
+#include "dc.h"
+
+namespace {
+
+#define DC_REP4(x) x x x x
+#define DC_REP32(x) DC_REP4(DC_REP4(x)) DC_REP4(DC_REP4(x))
+
+// operands: %0 a, %1 d, %2 q (64 bits), %3 f, %4 b, %5 c (1..8), %6 g
+#define DC_PROBE_KERNEL(NAME, ASM)                                                                          \
+    __global__ __launch_bounds__(256) void NAME(uint32_t *sink, uint32_t seed, uint32_t turns)              \
+    {                                                                                                       \
+        uint32_t a = seed + threadIdx.x, b = seed * 3 + 1, c = (threadIdx.x & 7) + 1, d = a ^ 0x5555u;      \
+        uint64_t q = ((uint64_t)a << 32) | b;                                                               \
+        float f = (float)a, g = 1.0001f;                                                                    \
+        for (uint32_t i = 0; i < turns; i++) {                                                              \
+            DC_REP32(asm volatile(ASM : "+v"(a), "+v"(d), "+v"(q), "+v"(f) : "v"(b), "v"(c), "v"(g) : "vcc");) \
+        }                                                                                                   \
+        if (blockIdx.x == 0) sink[threadIdx.x] = a + d + (uint32_t)q + (uint32_t)(q >> 32) + (uint32_t)f;   \
+    }
+
+DC_PROBE_KERNEL(probe_and, "v_and_b32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_or, "v_or_b32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_xor, "v_xor_b32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_add, "v_add_u32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_sub, "v_sub_u32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_lshr, "v_lshrrev_b32 %0, %5, %0")
+DC_PROBE_KERNEL(probe_lshl, "v_lshlrev_b32 %0, %5, %0")
+DC_PROBE_KERNEL(probe_mov, "v_mov_b32 %0, %1")
+DC_PROBE_KERNEL(probe_min, "v_min_u32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_alignbit, "v_alignbit_b32 %0, %1, %0, %5")
+DC_PROBE_KERNEL(probe_bfe, "v_bfe_u32 %0, %0, %5, 11")
+DC_PROBE_KERNEL(probe_perm, "v_perm_b32 %0, %0, %1, %4")
+DC_PROBE_KERNEL(probe_add3, "v_add3_u32 %0, %0, %4, %5")
+DC_PROBE_KERNEL(probe_lshl_add, "v_lshl_add_u32 %0, %0, 1, %4")
+DC_PROBE_KERNEL(probe_and_or, "v_and_or_b32 %0, %0, %4, %5")
+DC_PROBE_KERNEL(probe_lshl_or, "v_lshl_or_b32 %0, %0, 1, %4")
+DC_PROBE_KERNEL(probe_mul_u24, "v_mul_u32_u24 %0, %0, %4")
+DC_PROBE_KERNEL(probe_mad_u24, "v_mad_u32_u24 %0, %0, %4, %5")
+DC_PROBE_KERNEL(probe_lshr_b64, "v_lshrrev_b64 %2, %5, %2")
+DC_PROBE_KERNEL(probe_lshl_b64, "v_lshlrev_b64 %2, %5, %2")
+DC_PROBE_KERNEL(probe_sub_sdwa, "v_sub_u32_sdwa %0, %0, %4 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0")
+DC_PROBE_KERNEL(probe_cmp, "v_cmp_lt_u32 vcc, %0, %4")
+DC_PROBE_KERNEL(probe_mbcnt, "v_mbcnt_lo_u32_b32 %0, %4, %0")
+DC_PROBE_KERNEL(probe_mov_dpp, "v_mov_b32_dpp %0, %1 row_shr:1 row_mask:0xf bank_mask:0xf")
+DC_PROBE_KERNEL(probe_mul_f32, "v_mul_f32 %3, %3, %6")
+DC_PROBE_KERNEL(probe_add_f32, "v_add_f32 %3, %3, %6")
+DC_PROBE_KERNEL(probe_fma_f32, "v_fma_f32 %3, %3, %6, %6")
+DC_PROBE_KERNEL(probe_cvt_f32_i32, "v_cvt_f32_i32 %3, %0")
+DC_PROBE_KERNEL(probe_cvt_pk_bf16, "v_cvt_pk_bf16_f32 %0, %3, %6")
+
+typedef void (*probe_kernel)(uint32_t *, uint32_t, uint32_t);
+struct Probe {
+    const char *name;
+    probe_kernel kernel;
+};
+const Probe kProbes[] = {
+    {"v_and_b32", probe_and},           {"v_or_b32", probe_or},           {"v_xor_b32", probe_xor},
+    {"v_add_u32", probe_add},           {"v_sub_u32", probe_sub},         {"v_lshrrev_b32", probe_lshr},
+    {"v_lshlrev_b32", probe_lshl},      {"v_mov_b32", probe_mov},         {"v_min_u32", probe_min},
+    {"v_alignbit_b32", probe_alignbit}, {"v_bfe_u32", probe_bfe},         {"v_perm_b32", probe_perm},
+    {"v_add3_u32", probe_add3},         {"v_lshl_add_u32", probe_lshl_add}, {"v_and_or_b32", probe_and_or},
+    {"v_lshl_or_b32", probe_lshl_or},   {"v_mul_u32_u24", probe_mul_u24}, {"v_mad_u32_u24", probe_mad_u24},
+    {"v_lshrrev_b64", probe_lshr_b64},  {"v_lshlrev_b64", probe_lshl_b64}, {"v_sub_u32_sdwa", probe_sub_sdwa},
+    {"v_cmp_lt_u32", probe_cmp},        {"v_mbcnt_lo_u32_b32", probe_mbcnt}, {"v_mov_b32_dpp", probe_mov_dpp},
+    {"v_mul_f32", probe_mul_f32},       {"v_add_f32", probe_add_f32},     {"v_fma_f32", probe_fma_f32},
+    {"v_cvt_f32_i32", probe_cvt_f32_i32}, {"v_cvt_pk_bf16_f32", probe_cvt_pk_bf16},
+};
+constexpr uint32_t kProbeCount = sizeof(kProbes) / sizeof(kProbes[0]);
+constexpr uint32_t kTurns = 1000, kPerTurn = 32, kWavesPerSimd = 8;
+
+} // namespace
+
+extern "C" uint32_t dc_issue_rate_count() { return kProbeCount; }
+
+extern "C" const char *dc_issue_rate_name(uint32_t which) { return which < kProbeCount ? kProbes[which].name : nullptr; }
+
+extern "C" int dc_issue_rate(uint32_t which, uint32_t *sink_dev, uint64_t sink_bytes, void *hip_stream, double *ns_per_instruction)
+{
+    if (which >= kProbeCount || !sink_dev || sink_bytes < 1024 || !ns_per_instruction) return DC_E_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int device = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&device) != hipSuccess || hipGetDeviceProperties(&prop, device) != hipSuccess) return DC_E_HIP;
+    // eight workgroups of four wavefronts on every compute unit: eight wavefronts on every SIMD
+    const uint32_t blocks = (uint32_t)prop.multiProcessorCount * kWavesPerSimd;
+    hipEvent_t t0, t1;
+    if (hipEventCreate(&t0) != hipSuccess) return DC_E_HIP;
+    if (hipEventCreate(&t1) != hipSuccess) {
+        (void)hipEventDestroy(t0);
+        return DC_E_HIP;
+    }
+    int rc = DC_OK;
+    float ms = 0.0f;
+    hipLaunchKernelGGL(kProbes[which].kernel, dim3(blocks), dim3(256), 0, stream, sink_dev, 1u, kTurns); // untimed
+    if (hipEventRecord(t0, stream) != hipSuccess) rc = DC_E_HIP;
+    hipLaunchKernelGGL(kProbes[which].kernel, dim3(blocks), dim3(256), 0, stream, sink_dev, 2u, kTurns);
+    if (hipEventRecord(t1, stream) != hipSuccess || hipEventSynchronize(t1) != hipSuccess ||
+        hipEventElapsedTime(&ms, t0, t1) != hipSuccess || hipGetLastError() != hipSuccess)
+        rc = DC_E_HIP;
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (rc == DC_OK) *ns_per_instruction = (double)ms * 1e6 / ((double)kWavesPerSimd * kTurns * kPerTurn);
+    return rc;
+}

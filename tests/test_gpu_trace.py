@@ -65,3 +65,21 @@ def test_traced_launch_is_for_huffman_at_256_sub_streams(env):
         with pytest.raises(dc.DCError) as e:
             dc.decompress_chunks_traced(_up(torch, blob), blob.size, _up(torch, table), len(table), p, dst, q.size, trace, 0)
         assert e.value.code == -1  # DC_E_ARG
+
+
+def test_issue_rate_probe_separates_the_two_classes_of_instruction(env):
+    """The figures behind the ALU peak of the bench line: plain 32-bit logic and addition issue about twice as fast
+    as three-operand, 64-bit, SDWA and conversion instructions."""
+    torch, dc = env
+    sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    names = dc.issue_rate_names()
+    assert len(names) == len(set(names)) >= 20
+    ns = {n: min(dc.issue_rate(i, sink, 1024, 0) for _ in range(2)) for i, n in enumerate(names)}
+    fast = [ns[n] for n in ("v_and_b32", "v_or_b32", "v_add_u32", "v_lshrrev_b32")]
+    slow = [ns[n] for n in ("v_alignbit_b32", "v_perm_b32", "v_add3_u32", "v_lshrrev_b64", "v_sub_u32_sdwa", "v_cvt_f32_i32")]
+    assert 0.5 < min(fast) and max(slow) < 5.0  # ns: two to four cycles at 1.5-2.5 GHz
+    assert max(fast) < 0.7 * min(slow)
+    with pytest.raises(dc.DCError):
+        dc.issue_rate(len(names), sink, 1024, 0)
+    with pytest.raises(dc.DCError):
+        dc.issue_rate(0, sink, 512, 0)
