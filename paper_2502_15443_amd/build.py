@@ -35,7 +35,7 @@ PACKED_FP32 = re.compile(r"\bv_pk_(add|mul|fma)_f32\b")
 # Vector-ALU instructions a SIMD issues every two cycles for a wavefront (bench.py --issue-rates measures them);
 # all others met in the kernels take four.
 TWO_CYCLE = {"v_and_b32", "v_or_b32", "v_xor_b32", "v_add_u32", "v_sub_u32", "v_subrev_u32", "v_lshrrev_b32", "v_mov_b32",
-             "v_mul_f32", "v_add_f32"}
+             "v_mul_f32", "v_add_f32", "v_cndmask_b32", "v_lshrrev_b16", "v_add_u16"}
 
 
 def loop_mix(asm_text: str) -> dict:

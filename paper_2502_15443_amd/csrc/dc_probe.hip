@@ -54,6 +54,15 @@ DC_PROBE_KERNEL(probe_add_f32, "v_add_f32 %3, %3, %6")
 DC_PROBE_KERNEL(probe_fma_f32, "v_fma_f32 %3, %3, %6, %6")
 DC_PROBE_KERNEL(probe_cvt_f32_i32, "v_cvt_f32_i32 %3, %0")
 DC_PROBE_KERNEL(probe_cvt_pk_bf16, "v_cvt_pk_bf16_f32 %0, %3, %6")
+DC_PROBE_KERNEL(probe_cvt_sdwa, "v_cvt_f32_i32_sdwa %3, sext(%0) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1")
+DC_PROBE_KERNEL(probe_cvt_ubyte, "v_cvt_f32_ubyte1 %3, %0")
+DC_PROBE_KERNEL(probe_dot2_bf16, "v_dot2_f32_bf16 %3, %0, %4, %3")
+DC_PROBE_KERNEL(probe_dot2c_bf16, "v_dot2c_f32_bf16 %3, %0, %4")
+DC_PROBE_KERNEL(probe_cmp_cndmask, "v_cmp_lt_u32 vcc, %1, %4\n\tv_cndmask_b32 %0, %0, %4, vcc")
+DC_PROBE_KERNEL(probe_max, "v_max_u32 %0, %0, %4")
+DC_PROBE_KERNEL(probe_bfi, "v_bfi_b32 %0, %4, %0, %1")
+DC_PROBE_KERNEL(probe_lshr_b16, "v_lshrrev_b16 %0, %5, %0")
+DC_PROBE_KERNEL(probe_add_u16, "v_add_u16 %0, %0, %4")
 
 typedef void (*probe_kernel)(uint32_t *, uint32_t, uint32_t);
 struct Probe {
@@ -70,7 +79,10 @@ const Probe kProbes[] = {
     {"v_lshrrev_b64", probe_lshr_b64},  {"v_lshlrev_b64", probe_lshl_b64}, {"v_sub_u32_sdwa", probe_sub_sdwa},
     {"v_cmp_lt_u32", probe_cmp},        {"v_mbcnt_lo_u32_b32", probe_mbcnt}, {"v_mov_b32_dpp", probe_mov_dpp},
     {"v_mul_f32", probe_mul_f32},       {"v_add_f32", probe_add_f32},     {"v_fma_f32", probe_fma_f32},
-    {"v_cvt_f32_i32", probe_cvt_f32_i32}, {"v_cvt_pk_bf16_f32", probe_cvt_pk_bf16},
+    {"v_cvt_f32_i32", probe_cvt_f32_i32}, {"v_cvt_pk_bf16_f32", probe_cvt_pk_bf16}, {"v_cvt_f32_i32_sdwa", probe_cvt_sdwa},
+    {"v_cvt_f32_ubyte1", probe_cvt_ubyte}, {"v_dot2_f32_bf16", probe_dot2_bf16}, {"v_dot2c_f32_bf16", probe_dot2c_bf16},
+    {"v_cmp_lt_u32 + v_cndmask_b32", probe_cmp_cndmask}, {"v_max_u32", probe_max},
+    {"v_bfi_b32", probe_bfi}, {"v_lshrrev_b16", probe_lshr_b16}, {"v_add_u16", probe_add_u16},
 };
 constexpr uint32_t kProbeCount = sizeof(kProbes) / sizeof(kProbes[0]);
 constexpr uint32_t kTurns = 1000, kPerTurn = 32, kWavesPerSimd = 8;
