@@ -457,6 +457,13 @@ __device__ __forceinline__ uint32_t bf16x2(float a, float b)
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// acc + a.lo * b.lo + a.hi * b.hi for two pairs of bf16 values
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "v"(a), "v"(b));
+    return acc;
+}
+
 // int8 value number N of a word as fp32: one v_cvt_f32_i32 whose operand selects the byte and sign-extends it
 template <int N> __device__ __forceinline__ float byte_f32(uint32_t w) { return (float)(int)(int8_t)(w >> (8 * N)); }
 
@@ -1005,10 +1012,10 @@ __global__ __launch_bounds__(Geometry<S>::kThreads) void dc_decode_kernel(Decode
                 const uint32_t xs[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    acc = __builtin_fmaf(byte_f32<0>(w[i]), bf16_bits_to_f32(xs[2 * i] & 0xFFFFu), acc);
-                    acc = __builtin_fmaf(byte_f32<1>(w[i]), __uint_as_float(xs[2 * i] & 0xFFFF0000u), acc);
-                    acc = __builtin_fmaf(byte_f32<2>(w[i]), bf16_bits_to_f32(xs[2 * i + 1] & 0xFFFFu), acc);
-                    acc = __builtin_fmaf(byte_f32<3>(w[i]), __uint_as_float(xs[2 * i + 1] & 0xFFFF0000u), acc);
+                    // an int8 value is a bf16 value exactly: two of them packed, times two values of x as they lie in
+                    // memory, in one instruction (products exact in fp32, summed in fp32)
+                    acc = dot2_bf16(bf16x2(byte_f32<0>(w[i]), byte_f32<1>(w[i])), xs[2 * i], acc);
+                    acc = dot2_bf16(bf16x2(byte_f32<2>(w[i]), byte_f32<3>(w[i])), xs[2 * i + 1], acc);
                 }
             }
             col += round_bytes;
