@@ -475,7 +475,7 @@ void write_payload(const uint8_t *src, uint32_t raw, uint32_t S, const CodeBook 
 // C ABI
 // ---------------------------------------------------------------------------------------------
 
-extern "C" const char *dc_version(void) { return "dc_mi355x 0.5 (gfx950; stored format 5: canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks, trailer)"; }
+extern "C" const char *dc_version(void) { return "dc_mi355x 0.6 (gfx950; stored format 5: canonical Huffman L11 or tANS 2048, block-interleaved sub-streams, short first blocks, trailer)"; }
 
 extern "C" int dc_blob_trailer(const uint8_t *trailer_host, dc_params *params_out)
 {
