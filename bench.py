@@ -851,15 +851,20 @@ def compress_only(torch, dc, synth, args):
 def issue_rates_table(torch, dc):
     """dc_issue_rate for every instruction the library knows: time from one wavefront instruction to the next on a
     SIMD (eight wavefronts resident), and the class it falls into, the fastest instruction's time taken as two
-    cycles.  One JSON line."""
+    cycles.  The LDS reads (names beginning with ds_) share one LDS among a compute unit's four SIMDs: their cycles
+    divided by four are LDS cycles a read.  One JSON line."""
     sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     names = dc.issue_rate_names()
     ns = [min(dc.issue_rate(i, sink, 1024, stream) for _ in range(3)) for i in range(len(names))]
     fastest = min(ns)
-    rows = [{"instruction": n, "ns": round(t, 3), "cycles_if_the_fastest_takes_two": round(2 * t / fastest, 2)}
-            for n, t in zip(names, ns)]
-    print(json.dumps({"vector_alu_issue": rows, "implied_clock_GHz": round(2 / fastest, 2),
+    rows = []
+    for n, t in zip(names, ns):
+        row = {"instruction": n, "ns": round(t, 3), "cycles_if_the_fastest_takes_two": round(2 * t / fastest, 2)}
+        if n.startswith("ds_"):
+            row["lds_cycles_a_read"] = round(2 * t / fastest / 4, 2)
+        rows.append(row)
+    print(json.dumps({"instruction_issue": rows, "implied_clock_GHz": round(2 / fastest, 2),
                       "how": "32 copies of the instruction per loop turn on registers only, 1000 turns, 8 wavefronts per SIMD, "
                              "best of 3 timed launches"}))
     return 0

@@ -389,7 +389,8 @@ int dc_decompress_chunks_traced(const uint8_t *blob_dev, uint64_t blob_bytes, co
  * How fast a SIMD issues one vector-ALU instruction, for whoever wants to know how close a kernel's instruction mix
  * comes to what the chip issues (the decode kernels are bound by instruction issue and the LDS, not by memory); not
  * part of the method.  dc_issue_rate_count() instructions are known, dc_issue_rate_name(which) is the mnemonic of
- * one (NULL beyond the count).  dc_issue_rate(which, ...) runs a chain of that instruction on values in registers
+ * one (NULL beyond the count); names that begin with ds_ are LDS reads of a 4 KiB table with the named pattern of
+ * addresses over the lanes (l), whose time is set by the one LDS that the four SIMDs of a compute unit share.  dc_issue_rate(which, ...) runs a chain of that instruction on values in registers
  * with eight wavefronts resident on every SIMD, twice (the second launch is timed with events on the stream), waits
  * for it, and writes to *ns_per_instruction_host the time from one wavefront instruction to the next on a SIMD.
  *   sink_dev, sink_bytes   at least 1024 bytes of device memory that the kernel may overwrite, owned by the caller

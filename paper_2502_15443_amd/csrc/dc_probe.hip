@@ -64,6 +64,37 @@ DC_PROBE_KERNEL(probe_bfi, "v_bfi_b32 %0, %4, %0, %1")
 DC_PROBE_KERNEL(probe_lshr_b16, "v_lshrrev_b16 %0, %5, %0")
 DC_PROBE_KERNEL(probe_add_u16, "v_add_u16 %0, %0, %4")
 
+// LDS reads: every wavefront reads a 4 KiB table (the size of the decode table) at addresses of a given pattern,
+// 32 reads a loop turn, the address of each read made to depend on the one before (by a value that is always 0).
+//   PATTERN 0: every lane the same address; 1: lane l reads 16-bit entry l (two lanes a dword); 2: dword l;
+//   3: dword 2 l; 4: dword 32 l mod 1024 (one bank if there are 32); 5: dword 64 l mod 1024; 6: a different
+//   pseudo-random 11-bit entry per lane and read (what a table look-up of the decoder is)
+template <int PATTERN, bool HALFWORD> __global__ __launch_bounds__(256) void probe_lds(uint32_t *sink, uint32_t seed, uint32_t turns)
+{
+    __shared__ uint32_t table[1024];
+    for (uint32_t i = threadIdx.x; i < 1024; i += 256) table[i] = 0;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t byte = PATTERN == 0 ? 64u : PATTERN == 1 ? 2 * lane : PATTERN == 2 ? 4 * lane : PATTERN == 3 ? 8 * lane
+                  : PATTERN == 4 ? (128 * lane) & 4095u : PATTERN == 5 ? (256 * lane) & 4095u : 0u;
+    uint32_t state = (seed + threadIdx.x + 1) * 2654435761u, sum = 0;
+    const uint32_t base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)table;
+    for (uint32_t i = 0; i < turns; i++) {
+#pragma unroll
+        for (int j = 0; j < 32; j++) {
+            if (PATTERN == 6) {
+                state = state * 1664525u + 1013904223u;
+                byte = (state >> 20) & 0xFFEu;
+            }
+            uint32_t v;
+            if (HALFWORD) v = *(const __attribute__((address_space(3))) uint16_t *)(uintptr_t)(base + (byte & ~1u) + sum);
+            else v = *(const __attribute__((address_space(3))) uint32_t *)(uintptr_t)(base + (byte & ~3u) + sum);
+            sum += v; // always 0: the next address waits for this read
+        }
+    }
+    if (blockIdx.x == 0) sink[threadIdx.x] = sum + state;
+}
+
 typedef void (*probe_kernel)(uint32_t *, uint32_t, uint32_t);
 struct Probe {
     const char *name;
@@ -83,6 +114,10 @@ const Probe kProbes[] = {
     {"v_cvt_f32_ubyte1", probe_cvt_ubyte}, {"v_dot2_f32_bf16", probe_dot2_bf16}, {"v_dot2c_f32_bf16", probe_dot2c_bf16},
     {"v_cmp_lt_u32 + v_cndmask_b32", probe_cmp_cndmask}, {"v_max_u32", probe_max},
     {"v_bfi_b32", probe_bfi}, {"v_lshrrev_b16", probe_lshr_b16}, {"v_add_u16", probe_add_u16},
+    {"ds_read_u16, one address", probe_lds<0, true>}, {"ds_read_u16, entry l", probe_lds<1, true>},
+    {"ds_read_b32, dword l", probe_lds<2, false>}, {"ds_read_b32, dword 2l", probe_lds<3, false>},
+    {"ds_read_b32, dword 32l", probe_lds<4, false>}, {"ds_read_b32, dword 64l", probe_lds<5, false>},
+    {"ds_read_u16, random entry of 2048", probe_lds<6, true>}, {"ds_read_b32, random dword of 1024", probe_lds<6, false>},
 };
 constexpr uint32_t kProbeCount = sizeof(kProbes) / sizeof(kProbes[0]);
 constexpr uint32_t kTurns = 1000, kPerTurn = 32, kWavesPerSimd = 8;
